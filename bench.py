@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed paged-attention pass on one MI355X.
+
+A step is one whole pass (KV append, decode split-K, combine, prefill tiles) over one synthetic
+batch that is already resident in HBM.  The default workload is the decode-only Llama-3-8B-like
+layer (32/8/128 bf16, 256 sequences, context U[512,4096]); `--workload` selects the others.
+Prints one JSON line with tokens/s, the roofline of the dominant kernel (duration from HIP
+events recorded on the launch stream around every launch of the timed region) and the fp64 CPU
+oracle timed on a bounded sample of the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_workload(name: str, device: str):
+    import workloads as W
+    if name == "cfg2":
+        return W.config2(device=device)
+    if name == "cfg4":
+        return W.config4(device=device)
+    if name == "cfg5":
+        return W.config5(device=device)
+    if name == "cfg3":
+        return W.config3_step(0, device=device)
+    if name == "cfg1":
+        return W.config1(device=device)
+    raise SystemExit(f"unknown workload {name}")
+
+
+def algorithmic_work(batch):
+    """Bytes / flops the method must move or do, per kernel, from the drawn lengths."""
+    import numpy as np
+    sh = batch.shape
+    Hq, Hkv, D = sh.num_q_heads, sh.num_kv_heads, sh.head_dim
+    s_kv = {"f32": 4, "bf16": 2, "fp8": 1}[sh.kv_dtype]
+    s_q = {"f32": 4, "bf16": 2}[sh.q_dtype]
+    ql = batch.q_lens.astype(np.int64)
+    cl = batch.ctx_lens.astype(np.int64)
+    pre = cl - ql
+    dec = ql == 1
+    pf = ql > 1
+    pages = (cl + 15) // 16
+    dec_bytes = int((cl[dec] * 2 * Hkv * D * s_kv + Hq * D * 2 * s_q + pages[dec] * 4).sum())
+    dec_flops = int((4 * Hq * D * cl[dec]).sum())
+    pf_flops = int((4 * Hq * D * (ql[pf] * pre[pf] + ql[pf] * (ql[pf] + 1) // 2)).sum())
+    pf_bytes = int((cl[pf] * 2 * Hkv * D * s_kv + 2 * ql[pf] * Hq * D * s_q).sum())
+    app_bytes = int(ql.sum() * 2 * Hkv * D * (s_q + s_kv))
+    return dict(decode_bytes=dec_bytes, decode_flops=dec_flops, prefill_flops=pf_flops,
+                prefill_bytes=pf_bytes, append_bytes=app_bytes)
+
+
+def cpu_baseline(batch, out_gpu, max_seqs: int, row_stride: int):
+    """Times the oracle (as it stands) on a bounded sample and checks the GPU rows against it."""
+    import numpy as np
+    import oracle
+    import workloads as W
+    S = batch.num_seqs
+    step = max(1, S // max_seqs)
+    sample = list(range(0, S, step))[:max_seqs]
+    sub = W.to_cpu(W.select_sequences(batch, sample))
+    sh = sub.shape
+    args = (sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.q_dtype, sh.kv_dtype)
+    kc = oracle.new_cache(sub.num_pages, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
+    vc = oracle.new_cache(sub.num_pages, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
+    ks = None if sub.k_scale is None else oracle.raw(sub.k_scale)
+    vs = None if sub.v_scale is None else oracle.raw(sub.v_scale)
+    pre = sub.prefix_lens
+    if pre.sum():
+        oracle.kv_append(*args, oracle.raw(sub.k_prefix), oracle.raw(sub.v_prefix), kc, vc, ks, vs,
+                         sub.block_table, pre, pre, sub.num_pages)
+    q_raw = oracle.raw(sub.q)
+    kn, vn = oracle.raw(sub.k_new), oracle.raw(sub.v_new)
+    t0 = time.perf_counter()
+    oracle.kv_append(*args, kn, vn, kc, vc, ks, vs, sub.block_table, sub.q_lens, sub.ctx_lens, sub.num_pages)
+    ref = oracle.mixed_paged_attention(*args, q_raw, kc, vc, ks, vs, sub.block_table, sub.q_lens,
+                                       sub.ctx_lens, sub.sm_scale, sub.num_pages, row_stride=row_stride)
+    dt = time.perf_counter() - t0
+    done = ~np.isnan(ref[:, 0, 0])
+    n_rows = int(done.sum())
+    q_off = np.concatenate([[0], np.cumsum(batch.q_lens)])
+    got = np.concatenate([out_gpu[q_off[s]:q_off[s + 1]] for s in sample])
+    err = float(np.max(np.abs(got[done] - ref[done]))) if n_rows else 0.0
+    return dict(value=n_rows / dt, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"{n_rows} query rows ({len(sample)} of {S} sequences, every {row_stride} row(s)), "
+                       f"{dt:.1f} s of fp64 CPU work incl. their KV append",
+                max_abs_err_vs_gpu=err)
+
+
+def calibrate(nbytes: int = 2 << 30):
+    import torch
+    import paper_2512_03416_amd as ts
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    res = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = {}
+    for name, fn, moved in (("copy", lambda: ts.calib_copy(src, dst, nbytes), 2 * nbytes),
+                            ("read", lambda: ts.calib_read(src, res, nbytes), nbytes)):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        out[name + "_GBps"] = moved * 10 / (a.elapsed_time(b) * 1e-3) / 1e9
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences in the oracle sample (0 = auto)")
+    ap.add_argument("--calibrate", action="store_true", help="also time the plain copy/read kernels")
+    ap.add_argument("--split-pages", type=int, default=0)
+    ap.add_argument("--prefetch-tiles", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2512_03416_amd as ts
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    ts.load_library()
+    torch.cuda.set_device(0)
+
+    t_setup = time.perf_counter()
+    batch = build_workload(args.workload, "cuda")
+    sh = batch.shape
+    desc = ts.Desc.make(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.q_dtype, sh.kv_dtype,
+                        batch.num_pages, batch.max_pages_per_seq)
+    ctx = ts.Context(desc)
+    if args.split_pages:
+        ctx.set_option("decode_split_pages", args.split_pages)
+    if args.prefetch_tiles:
+        ctx.set_option("decode_prefetch_tiles", args.prefetch_tiles)
+    nbytes = ts.cache_bytes(desc)
+    kc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    vc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    bt = torch.from_numpy(batch.block_table).cuda()
+    pre = batch.prefix_lens
+    info = ts.plan_describe(desc, batch.q_lens, batch.ctx_lens, args.split_pages)
+    ctx.reserve(batch.total_q, batch.num_seqs, int(info.ctx_pages))
+    if int(pre.sum()):
+        ctx.kv_append(batch.k_prefix, batch.v_prefix, kc, vc, batch.k_scale, batch.v_scale, bt, pre, pre)
+    out = torch.zeros((batch.total_q, sh.num_q_heads, sh.head_dim), dtype=batch.q.dtype, device="cuda")
+    torch.cuda.synchronize()
+    log(f"[bench] workload {batch.name}: S={batch.num_seqs} T={batch.total_q} ctx_pages={info.ctx_pages} "
+        f"pool={batch.num_pages} pages, cache 2 x {nbytes / 1e9:.2f} GB, decode items {info.n_decode_items} "
+        f"(split {info.split_pages} pages), prefill tiles {info.n_prefill_tiles}, generic rows "
+        f"{info.n_generic_rows}; setup {time.perf_counter() - t_setup:.1f} s")
+
+    def step():
+        ctx.mixed_paged_attention(batch.q, batch.k_new, batch.v_new, kc, vc, batch.k_scale, batch.v_scale, bt,
+                                  batch.q_lens, batch.ctx_lens, batch.sm_scale, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # reference loop without per-kernel events
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_plain = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # timed region: HIP events on the launch stream around every kernel launch
+    ctx.set_option("kernel_timing", 1)
+    ctx.kernel_times(reset=True)
+    ctx.token_velocity(reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    vel = ctx.token_velocity(sync=True)
+    ktimes = ctx.kernel_times()
+    ctx.set_option("kernel_timing", 0)
+    ms_step = elapsed * 1e3 / args.steps
+    T = batch.total_q
+    value = T * args.steps / elapsed
+    log(f"[bench] {ms_step:.4f} ms/step with kernel events, {ms_plain:.4f} ms/step without; kernels: " +
+        ", ".join(f"{k} {v[1] * 1e3:.1f} us x{v[0]}" for k, v in ktimes.items() if v[0]))
+    log(f"[bench] token velocity counters: prefill {vel.prefill_tok_per_s:.0f} tok/s, decode "
+        f"{vel.decode_tok_per_s:.0f} tok/s over {vel.window_s:.3f} s ({vel.passes} passes)")
+
+    work = algorithmic_work(batch)
+    tot = {k: v[0] * v[1] for k, v in ktimes.items()}
+    dominant = max(("decode", "prefill", "rows"), key=lambda k: tot.get(k, 0.0))
+    dom_ms = ktimes[dominant][1]
+    if dominant == "decode":
+        ach = work["decode_bytes"] / (dom_ms * 1e-3) / 1e9
+        roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
+                    traffic=None, kernel="decode_kernel", kernel_ms=dom_ms,
+                    algorithmic_bytes=work["decode_bytes"])
+    elif dominant == "prefill":
+        ach = work["prefill_flops"] / (dom_ms * 1e-3) / 1e12
+        roof = dict(bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=ach / PEAK_BF16_TFLOPS, traffic=None, kernel="prefill_kernel", kernel_ms=dom_ms,
+                    algorithmic_flops=work["prefill_flops"])
+    else:
+        bytes_all = work["decode_bytes"] + work["prefill_bytes"]
+        ach = bytes_all / (dom_ms * 1e-3) / 1e9
+        roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
+                    traffic=None, kernel="rows_kernel", kernel_ms=dom_ms, algorithmic_bytes=bytes_all)
+
+    result = {
+        "metric": "mixed-batch tokens/s (decode+prefill) on 1 MI355X",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if sh.q_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": batch.name, "num_seqs": batch.num_seqs, "query_tokens": T,
+                   "heads": f"{sh.num_q_heads}q/{sh.num_kv_heads}kv/d{sh.head_dim}", "kv_dtype": sh.kv_dtype,
+                   "page_size": 16, "ctx_tokens": int(batch.ctx_lens.sum()), "pool_pages": batch.num_pages,
+                   "decode_split_pages": int(info.split_pages)},
+        "roofline": roof,
+        "ms_per_step_without_kernel_events": ms_plain,
+        "kernels_us": {k: round(v[1] * 1e3, 2) for k, v in ktimes.items() if v[0]},
+    }
+    if args.calibrate:
+        result["calibration"] = calibrate()
+        log(f"[bench] calibration: {result['calibration']}")
+    if not args.no_cpu_baseline:
+        out_host = out.double().cpu().numpy()
+        n = args.cpu_seqs or {"cfg2": 128, "cfg4": 40, "cfg5": 24, "cfg3": 4, "cfg1": 8}[args.workload]
+        stride = {"cfg4": 8, "cfg5": 64, "cfg3": 8}.get(args.workload, 1)
+        result["cpu_baseline"] = cpu_baseline(batch, out_host, n, stride)
+        log(f"[bench] oracle: {result['cpu_baseline']}")
+    print(json.dumps(result), flush=True)
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

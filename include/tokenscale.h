@@ -1,0 +1,204 @@
+/*
+ * tokenscale.h -- C ABI of the MI355X mixed paged-attention library.
+ *
+ * The library implements the GPU work a Convertible Decoder performs in one serving iteration
+ * (paper Sec. 3.4, Sec. 4.4): a decode batch (one query token per sequence) runs next to
+ * absorbed chunked-prefill requests (many query tokens, causal, attending to their cached
+ * prefix), in one attention pass over a paged KV cache that also stores the iteration's new
+ * K/V (Sec. 2.1: prefill builds the cache for all input tokens, each decode iteration adds the
+ * last token's entry).  Token Velocity -- tokens an instance releases per second (Sec. 3.2) --
+ * is kept per context as host-side counters.
+ *
+ * Conventions
+ *   - Pointers marked DEV are device memory of the context's GPU, HOST are host memory.
+ *     The caller owns every buffer and the stream; the library owns only its scratch.
+ *   - GPU calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and never synchronise the device, except when scratch has to grow (see
+ *     ts_reserve).  One context serves one stream at a time.
+ *   - HOST arrays are consumed before the call returns.
+ *   - Return value 0 = TS_OK, negative = error; ts_last_error() gives the text.  Everything
+ *     that can be checked from host data is checked before any launch: a failing call has no
+ *     side effect on device memory.  Page ids inside block_table are device data and are not
+ *     validated: ids outside [0,num_pages) are undefined behaviour.
+ *
+ * Batch description (shared by the GPU calls)
+ *   S = num_seqs sequences.  Sequence s brings q_lens[s] >= 0 new tokens and, once they are
+ *   appended, holds ctx_lens[s] >= q_lens[s] tokens; prefix_s = ctx_lens[s] - q_lens[s] tokens
+ *   are already cached.  New token i of sequence s has position prefix_s + i and sees keys
+ *   0 .. prefix_s + i (causal).  q_lens[s] == 1 is a decode row, > 1 a prefill chunk, 0 is
+ *   skipped.  Tokens are packed by sequence: row index = sum of q_lens of earlier sequences + i;
+ *   T = sum of q_lens.
+ *   block_table[s][j] (int32, row stride max_pages_per_seq) is the physical page holding
+ *   positions 16j .. 16j+15 of sequence s; entries past ceil(ctx_lens[s]/16) are ignored.
+ *   Two sequences must not append into the same physical page in one call.
+ *
+ * Cache layout (per cache, K and V are separate buffers of ts_cache_bytes() bytes)
+ *   tiles ordered [page][kv_head]; with x = 16 bytes / element size (4 f32, 8 bf16, 16 fp8):
+ *     K tile: element (slot, dim) at  (dim / x) * 16 * x + slot * x + dim % x
+ *     V tile: element (slot, dim) at  dim * 16 + slot
+ *   i.e. K keeps 16-byte dim-chunks of the 16 tokens together, V is stored token-fastest.
+ *   Both are the operand order of the matrix instructions that consume them, so every load of
+ *   the attention kernels is a full, aligned 16-byte (or 8-byte) vector of one tile.
+ *   fp8 caches hold OCP e4m3 (bias 7, max 448, no inf) of value / scale[kv_head], the division
+ *   in IEEE single precision, rounded to nearest-even, saturating to +-448, NaN kept.
+ */
+#ifndef TOKENSCALE_H
+#define TOKENSCALE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TS_PAGE_SIZE 16
+
+typedef struct ts_ctx ts_ctx;
+
+typedef enum { TS_F32 = 0, TS_BF16 = 1, TS_FP8_E4M3 = 2 } ts_dtype;
+
+enum {
+    TS_OK = 0,
+    TS_ERR_INVALID_ARG = -1,  /* null pointer, bad length, bad descriptor                  */
+    TS_ERR_UNSUPPORTED = -2,  /* valid but not implemented combination                     */
+    TS_ERR_HIP = -3,          /* a HIP runtime call failed (text in ts_last_error)          */
+    TS_ERR_NOMEM = -4         /* scratch allocation failed                                  */
+};
+
+/* Geometry of one attention layer; fixed for the lifetime of a context.
+ * Supported: head_dim 64 or 128; num_q_heads a multiple of num_kv_heads with a group size
+ * <= 16; page_size 16; (q_dtype, kv_dtype) in {(F32,F32), (BF16,BF16), (BF16,FP8_E4M3)}. */
+typedef struct {
+    int32_t num_q_heads, num_kv_heads, head_dim;
+    int32_t page_size;
+    int32_t q_dtype, kv_dtype;        /* ts_dtype */
+    int64_t num_pages;                /* size of the physical page pool */
+    int32_t max_pages_per_seq;        /* row stride of block_table */
+} ts_attn_desc;
+
+/* Host only.  TS_OK if the descriptor is supported, else the error code. */
+int ts_check_desc(const ts_attn_desc *desc);
+
+/* Host only.  Bytes of ONE cache buffer (K or V) for this descriptor, 0 if it is invalid. */
+int64_t ts_cache_bytes(const ts_attn_desc *desc);
+
+/* Creates a context on GPU `device` (made current for the calling thread during the call).
+ * Allocates a small initial scratch. */
+int ts_create(const ts_attn_desc *desc, int device, ts_ctx **out);
+int ts_destroy(ts_ctx *ctx);
+
+/* Pre-sizes scratch for batches of up to max_tokens query tokens, max_seqs sequences and
+ * max_ctx_pages cache pages in total over the batch (sum over sequences of ceil(ctx/16)), so
+ * that later GPU calls never allocate.  Without it scratch grows on demand, which synchronises
+ * the device once per growth. */
+int ts_reserve(ts_ctx *ctx, int64_t max_tokens, int64_t max_seqs, int64_t max_ctx_pages);
+
+/* Step a1 -- store the new K/V rows into the paged cache (Sec. 2.1).
+ *   k_new, v_new : DEV [T, Hkv, D] of q_dtype, packed by sequence
+ *   k_cache, v_cache : DEV, layout above, kv_dtype; written in place
+ *   k_scale, v_scale : DEV fp32 [Hkv], FP8 caches only (else may be NULL)
+ *   block_table : DEV int32 [S, max_pages_per_seq]
+ *   q_lens, ctx_lens : HOST int32 [S]
+ * Errors: TS_ERR_INVALID_ARG for null pointers, q_len < 0, ctx_len < q_len,
+ * ctx_len > 16 * max_pages_per_seq, num_seqs < 0. */
+int ts_kv_append(ts_ctx *ctx, void *stream,
+                 const void *k_new, const void *v_new,
+                 void *k_cache, void *v_cache,
+                 const float *k_scale, const float *v_scale,
+                 const int32_t *block_table,
+                 const int32_t *q_lens, const int32_t *ctx_lens, int num_seqs);
+
+/* Steps a1..a5 -- one pass of a Convertible Decoder iteration (Sec. 3.4, 4.4): optional
+ * append, then softmax attention for every query token of every sequence,
+ *   out[row, h, :] = sum_j w_j V_j,  w = softmax_j( sm_scale * <q[row,h,:], K_j> ),
+ * over the keys the row sees, K/V taken from the cache through KV head h / (Hq/Hkv); fp8
+ * elements are multiplied by their head's scale.
+ *   q   : DEV [T, Hq, D] q_dtype        out : DEV [T, Hq, D] q_dtype (nearest-even cast)
+ *   k_new, v_new : DEV [T, Hkv, D], or both NULL when the new tokens are already cached
+ *   sm_scale : softmax scale, <= 0 selects 1/sqrt(head_dim)
+ * Decode rows run as split-K items over the sequence's pages, prefill chunks as causal MFMA
+ * tiles; partial results are merged in a fixed order, so results are run-to-run identical.
+ * Also adds the batch's token counts to the context's velocity counters. */
+int ts_mixed_paged_attention(ts_ctx *ctx, void *stream,
+                             const void *q,
+                             const void *k_new, const void *v_new,
+                             void *k_cache, void *v_cache,
+                             const float *k_scale, const float *v_scale,
+                             const int32_t *block_table,
+                             const int32_t *q_lens, const int32_t *ctx_lens, int num_seqs,
+                             float sm_scale,
+                             void *out);
+
+/* Step a6 -- Token Velocity of this context (Sec. 3.2): tokens released per second, separately
+ * for prefill chunks (rows of sequences with q_len > 1) and decode rows (q_len == 1), over the
+ * window that started at the first pass after the last reset. */
+typedef struct {
+    double prefill_tok_per_s, decode_tok_per_s;
+    uint64_t prefill_tokens, decode_tokens;
+    uint64_t passes;
+    double window_s;
+} ts_velocity;
+
+#define TS_VELOCITY_RESET 1   /* start a new window after reporting                         */
+#define TS_VELOCITY_SYNC  2   /* wait for the last pass to finish on the GPU before reading
+                                 the clock (otherwise the call touches no GPU state)        */
+int ts_token_velocity(ts_ctx *ctx, ts_velocity *out, int flags);
+
+/* Text of the last error of this context ("" if none); valid until the next call on it.
+ * With ctx == NULL: the last error of a failed ts_create on this thread. */
+const char *ts_last_error(const ts_ctx *ctx);
+
+/* Tuning knobs (all optional).  Names:
+ *   "decode_split_pages"  pages per decode split-K item (0 = choose from the batch)
+ *   "prefill_path"        0 = MFMA tiles where supported, 1 = force the generic row kernel
+ *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave (process-wide)
+ *   "kernel_timing"       1 = record HIP events around every launch (see ts_kernel_times)
+ * Unknown names give TS_ERR_INVALID_ARG. */
+int ts_set_option(ts_ctx *ctx, const char *name, int64_t value);
+
+/* Optional per-kernel timing with HIP events recorded on the caller's stream around each launch
+ * (enable with ts_set_option(ctx, "kernel_timing", 1); costs two event records per launch).
+ * ts_kernel_times waits for the recorded events, then reports, per kernel, the number of timed
+ * launches and their mean duration in milliseconds since the last reset. */
+enum { TS_K_APPEND = 0, TS_K_DECODE = 1, TS_K_COMBINE = 2, TS_K_PREFILL = 3, TS_K_ROWS = 4, TS_K_COUNT = 5 };
+typedef struct {
+    uint64_t launches[TS_K_COUNT];
+    double mean_ms[TS_K_COUNT];
+} ts_kernel_stats;
+int ts_kernel_times(ts_ctx *ctx, ts_kernel_stats *out, int reset);
+
+/* Calibration helpers for bandwidth measurements: a plain streaming copy (dst[i] = src[i]) and a
+ * streaming read (sum into a 4-byte result) of `bytes` bytes (multiple of 16) of DEV memory,
+ * launched on `stream`.  They let a profile be scaled against a kernel of known traffic. */
+int ts_calib_copy(void *stream, const void *src, void *dst, int64_t bytes);
+int ts_calib_read(void *stream, const void *src, void *result4, int64_t bytes);
+
+/* Host only -- step a0.  Describes the work the planner makes of a batch, without touching a
+ * GPU: how many decode split items, combine rows, prefill tiles and generic rows.
+ * split_pages = 0 lets the planner choose. */
+typedef struct {
+    int64_t total_tokens, decode_tokens, prefill_tokens;
+    int32_t n_decode_items;     /* (row, page range) split-K items, each run for every KV head */
+    int32_t n_combine_rows;     /* decode rows that were split and need merging                */
+    int32_t n_prefill_tiles;    /* causal query tiles, each run for every KV head              */
+    int32_t n_generic_rows;     /* rows sent to the generic row kernel                         */
+    int32_t split_pages;        /* pages per decode item actually used                         */
+    int32_t tile_tokens;        /* query tokens per prefill tile                               */
+    int64_t partial_slots;      /* split-K partial results held in scratch                     */
+    int64_t ctx_pages;          /* sum over sequences of ceil(ctx_len/16)                      */
+} ts_plan_info;
+
+int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
+                     int num_seqs, int32_t split_pages, ts_plan_info *out);
+
+/* Host only.  Copies the decode items of the plan as int32 quintuples
+ * (row, seq, n_keys, page_begin, page_end) into items_out (capacity in items); returns the
+ * number of items, or a negative error. */
+int64_t ts_plan_decode_items(const ts_attn_desc *desc, const int32_t *q_lens,
+                             const int32_t *ctx_lens, int num_seqs, int32_t split_pages,
+                             int32_t *items_out, int64_t capacity);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOKENSCALE_H */

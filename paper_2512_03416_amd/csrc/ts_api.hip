@@ -1,0 +1,486 @@
+// C-ABI boundary: argument checks, scratch, work-list upload, kernel launches, velocity counters.
+//
+// Every GPU step of the pass runs in the kernels of this library; this file only validates,
+// plans (ts_planner.cpp), copies the small work lists to the device and launches.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "ts_internal.h"
+
+namespace ts {
+int check_desc_msg(const ts_attn_desc* d, std::string* err);
+void set_decode_nbuf(int n);
+}
+
+using namespace ts;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+constexpr int kRing = 4;
+
+struct HostSlot {
+    void* ptr = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool pending = false;
+};
+
+}  // namespace
+
+struct ts_ctx {
+    ts_attn_desc desc{};
+    int device = 0;
+    std::string err;
+    PlanOptions opt;
+    Plan plan;
+    // device scratch
+    char* d_work = nullptr;  size_t work_cap = 0;
+    float* d_part_o = nullptr; float* d_part_ml = nullptr; int64_t part_cap = 0;
+    // pinned staging ring for the work lists
+    HostSlot ring[kRing];
+    int ring_pos = 0;
+    // token velocity (Sec. 3.2)
+    std::mutex mu;
+    uint64_t prefill_tokens = 0, decode_tokens = 0, passes = 0;
+    bool window_open = false;
+    std::chrono::steady_clock::time_point t0;
+    hipEvent_t last_pass = nullptr;
+    bool have_last = false;
+    // optional per-kernel timing
+    bool timing = false;
+    struct Timed { int which; hipEvent_t a, b; };
+    std::vector<Timed> timed;          // recorded, not yet read
+    std::vector<hipEvent_t> ev_pool;   // spare events
+    uint64_t k_launches[TS_K_COUNT] = {};
+    double k_ms[TS_K_COUNT] = {};
+};
+
+namespace {
+
+int fail(ts_ctx* c, int code, const std::string& msg)
+{
+    if (c) c->err = msg;
+    return code;
+}
+
+int hip_fail(ts_ctx* c, hipError_t e, const char* what)
+{
+    return fail(c, TS_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define TS_HIP(c, call)                                              \
+    do {                                                             \
+        hipError_t e_ = (call);                                      \
+        if (e_ != hipSuccess) return hip_fail((c), e_, #call);       \
+    } while (0)
+
+struct DeviceGuard {
+    int prev = -1; bool switched = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) == hipSuccess && prev != dev) switched = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard() { if (switched) (void)hipSetDevice(prev); }
+};
+
+size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
+
+int ensure_work(ts_ctx* c, size_t bytes)
+{
+    if (bytes <= c->work_cap) return TS_OK;
+    size_t cap = std::max<size_t>(bytes * 2, 1 << 16);
+    TS_HIP(c, hipDeviceSynchronize());
+    if (c->d_work) TS_HIP(c, hipFree(c->d_work));
+    c->d_work = nullptr; c->work_cap = 0;
+    hipError_t e = hipMalloc((void**)&c->d_work, cap);
+    if (e != hipSuccess) return fail(c, TS_ERR_NOMEM, "work-list scratch allocation failed");
+    c->work_cap = cap;
+    return TS_OK;
+}
+
+int ensure_partials(ts_ctx* c, int64_t slots)
+{
+    if (slots <= c->part_cap) return TS_OK;
+    int64_t cap = std::max<int64_t>(slots * 2, 1024);
+    TS_HIP(c, hipDeviceSynchronize());
+    if (c->d_part_o) TS_HIP(c, hipFree(c->d_part_o));
+    if (c->d_part_ml) TS_HIP(c, hipFree(c->d_part_ml));
+    c->d_part_o = c->d_part_ml = nullptr; c->part_cap = 0;
+    const size_t Hq = (size_t)c->desc.num_q_heads, D = (size_t)c->desc.head_dim;
+    if (hipMalloc((void**)&c->d_part_o, (size_t)cap * Hq * D * sizeof(float)) != hipSuccess ||
+        hipMalloc((void**)&c->d_part_ml, (size_t)cap * Hq * 2 * sizeof(float)) != hipSuccess)
+        return fail(c, TS_ERR_NOMEM, "split-K partial scratch allocation failed");
+    c->part_cap = cap;
+    return TS_OK;
+}
+
+// Next pinned staging slot with at least `bytes`, free of any copy still in flight.
+int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out)
+{
+    HostSlot& s = c->ring[c->ring_pos];
+    c->ring_pos = (c->ring_pos + 1) % kRing;
+    if (s.pending) { TS_HIP(c, hipEventSynchronize(s.ev)); s.pending = false; }
+    if (!s.ev) TS_HIP(c, hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
+    if (bytes > s.cap) {
+        if (s.ptr) TS_HIP(c, hipHostFree(s.ptr));
+        s.ptr = nullptr; s.cap = 0;
+        size_t cap = std::max<size_t>(bytes * 2, 1 << 16);
+        if (hipHostMalloc(&s.ptr, cap, hipHostMallocDefault) != hipSuccess)
+            return fail(c, TS_ERR_NOMEM, "pinned staging allocation failed");
+        s.cap = cap;
+    }
+    *out = &s;
+    return TS_OK;
+}
+
+struct WorkLayout {
+    size_t seqs, dec, cmb, pf, rows, total;
+};
+
+WorkLayout layout_of(const Plan& p)
+{
+    WorkLayout w{};
+    size_t o = 0;
+    w.seqs = o; o = align16(o + p.seqs.size() * sizeof(SeqMeta));
+    w.dec = o;  o = align16(o + p.dec.size() * sizeof(DecItem));
+    w.cmb = o;  o = align16(o + p.cmb.size() * sizeof(CmbItem));
+    w.pf = o;   o = align16(o + p.pf.size() * sizeof(PfItem));
+    w.rows = o; o = align16(o + p.rows.size() * sizeof(RowItem));
+    w.total = o;
+    return w;
+}
+
+int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
+{
+    int rc = ensure_work(c, w.total);
+    if (rc != TS_OK) return rc;
+    HostSlot* slot = nullptr;
+    rc = acquire_slot(c, w.total, &slot);
+    if (rc != TS_OK) return rc;
+    const Plan& p = c->plan;
+    char* h = (char*)slot->ptr;
+    memcpy(h + w.seqs, p.seqs.data(), p.seqs.size() * sizeof(SeqMeta));
+    if (!p.dec.empty()) memcpy(h + w.dec, p.dec.data(), p.dec.size() * sizeof(DecItem));
+    if (!p.cmb.empty()) memcpy(h + w.cmb, p.cmb.data(), p.cmb.size() * sizeof(CmbItem));
+    if (!p.pf.empty()) memcpy(h + w.pf, p.pf.data(), p.pf.size() * sizeof(PfItem));
+    if (!p.rows.empty()) memcpy(h + w.rows, p.rows.data(), p.rows.size() * sizeof(RowItem));
+    TS_HIP(c, hipMemcpyAsync(c->d_work, h, w.total, hipMemcpyHostToDevice, st));
+    TS_HIP(c, hipEventRecord(slot->ev, st));
+    slot->pending = true;
+    return TS_OK;
+}
+
+hipEvent_t take_event(ts_ctx* c)
+{
+    if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Runs one launcher, bracketed by events on the launch stream when timing is on.
+template <typename F>
+int timed_launch(ts_ctx* c, int which, bool has_work, hipStream_t st, F&& launch)
+{
+    if (!c->timing || !has_work || c->timed.size() >= 65536) return launch();
+    hipEvent_t ea = take_event(c), eb = take_event(c);
+    if (!ea || !eb) return launch();
+    (void)hipEventRecord(ea, st);
+    int e = launch();
+    (void)hipEventRecord(eb, st);
+    c->timed.push_back({which, ea, eb});
+    return e;
+}
+
+int drain_timed(ts_ctx* c)
+{
+    for (auto& t : c->timed) {
+        TS_HIP(c, hipEventSynchronize(t.b));
+        float ms = 0.f;
+        TS_HIP(c, hipEventElapsedTime(&ms, t.a, t.b));
+        c->k_ms[t.which] += ms;
+        c->k_launches[t.which] += 1;
+        c->ev_pool.push_back(t.a);
+        c->ev_pool.push_back(t.b);
+    }
+    c->timed.clear();
+    return TS_OK;
+}
+
+Geometry geometry_of(const ts_attn_desc& d)
+{
+    Geometry g{};
+    g.Hq = d.num_q_heads; g.Hkv = d.num_kv_heads; g.G = d.num_q_heads / d.num_kv_heads;
+    g.D = d.head_dim; g.max_pages = d.max_pages_per_seq; g.q_dtype = d.q_dtype; g.kv_dtype = d.kv_dtype;
+    return g;
+}
+
+int check_common(ts_ctx* c, const void* k_cache, const void* v_cache, const float* k_scale,
+                 const float* v_scale, const int32_t* block_table, const int32_t* q_lens,
+                 const int32_t* ctx_lens, int num_seqs)
+{
+    if (!k_cache || !v_cache) return fail(c, TS_ERR_INVALID_ARG, "k_cache / v_cache is NULL");
+    if (c->desc.kv_dtype == TS_FP8_E4M3 && (!k_scale || !v_scale))
+        return fail(c, TS_ERR_INVALID_ARG, "fp8 cache needs k_scale and v_scale");
+    if (num_seqs > 0 && !block_table) return fail(c, TS_ERR_INVALID_ARG, "block_table is NULL");
+    std::string err;
+    int rc = validate_batch(c->desc, q_lens, ctx_lens, num_seqs, &err);
+    if (rc != TS_OK) return fail(c, rc, err);
+    return TS_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------------
+
+extern "C" const char* ts_last_error(const ts_ctx* ctx)
+{
+    return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
+{
+    g_create_error.clear();
+    if (!out) { g_create_error = "out is NULL"; return TS_ERR_INVALID_ARG; }
+    *out = nullptr;
+    int rc = check_desc_msg(desc, &g_create_error);
+    if (rc != TS_OK) return rc;
+    int n_dev = 0;
+    hipError_t e = hipGetDeviceCount(&n_dev);
+    if (e != hipSuccess || n_dev <= 0) {
+        g_create_error = std::string("no HIP device available: ") + hipGetErrorString(e);
+        return TS_ERR_HIP;
+    }
+    if (device < 0 || device >= n_dev) { g_create_error = "device index out of range"; return TS_ERR_INVALID_ARG; }
+    e = hipSetDevice(device);
+    if (e != hipSuccess) { g_create_error = std::string("hipSetDevice: ") + hipGetErrorString(e); return TS_ERR_HIP; }
+    ts_ctx* c = new (std::nothrow) ts_ctx();
+    if (!c) { g_create_error = "out of host memory"; return TS_ERR_NOMEM; }
+    c->desc = *desc;
+    c->device = device;
+    rc = ensure_work(c, 1 << 16);
+    if (rc == TS_OK) rc = ensure_partials(c, 1024);
+    if (rc == TS_OK && hipEventCreateWithFlags(&c->last_pass, hipEventDisableTiming) != hipSuccess) {
+        c->err = "hipEventCreate failed";
+        rc = TS_ERR_HIP;
+    }
+    if (rc != TS_OK) { g_create_error = c->err; ts_destroy(c); return rc; }
+    *out = c;
+    return TS_OK;
+}
+
+extern "C" int ts_destroy(ts_ctx* c)
+{
+    if (!c) return TS_ERR_INVALID_ARG;
+    DeviceGuard guard(c->device);
+    (void)hipDeviceSynchronize();
+    if (c->d_work) (void)hipFree(c->d_work);
+    if (c->d_part_o) (void)hipFree(c->d_part_o);
+    if (c->d_part_ml) (void)hipFree(c->d_part_ml);
+    for (HostSlot& s : c->ring) {
+        if (s.ptr) (void)hipHostFree(s.ptr);
+        if (s.ev) (void)hipEventDestroy(s.ev);
+    }
+    if (c->last_pass) (void)hipEventDestroy(c->last_pass);
+    for (auto& t : c->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    delete c;
+    return TS_OK;
+}
+
+extern "C" int ts_reserve(ts_ctx* c, int64_t max_tokens, int64_t max_seqs, int64_t max_ctx_pages)
+{
+    if (!c) return TS_ERR_INVALID_ARG;
+    if (max_tokens < 0 || max_seqs < 0 || max_ctx_pages < 0)
+        return fail(c, TS_ERR_INVALID_ARG, "negative size");
+    DeviceGuard guard(c->device);
+    // worst case: every token a generic row or decode row, decode items of >= 8 pages each plus one
+    // per sequence, a prefill tile per 8 tokens.
+    const size_t items = (size_t)max_ctx_pages / 8 + (size_t)max_seqs + (size_t)max_tokens;
+    const size_t bytes = ((size_t)max_seqs + 1) * sizeof(SeqMeta) + items * (sizeof(DecItem) + sizeof(CmbItem)) +
+                         (size_t)max_tokens * (sizeof(RowItem) + sizeof(PfItem)) + 256;
+    int rc = ensure_work(c, bytes);
+    if (rc != TS_OK) return rc;
+    for (int i = 0; i < kRing; ++i) {
+        HostSlot* s = nullptr;
+        rc = acquire_slot(c, bytes, &s);
+        if (rc != TS_OK) return rc;
+    }
+    return ensure_partials(c, (int64_t)(max_ctx_pages / 8 + max_seqs));
+}
+
+extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
+{
+    if (!c || !name) return TS_ERR_INVALID_ARG;
+    if (!strcmp(name, "decode_split_pages")) {
+        if (value < 0 || value > 128) return fail(c, TS_ERR_INVALID_ARG, "decode_split_pages must be 0..128");
+        c->opt.split_pages = (int32_t)value;
+        return TS_OK;
+    }
+    if (!strcmp(name, "prefill_path")) {
+        if (value != 0 && value != 1) return fail(c, TS_ERR_INVALID_ARG, "prefill_path must be 0 or 1");
+        c->opt.prefill_generic = value == 1;
+        return TS_OK;
+    }
+    if (!strcmp(name, "decode_prefetch_tiles")) {
+        if (value < 2 || value > 4) return fail(c, TS_ERR_INVALID_ARG, "decode_prefetch_tiles must be 2..4");
+        set_decode_nbuf((int)value);
+        return TS_OK;
+    }
+    if (!strcmp(name, "kernel_timing")) {
+        c->timing = value != 0;
+        return TS_OK;
+    }
+    return fail(c, TS_ERR_INVALID_ARG, std::string("unknown option: ") + name);
+}
+
+extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const void* v_new, void* k_cache,
+                            void* v_cache, const float* k_scale, const float* v_scale,
+                            const int32_t* block_table, const int32_t* q_lens, const int32_t* ctx_lens,
+                            int num_seqs)
+{
+    if (!c) return TS_ERR_INVALID_ARG;
+    c->err.clear();
+    int rc = check_common(c, k_cache, v_cache, k_scale, v_scale, block_table, q_lens, ctx_lens, num_seqs);
+    if (rc != TS_OK) return rc;
+    DeviceGuard guard(c->device);
+    PlanOptions opt = c->opt;
+    build_plan(c->desc, q_lens, ctx_lens, num_seqs, opt, &c->plan);
+    if (c->plan.info.total_tokens == 0) return TS_OK;
+    if (!k_new || !v_new) return fail(c, TS_ERR_INVALID_ARG, "k_new / v_new is NULL");
+    // only the sequence table is needed on the device
+    c->plan.dec.clear(); c->plan.cmb.clear(); c->plan.pf.clear(); c->plan.rows.clear();
+    const WorkLayout w = layout_of(c->plan);
+    hipStream_t st = (hipStream_t)stream;
+    rc = upload_plan(c, st, w);
+    if (rc != TS_OK) return rc;
+    AppendArgs a{};
+    a.geo = geometry_of(c->desc);
+    a.k_new = k_new; a.v_new = v_new; a.k_cache = k_cache; a.v_cache = v_cache;
+    a.k_scale = k_scale; a.v_scale = v_scale; a.block_table = block_table;
+    a.seqs = (const SeqMeta*)(c->d_work + w.seqs);
+    a.num_seqs = num_seqs; a.total_tokens = (int32_t)c->plan.info.total_tokens;
+    hipError_t e = (hipError_t)timed_launch(c, TS_K_APPEND, true, st, [&] { return launch_append(a, stream); });
+    if (e != hipSuccess) return hip_fail(c, e, "append launch");
+    return TS_OK;
+}
+
+extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, const void* k_new,
+                                        const void* v_new, void* k_cache, void* v_cache,
+                                        const float* k_scale, const float* v_scale,
+                                        const int32_t* block_table, const int32_t* q_lens,
+                                        const int32_t* ctx_lens, int num_seqs, float sm_scale, void* out)
+{
+    if (!c) return TS_ERR_INVALID_ARG;
+    c->err.clear();
+    int rc = check_common(c, k_cache, v_cache, k_scale, v_scale, block_table, q_lens, ctx_lens, num_seqs);
+    if (rc != TS_OK) return rc;
+    if ((k_new == nullptr) != (v_new == nullptr))
+        return fail(c, TS_ERR_INVALID_ARG, "k_new and v_new must both be given or both be NULL");
+    if (!(sm_scale == sm_scale)) return fail(c, TS_ERR_INVALID_ARG, "sm_scale is NaN");
+    DeviceGuard guard(c->device);
+    build_plan(c->desc, q_lens, ctx_lens, num_seqs, c->opt, &c->plan);
+    const Plan& p = c->plan;
+    if (p.info.total_tokens == 0) return TS_OK;
+    if (!q || !out) return fail(c, TS_ERR_INVALID_ARG, "q / out is NULL");
+    rc = ensure_partials(c, p.info.partial_slots);
+    if (rc != TS_OK) return rc;
+    const WorkLayout w = layout_of(p);
+    hipStream_t st = (hipStream_t)stream;
+    rc = upload_plan(c, st, w);
+    if (rc != TS_OK) return rc;
+
+    const Geometry geo = geometry_of(c->desc);
+    if (k_new) {
+        AppendArgs ap{};
+        ap.geo = geo;
+        ap.k_new = k_new; ap.v_new = v_new; ap.k_cache = k_cache; ap.v_cache = v_cache;
+        ap.k_scale = k_scale; ap.v_scale = v_scale; ap.block_table = block_table;
+        ap.seqs = (const SeqMeta*)(c->d_work + w.seqs);
+        ap.num_seqs = num_seqs; ap.total_tokens = (int32_t)p.info.total_tokens;
+        hipError_t e = (hipError_t)timed_launch(c, TS_K_APPEND, true, st, [&] { return launch_append(ap, stream); });
+        if (e != hipSuccess) return hip_fail(c, e, "append launch");
+    }
+    AttnArgs a{};
+    a.geo = geo;
+    a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_scale = k_scale; a.v_scale = v_scale;
+    a.block_table = block_table;
+    a.sm_scale = sm_scale > 0.0f ? sm_scale : 1.0f / sqrtf((float)c->desc.head_dim);
+    a.out = out;
+    a.dec = (const DecItem*)(c->d_work + w.dec);   a.n_dec = (int32_t)p.dec.size();
+    a.cmb = (const CmbItem*)(c->d_work + w.cmb);   a.n_cmb = (int32_t)p.cmb.size();
+    a.pf = (const PfItem*)(c->d_work + w.pf);      a.n_pf = (int32_t)p.pf.size();
+    a.rows = (const RowItem*)(c->d_work + w.rows); a.n_rows = (int32_t)p.rows.size();
+    a.part_o = c->d_part_o; a.part_ml = c->d_part_ml;
+
+    hipError_t e;
+    // decode first: the serving loop's TPOT depends on these rows (Sec. 4.5.2)
+    e = (hipError_t)timed_launch(c, TS_K_DECODE, a.n_dec > 0, st, [&] { return launch_decode(a, stream); });
+    if (e != hipSuccess) return hip_fail(c, e, "decode launch");
+    e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_cmb > 0, st, [&] { return launch_combine(a, stream); });
+    if (e != hipSuccess) return hip_fail(c, e, "combine launch");
+    e = (hipError_t)timed_launch(c, TS_K_PREFILL, a.n_pf > 0, st, [&] { return launch_prefill(a, stream); });
+    if (e != hipSuccess) return hip_fail(c, e, "prefill launch");
+    e = (hipError_t)timed_launch(c, TS_K_ROWS, a.n_rows > 0, st, [&] { return launch_rows(a, stream); });
+    if (e != hipSuccess) return hip_fail(c, e, "rows launch");
+
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        if (!c->window_open) { c->window_open = true; c->t0 = std::chrono::steady_clock::now(); }
+        c->prefill_tokens += (uint64_t)p.info.prefill_tokens;
+        c->decode_tokens += (uint64_t)p.info.decode_tokens;
+        c->passes += 1;
+        if (hipEventRecord(c->last_pass, st) == hipSuccess) c->have_last = true;
+    }
+    return TS_OK;
+}
+
+extern "C" int ts_token_velocity(ts_ctx* c, ts_velocity* out, int flags)
+{
+    if (!c || !out) return TS_ERR_INVALID_ARG;
+    if (flags & ~(TS_VELOCITY_RESET | TS_VELOCITY_SYNC)) return fail(c, TS_ERR_INVALID_ARG, "unknown flag");
+    if ((flags & TS_VELOCITY_SYNC) && c->have_last) {
+        DeviceGuard guard(c->device);
+        TS_HIP(c, hipEventSynchronize(c->last_pass));
+    }
+    std::lock_guard<std::mutex> lk(c->mu);
+    ts_velocity v{};
+    v.prefill_tokens = c->prefill_tokens;
+    v.decode_tokens = c->decode_tokens;
+    v.passes = c->passes;
+    if (c->window_open) {
+        v.window_s = std::chrono::duration<double>(std::chrono::steady_clock::now() - c->t0).count();
+        if (v.window_s > 0) {
+            v.prefill_tok_per_s = (double)v.prefill_tokens / v.window_s;
+            v.decode_tok_per_s = (double)v.decode_tokens / v.window_s;
+        }
+    }
+    *out = v;
+    if (flags & TS_VELOCITY_RESET) {
+        c->prefill_tokens = c->decode_tokens = c->passes = 0;
+        c->window_open = false;
+    }
+    return TS_OK;
+}
+
+extern "C" int ts_kernel_times(ts_ctx* c, ts_kernel_stats* out, int reset)
+{
+    if (!c || !out) return TS_ERR_INVALID_ARG;
+    DeviceGuard guard(c->device);
+    int rc = drain_timed(c);
+    if (rc != TS_OK) return rc;
+    for (int k = 0; k < TS_K_COUNT; ++k) {
+        out->launches[k] = c->k_launches[k];
+        out->mean_ms[k] = c->k_launches[k] ? c->k_ms[k] / (double)c->k_launches[k] : 0.0;
+        if (reset) { c->k_launches[k] = 0; c->k_ms[k] = 0.0; }
+    }
+    return TS_OK;
+}

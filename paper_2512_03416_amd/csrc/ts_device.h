@@ -1,0 +1,68 @@
+// Device-side helpers for the gfx950 kernels: vector types, element conversion, tile addressing.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+#include "ts_internal.h"
+
+namespace ts {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// bf16 bits <-> float
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+
+// round-to-nearest-even float -> bf16 bits (NaN kept quiet)
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// OCP e4m3 (bias 7, max 448, S.1111.111 = NaN, no inf) -> float, from the format definition.
+__device__ __forceinline__ float e4m3_bits_to_float(uint32_t b)
+{
+    uint32_t mag = b & 0x7fu;
+    // exponent/mantissa moved into fp32 position give value * 2^-120; subnormals come out
+    // right because the product below is exact.
+    float v = __uint_as_float(mag << 20) * 0x1p120f;
+    if (mag == 0x7fu) v = __uint_as_float(0x7fc00000u);
+    return (b & 0x80u) ? -v : v;
+}
+
+// float -> e4m3 bits: nearest-even, saturating to +-448 (inf too), NaN -> S.1111.111
+__device__ __forceinline__ uint32_t float_to_e4m3_bits(float y)
+{
+    uint32_t u = __float_as_uint(y);
+    uint32_t sign = (u >> 24) & 0x80u;
+    uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u) return sign | 0x7fu;
+    if (a >= 0x43e00000u) return sign | 0x7eu;             // |y| >= 448
+    if (a < 0x3c800000u) {                                 // |y| < 2^-6: spacing 2^-9
+        float q = __builtin_rintf(__uint_as_float(a) * 512.0f);
+        return sign | (uint32_t)(int)q;                    // q == 8 is the first normal code
+    }
+    uint32_t r = (a + 0x7ffffu + ((a >> 20) & 1u)) >> 20;  // keep 3 mantissa bits, ties to even
+    return sign | (r - (120u << 3));                       // rebias 127 -> 7
+}
+
+// ---- cache tile addressing (element offsets inside one cache buffer) ---------------------------
+// tiles ordered [page][kv_head]; K tile [D/x][16][x], V tile [D][16]; x = 16 bytes / element size.
+
+template <int ES> struct chunk_elems { static constexpr int value = 16 / ES; };
+
+__device__ __forceinline__ int64_t tile_elem_base(int64_t page, int Hkv, int g, int D)
+{
+    return (page * Hkv + g) * (int64_t)(kPage * D);
+}
+
+}  // namespace ts

@@ -1,0 +1,126 @@
+// Internal declarations shared by the host API, the planner and the kernel launchers.
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "tokenscale.h"
+
+namespace ts {
+
+constexpr int kPage = TS_PAGE_SIZE;
+
+// ---- work items (host planner -> device work list) ------------------------------------------
+
+struct SeqMeta {          // one per sequence, plus a sentinel with q_off = T
+    int32_t q_off;        // row index of the sequence's first new token
+    int32_t q_len;
+    int32_t ctx_len;
+    int32_t prefix;       // ctx_len - q_len
+};
+
+struct DecItem {          // one split of one decode row; launched once per KV head
+    int32_t row;          // query row in q / out
+    int32_t seq;
+    int32_t n_keys;       // keys the row sees
+    int32_t page_begin;   // [page_begin, page_end) of the sequence's page list
+    int32_t page_end;
+    int32_t part;         // partial slot, or -1 when the row has a single split
+    int32_t pad0, pad1;
+};
+
+struct CmbItem {          // a decode row whose splits must be merged
+    int32_t row;
+    int32_t part_begin;
+    int32_t n_split;
+    int32_t pad;
+};
+
+struct PfItem {           // a causal tile of a prefill chunk; launched once per KV head
+    int32_t seq;
+    int32_t row0;         // row of the chunk's first token
+    int32_t q_len;
+    int32_t prefix;
+    int32_t tok_begin;    // tile covers chunk tokens [tok_begin, tok_begin + tok_count)
+    int32_t tok_count;
+    int32_t ctx_len;
+    int32_t pad;
+};
+
+struct RowItem {          // one query row for the generic kernel
+    int32_t row;
+    int32_t seq;
+    int32_t n_keys;
+    int32_t pad;
+};
+
+struct Plan {
+    std::vector<SeqMeta> seqs;       // S + 1
+    std::vector<DecItem> dec;
+    std::vector<CmbItem> cmb;
+    std::vector<PfItem> pf;
+    std::vector<RowItem> rows;
+    ts_plan_info info{};
+};
+
+struct PlanOptions {
+    int32_t split_pages = 0;    // 0 = auto
+    bool generic_only = false;  // every row through the generic kernel
+    bool prefill_generic = false;
+    int32_t tile_tokens = 0;    // query tokens per prefill tile
+};
+
+// Which kernels serve a descriptor.
+bool desc_uses_mfma(const ts_attn_desc& d);
+int32_t prefill_tile_tokens(const ts_attn_desc& d);
+
+// Validates lengths; returns TS_OK or an error and fills err.
+int validate_batch(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx_lens,
+                   int num_seqs, std::string* err);
+
+// Builds the work lists (validate_batch must have passed).
+void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx_lens, int num_seqs,
+                const PlanOptions& opt, Plan* plan);
+
+// ---- device-side parameter blocks -------------------------------------------------------------
+
+struct Geometry {
+    int32_t Hq, Hkv, G, D;
+    int32_t max_pages;         // block_table row stride
+    int32_t q_dtype, kv_dtype;
+};
+
+struct AppendArgs {
+    Geometry geo;
+    const void* k_new; const void* v_new;
+    void* k_cache; void* v_cache;
+    const float* k_scale; const float* v_scale;
+    const int32_t* block_table;
+    const SeqMeta* seqs; int32_t num_seqs; int32_t total_tokens;
+};
+
+struct AttnArgs {
+    Geometry geo;
+    const void* q;
+    const void* k_cache; const void* v_cache;
+    const float* k_scale; const float* v_scale;
+    const int32_t* block_table;
+    float sm_scale;
+    void* out;
+    // work lists
+    const DecItem* dec; int32_t n_dec;
+    const CmbItem* cmb; int32_t n_cmb;
+    const PfItem* pf;   int32_t n_pf;
+    const RowItem* rows; int32_t n_rows;
+    // split-K partials: o [slot][Hq][D] fp32 (unnormalised), ml [slot][Hq][2] = (max, sum) in log2 units
+    float* part_o; float* part_ml;
+};
+
+// Launchers (defined in the .hip files).  All return a hipError_t cast to int.
+int launch_append(const AppendArgs& a, void* stream);
+int launch_rows(const AttnArgs& a, void* stream);
+int launch_decode(const AttnArgs& a, void* stream);
+int launch_combine(const AttnArgs& a, void* stream);
+int launch_prefill(const AttnArgs& a, void* stream);
+
+}  // namespace ts

@@ -1,0 +1,225 @@
+// Host work planner (step a0): turns the per-sequence lengths of one iteration's batch into the
+// device work lists.  Pure host code, no GPU calls.
+//
+// The batch is the one a Convertible Decoder forms each iteration: its decode batch plus the
+// prefill chunk(s) it absorbed, bounded by the profiled chunk size (paper Sec. 4.4).  Decode rows
+// are cut into split-K items over the sequence's page list so that an HBM-bound scan is spread
+// over all CUs; prefill chunks are cut into causal query tiles.  Items are ordered longest first
+// so that the hardware dispatcher, which hands out workgroups in order, balances the tail.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+
+#include "ts_internal.h"
+
+namespace ts {
+
+bool desc_uses_mfma(const ts_attn_desc& d)
+{
+    return d.q_dtype == TS_BF16 && d.head_dim == 128 &&
+           (d.kv_dtype == TS_BF16 || d.kv_dtype == TS_FP8_E4M3);
+}
+
+int32_t prefill_tile_tokens(const ts_attn_desc& d)
+{
+    int G = d.num_q_heads / d.num_kv_heads;
+    return 128 / G;     // 128 query rows (token, head-in-group) per tile
+}
+
+static int check_desc_impl(const ts_attn_desc* d, std::string* err)
+{
+    auto fail = [&](int code, const char* msg) { if (err) *err = msg; return code; };
+    if (!d) return fail(TS_ERR_INVALID_ARG, "descriptor is NULL");
+    if (d->page_size != kPage) return fail(TS_ERR_INVALID_ARG, "page_size must be 16");
+    if (d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->num_q_heads % d->num_kv_heads)
+        return fail(TS_ERR_INVALID_ARG, "num_q_heads must be a positive multiple of num_kv_heads");
+    if (d->num_pages <= 0 || d->max_pages_per_seq <= 0)
+        return fail(TS_ERR_INVALID_ARG, "num_pages and max_pages_per_seq must be positive");
+    if (d->num_pages * (int64_t)d->num_kv_heads >= (int64_t)1 << 31)
+        return fail(TS_ERR_INVALID_ARG, "num_pages * num_kv_heads must stay below 2^31");
+    if (d->head_dim != 64 && d->head_dim != 128)
+        return fail(TS_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (d->num_q_heads / d->num_kv_heads > 16)
+        return fail(TS_ERR_UNSUPPORTED, "more than 16 query heads per KV head");
+    bool ok = (d->q_dtype == TS_F32 && d->kv_dtype == TS_F32) ||
+              (d->q_dtype == TS_BF16 && d->kv_dtype == TS_BF16) ||
+              (d->q_dtype == TS_BF16 && d->kv_dtype == TS_FP8_E4M3);
+    if (!ok) {
+        bool known = d->q_dtype >= TS_F32 && d->q_dtype <= TS_FP8_E4M3 && d->kv_dtype >= TS_F32 &&
+                     d->kv_dtype <= TS_FP8_E4M3;
+        return fail(known ? TS_ERR_UNSUPPORTED : TS_ERR_INVALID_ARG,
+                    "dtype pair must be (f32,f32), (bf16,bf16) or (bf16,fp8_e4m3)");
+    }
+    return TS_OK;
+}
+
+int validate_batch(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx_lens,
+                   int num_seqs, std::string* err)
+{
+    char buf[160];
+    if (num_seqs < 0) { *err = "num_seqs is negative"; return TS_ERR_INVALID_ARG; }
+    if (num_seqs > 0 && (!q_lens || !ctx_lens)) {
+        *err = "q_lens / ctx_lens is NULL";
+        return TS_ERR_INVALID_ARG;
+    }
+    int64_t total = 0;
+    for (int s = 0; s < num_seqs; ++s) {
+        if (q_lens[s] < 0 || ctx_lens[s] < q_lens[s]) {
+            snprintf(buf, sizeof buf, "sequence %d: q_len %d, ctx_len %d (need 0 <= q_len <= ctx_len)",
+                     s, q_lens[s], ctx_lens[s]);
+            *err = buf;
+            return TS_ERR_INVALID_ARG;
+        }
+        if ((int64_t)ctx_lens[s] > (int64_t)kPage * d.max_pages_per_seq) {
+            snprintf(buf, sizeof buf, "sequence %d: ctx_len %d exceeds 16 * max_pages_per_seq (%d)", s,
+                     ctx_lens[s], d.max_pages_per_seq);
+            *err = buf;
+            return TS_ERR_INVALID_ARG;
+        }
+        total += q_lens[s];
+    }
+    if (total >= ((int64_t)1 << 31) / std::max(1, d.num_q_heads * d.head_dim / 64)) {
+        *err = "batch has too many query tokens";
+        return TS_ERR_INVALID_ARG;
+    }
+    return TS_OK;
+}
+
+static int32_t auto_split_pages(int64_t decode_tiles)
+{
+    // Enough items to keep every SIMD of 256 CUs busy with several waves and leave a tail to
+    // balance, but long enough that the prologue (query load, first page latency) and the
+    // partial write are amortised.
+    const int64_t want_waves = 8192;
+    int64_t L = (decode_tiles + want_waves - 1) / want_waves;
+    return (int32_t)std::min<int64_t>(128, std::max<int64_t>(8, L));
+}
+
+void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx_lens, int num_seqs,
+                const PlanOptions& opt, Plan* plan)
+{
+    Plan& p = *plan;
+    p = Plan();
+    const bool mfma = desc_uses_mfma(d) && !opt.generic_only;
+    const int Hkv = d.num_kv_heads;
+    p.seqs.resize((size_t)num_seqs + 1);
+    int32_t off = 0;
+    int64_t decode_tiles = 0;
+    for (int s = 0; s < num_seqs; ++s) {
+        p.seqs[s] = SeqMeta{off, q_lens[s], ctx_lens[s], ctx_lens[s] - q_lens[s]};
+        off += q_lens[s];
+        p.info.ctx_pages += (ctx_lens[s] + kPage - 1) / kPage;
+        if (q_lens[s] == 1) {
+            p.info.decode_tokens += 1;
+            decode_tiles += (int64_t)((ctx_lens[s] + kPage - 1) / kPage) * Hkv;
+        } else {
+            p.info.prefill_tokens += q_lens[s];
+        }
+    }
+    p.seqs[num_seqs] = SeqMeta{off, 0, 0, 0};
+    p.info.total_tokens = off;
+
+    const int32_t L = opt.split_pages > 0 ? opt.split_pages : auto_split_pages(decode_tiles);
+    const int32_t TT = opt.tile_tokens > 0 ? opt.tile_tokens : prefill_tile_tokens(d);
+    p.info.split_pages = L;
+    p.info.tile_tokens = TT;
+
+    int32_t part = 0;
+    for (int s = 0; s < num_seqs; ++s) {
+        const SeqMeta& m = p.seqs[s];
+        if (m.q_len == 0) continue;
+        const bool as_decode = mfma && m.q_len == 1;
+        const bool as_tiles = mfma && m.q_len > 1 && !opt.prefill_generic;
+        if (as_decode) {
+            int32_t n_pages = (m.ctx_len + kPage - 1) / kPage;
+            int32_t n_split = (n_pages + L - 1) / L;
+            int32_t per = (n_pages + n_split - 1) / n_split;
+            n_split = (n_pages + per - 1) / per;
+            if (n_split > 1) p.cmb.push_back(CmbItem{m.q_off, part, n_split, 0});
+            for (int32_t k = 0; k < n_split; ++k) {
+                int32_t b = k * per, e = std::min(n_pages, b + per);
+                p.dec.push_back(DecItem{m.q_off, s, m.ctx_len, b, e, n_split > 1 ? part + k : -1, 0, 0});
+            }
+            if (n_split > 1) part += n_split;
+        } else if (as_tiles) {
+            for (int32_t t0 = 0; t0 < m.q_len; t0 += TT)
+                p.pf.push_back(PfItem{s, m.q_off, m.q_len, m.prefix, t0, std::min(TT, m.q_len - t0),
+                                      m.ctx_len, 0});
+        } else {
+            for (int32_t i = 0; i < m.q_len; ++i)
+                p.rows.push_back(RowItem{m.q_off + i, s, m.prefix + i + 1, 0});
+        }
+    }
+    // longest first (stable, so equal lengths keep batch order and runs stay reproducible)
+    std::stable_sort(p.dec.begin(), p.dec.end(), [](const DecItem& a, const DecItem& b) {
+        return (a.page_end - a.page_begin) > (b.page_end - b.page_begin);
+    });
+    std::stable_sort(p.pf.begin(), p.pf.end(), [](const PfItem& a, const PfItem& b) {
+        return (a.prefix + a.tok_begin + a.tok_count) > (b.prefix + b.tok_begin + b.tok_count);
+    });
+    std::stable_sort(p.rows.begin(), p.rows.end(),
+                     [](const RowItem& a, const RowItem& b) { return a.n_keys > b.n_keys; });
+    p.info.n_decode_items = (int32_t)p.dec.size();
+    p.info.n_combine_rows = (int32_t)p.cmb.size();
+    p.info.n_prefill_tiles = (int32_t)p.pf.size();
+    p.info.n_generic_rows = (int32_t)p.rows.size();
+    p.info.partial_slots = part;
+}
+
+}  // namespace ts
+
+// ---- host-only C entry points -------------------------------------------------------------------
+
+extern "C" int ts_check_desc(const ts_attn_desc* desc)
+{
+    return ts::check_desc_impl(desc, nullptr);
+}
+
+namespace ts { int check_desc_msg(const ts_attn_desc* d, std::string* err) { return check_desc_impl(d, err); } }
+
+extern "C" int64_t ts_cache_bytes(const ts_attn_desc* d)
+{
+    if (ts::check_desc_impl(d, nullptr) != TS_OK) return 0;
+    int64_t es = d->kv_dtype == TS_F32 ? 4 : (d->kv_dtype == TS_BF16 ? 2 : 1);
+    return d->num_pages * d->num_kv_heads * ts::kPage * d->head_dim * es;
+}
+
+extern "C" int ts_plan_describe(const ts_attn_desc* desc, const int32_t* q_lens, const int32_t* ctx_lens,
+                                int num_seqs, int32_t split_pages, ts_plan_info* out)
+{
+    std::string err;
+    int rc = ts::check_desc_impl(desc, &err);
+    if (rc != TS_OK) return rc;
+    if (!out || split_pages < 0) return TS_ERR_INVALID_ARG;
+    rc = ts::validate_batch(*desc, q_lens, ctx_lens, num_seqs, &err);
+    if (rc != TS_OK) return rc;
+    ts::Plan plan;
+    ts::PlanOptions opt;
+    opt.split_pages = split_pages;
+    ts::build_plan(*desc, q_lens, ctx_lens, num_seqs, opt, &plan);
+    *out = plan.info;
+    return TS_OK;
+}
+
+extern "C" int64_t ts_plan_decode_items(const ts_attn_desc* desc, const int32_t* q_lens,
+                                        const int32_t* ctx_lens, int num_seqs, int32_t split_pages,
+                                        int32_t* items_out, int64_t capacity)
+{
+    std::string err;
+    int rc = ts::check_desc_impl(desc, &err);
+    if (rc != TS_OK) return rc;
+    if (split_pages < 0 || capacity < 0 || (capacity > 0 && !items_out)) return TS_ERR_INVALID_ARG;
+    rc = ts::validate_batch(*desc, q_lens, ctx_lens, num_seqs, &err);
+    if (rc != TS_OK) return rc;
+    ts::Plan plan;
+    ts::PlanOptions opt;
+    opt.split_pages = split_pages;
+    ts::build_plan(*desc, q_lens, ctx_lens, num_seqs, opt, &plan);
+    int64_t n = (int64_t)plan.dec.size();
+    for (int64_t i = 0; i < n && i < capacity; ++i) {
+        const ts::DecItem& it = plan.dec[(size_t)i];
+        int32_t* o = items_out + 5 * i;
+        o[0] = it.row; o[1] = it.seq; o[2] = it.n_keys; o[3] = it.page_begin; o[4] = it.page_end;
+    }
+    return n;
+}

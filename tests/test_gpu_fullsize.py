@@ -1,0 +1,60 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: the whole
+batch runs on the GPU, a seeded sample of its rows is recomputed by the oracle one by one."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _sampled_check(batch, seq_sample, row_stride, tol):
+    import gpu_harness as g
+    print(f"[case] {batch.name} full size S={batch.num_seqs} T={batch.total_q} sample={list(seq_sample)}",
+          flush=True)
+    out, _, _ = g.run_batch(batch)
+    assert np.all(np.isfinite(out))
+    q_off = np.concatenate([[0], np.cumsum(batch.q_lens)])
+    sub = W.to_cpu(W.select_sequences(batch, seq_sample))
+    sh = sub.shape
+    ref_out, _, _ = None, None, None
+    kc = oracle.new_cache(sub.num_pages, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
+    vc = oracle.new_cache(sub.num_pages, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
+    ks = None if sub.k_scale is None else oracle.raw(sub.k_scale)
+    vs = None if sub.v_scale is None else oracle.raw(sub.v_scale)
+    pre = sub.prefix_lens
+    args = (sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.q_dtype, sh.kv_dtype)
+    if pre.sum():
+        oracle.kv_append(*args, oracle.raw(sub.k_prefix), oracle.raw(sub.v_prefix), kc, vc, ks, vs,
+                         sub.block_table, pre, pre, sub.num_pages)
+    oracle.kv_append(*args, oracle.raw(sub.k_new), oracle.raw(sub.v_new), kc, vc, ks, vs, sub.block_table,
+                     sub.q_lens, sub.ctx_lens, sub.num_pages)
+    ref = oracle.mixed_paged_attention(*args, oracle.raw(sub.q), kc, vc, ks, vs, sub.block_table, sub.q_lens,
+                                       sub.ctx_lens, sub.sm_scale, sub.num_pages, row_stride=row_stride)
+    worst, n_rows, o = 0.0, 0, 0
+    for s in seq_sample:
+        ql = int(batch.q_lens[s])
+        got = out[q_off[s]:q_off[s] + ql]
+        want = ref[o:o + ql]
+        sel = ~np.isnan(want[:, 0, 0])
+        worst = max(worst, float(np.max(np.abs(got[sel] - want[sel]))))
+        n_rows += int(sel.sum())
+        o += ql
+    print(f"       {n_rows} sampled rows, max abs err {worst:.3e} (bar {tol})", flush=True)
+    assert n_rows > 0 and worst <= tol
+
+
+def test_config2_decode_full_size_sampled():
+    b = W.config2(device="cuda")
+    assert b.num_seqs == 256 and b.shape.num_q_heads == 32
+    sample = np.random.default_rng(7).choice(256, size=12, replace=False)
+    longest, shortest = int(np.argmax(b.ctx_lens)), int(np.argmin(b.ctx_lens))
+    _sampled_check(b, sorted(set(sample.tolist() + [longest, shortest])), 1, 2e-2)
+
+
+def test_config4_burst_full_size_sampled():
+    b = W.config4(device="cuda")
+    dec = np.random.default_rng(8).choice(128, size=6, replace=False).tolist()
+    _sampled_check(b, sorted(dec) + [128, 131], 61, 2e-2)     # every 61st row of two of the chunks

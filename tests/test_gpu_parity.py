@@ -1,0 +1,268 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle on the same seeded inputs.
+
+Bars: KV append bit-exact; attention max-abs-error <= 1e-5 (fp32), 2e-2 (bf16), 6e-2 (fp8 cache,
+the oracle reading the same quantised bytes).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+from workloads import AttnShape, make_batch
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2, "fp8": 6e-2}
+
+
+def gpu():
+    import gpu_harness
+    return gpu_harness
+
+
+def check(batch, options=None, fused_append=True, tol=None, what=""):
+    print(f"[case] {batch.name} {what} shape={batch.shape} S={batch.num_seqs} T={batch.total_q} "
+          f"opts={options}", flush=True)
+    ref, rk, rv = oracle.run_batch(W.to_cpu(batch))
+    out, gk, gv = gpu().run_batch(batch, options=options, fused_append=fused_append)
+    assert np.array_equal(gk, rk), "K cache differs from the oracle's"
+    assert np.array_equal(gv, rv), "V cache differs from the oracle's"
+    assert out.shape == ref.shape
+    assert np.all(np.isfinite(out)), "non-finite output"
+    err = float(np.max(np.abs(out - ref))) if out.size else 0.0
+    bar = tol if tol is not None else TOL[batch.shape.kv_dtype]
+    print(f"       max abs err {err:.3e} (bar {bar})", flush=True)
+    assert err <= bar
+    return err
+
+
+# ---------------------------------------------------------------------------------------------
+# configuration 1 and its relatives (generic row kernel)
+# ---------------------------------------------------------------------------------------------
+
+def test_config1_tiny_fp32_mixed():
+    check(W.config1())
+
+
+@pytest.mark.parametrize("shape", [
+    AttnShape(4, 1, 64, "f32", "f32"), AttnShape(8, 2, 128, "f32", "f32"),
+    AttnShape(8, 2, 64, "bf16", "bf16"), AttnShape(8, 2, 64, "bf16", "fp8"),
+], ids=["f32-64", "f32-128", "bf16-64", "fp8-64"])
+def test_generic_rows_shapes(shape):
+    b = make_batch(shape, [1, 1, 1, 37, 64, 0, 1, 130], [1, 16, 333, 37, 112, 40, 17, 130], seed=21,
+                   pool_rule=1.4, value_mult=0.7)
+    check(b)
+
+
+# ---------------------------------------------------------------------------------------------
+# MFMA decode path (bf16 / fp8 cache, head_dim 128)
+# ---------------------------------------------------------------------------------------------
+
+DEC_CTX = [1, 2, 15, 16, 17, 31, 33, 64, 100, 255, 256, 257, 600, 1000, 2049, 3000]
+
+
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+@pytest.mark.parametrize("heads", [(8, 2), (4, 4), (16, 2), (32, 2), (6, 2)], ids=lambda h: f"{h[0]}q{h[1]}kv")
+def test_decode_rows(kv, heads):
+    shape = AttnShape(heads[0], heads[1], 128, "bf16", kv)
+    b = make_batch(shape, [1] * len(DEC_CTX), DEC_CTX, seed=31, pool_rule=1.3, value_mult=0.5)
+    check(b)
+
+
+@pytest.mark.parametrize("split", [8, 9, 64, 128])
+@pytest.mark.parametrize("nbuf", [2, 3, 4])
+def test_decode_split_and_prefetch_variants(split, nbuf):
+    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+    b = make_batch(shape, [1] * len(DEC_CTX), DEC_CTX, seed=32, pool_rule=1.3, value_mult=0.5)
+    check(b, options={"decode_split_pages": split, "decode_prefetch_tiles": nbuf})
+
+
+def test_decode_large_scores_and_shifting_maximum():
+    # keys grow along the sequence so the running maximum keeps rising across pages and splits
+    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+    b = make_batch(shape, [1, 1], [700, 90], seed=33, value_mult=1.0, sm_scale=1.0)
+    ramp = torch.linspace(0.05, 1.5, 699).view(-1, 1, 1)
+    b.k_prefix[:699] = (b.k_prefix[:699].float() * ramp).to(torch.bfloat16)
+    check(b, options={"decode_split_pages": 8, "decode_prefetch_tiles": 3})
+
+
+# ---------------------------------------------------------------------------------------------
+# MFMA prefill path
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+@pytest.mark.parametrize("heads", [(8, 2), (4, 4), (16, 2), (32, 2), (6, 2)], ids=lambda h: f"{h[0]}q{h[1]}kv")
+def test_prefill_chunks(kv, heads):
+    shape = AttnShape(heads[0], heads[1], 128, "bf16", kv)
+    q = [37, 64, 2, 130, 300, 17]
+    pre = [0, 48, 0, 5, 200, 63]
+    b = make_batch(shape, q, [a + c for a, c in zip(q, pre)], seed=41, pool_rule=1.3, value_mult=0.5)
+    check(b)
+
+
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+def test_mixed_batch_one_pass(kv):
+    shape = AttnShape(32, 8, 128, "bf16", kv)
+    q = [1, 1, 200, 1, 0, 77, 1, 1, 512, 1]
+    c = [40, 1500, 260, 16, 9, 77, 4097, 333, 700, 1]
+    b = make_batch(shape, q, c, seed=42, pool_rule=1.25, value_mult=0.5)
+    e1 = check(b)
+    # appended beforehand (k_new = NULL) gives the same result as the fused pass
+    b2 = make_batch(shape, q, c, seed=42, pool_rule=1.25, value_mult=0.5)
+    e2 = check(b2, fused_append=False, what="pre-appended")
+    assert e1 == e2
+
+
+def test_prefill_generic_path_agrees():
+    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+    b = make_batch(shape, [150, 1], [190, 50], seed=43, value_mult=0.5)
+    check(b, options={"prefill_path": 1})
+
+
+# ---------------------------------------------------------------------------------------------
+# append and fp8 codec
+# ---------------------------------------------------------------------------------------------
+
+def test_fp8_append_exhaustive_bf16_inputs():
+    """All 65536 bf16 bit patterns through ts_kv_append (4 kv heads = 4 scales), bit-exact."""
+    shape = AttnShape(4, 4, 128, "bf16", "fp8")
+    n = 65536 // (4 * 128)                                       # tokens so that K holds every pattern once
+    b = make_batch(shape, [n], [n], seed=51)
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    allv = bits.view(torch.bfloat16).view(n, 4, 128)
+    # every head sees every pattern: rotate the assignment over 4 passes
+    for rot in range(4):
+        b.k_new = torch.roll(allv, rot, dims=1).contiguous()
+        b.v_new = torch.roll(allv, rot + 1, dims=1).contiguous()
+        b.k_scale = torch.tensor([1.0, 0.0078125, 0.0123, 3.7])
+        b.v_scale = torch.tensor([1.0 / 448.0, 2.5, 0.3, 1e-3])
+        b.name = f"fp8_exhaustive_rot{rot}"
+        print(f"[case] {b.name}", flush=True)
+        kc = oracle.new_cache(b.num_pages, 4, 128, "fp8")
+        vc = oracle.new_cache(b.num_pages, 4, 128, "fp8")
+        oracle.kv_append(4, 4, 128, "bf16", "fp8", oracle.raw(b.k_new), oracle.raw(b.v_new), kc, vc,
+                         oracle.raw(b.k_scale), oracle.raw(b.v_scale), b.block_table, b.q_lens, b.ctx_lens,
+                         b.num_pages)
+        import paper_2512_03416_amd as ts
+        g = gpu()
+        b = g.to_dev(b)
+        ctx = ts.Context(g.make_desc(b))
+        gk, gv = g.new_caches(b)
+        bt = torch.from_numpy(b.block_table).cuda()
+        ctx.kv_append(b.k_new, b.v_new, gk, gv, b.k_scale, b.v_scale, bt, b.q_lens, b.ctx_lens)
+        torch.cuda.synchronize()
+        assert np.array_equal(g.cache_raw(gk, "fp8"), kc)
+        assert np.array_equal(g.cache_raw(gv, "fp8"), vc)
+        ctx.close()
+        W.to_cpu(b)
+
+
+@pytest.mark.parametrize("q_len", [1, 3])
+def test_fp8_every_code_dequantises_exactly(q_len):
+    """A row that sees one key returns that key's value: run every finite e4m3 code through V."""
+    shape = AttnShape(2, 2, 128, "bf16", "fp8")
+    codes = [c for c in range(256) if (c & 0x7F) != 0x7F]
+    vals = torch.tensor([oracle.e4m3_to_double(c) for c in codes], dtype=torch.float32)   # exact in bf16
+    vals = torch.cat([vals, vals[:2]])                                                   # 256 values
+    S = 2
+    b = make_batch(shape, [q_len] * S, [q_len] * S, seed=52)
+    b.k_scale = torch.tensor([1.0, 0.5])
+    b.v_scale = torch.tensor([1.0, 0.25])
+    for s in range(S):
+        row = s * q_len                                      # first row of each sequence sees one key
+        b.v_new[row, 0] = vals[:128].to(torch.bfloat16)
+        b.v_new[row, 1] = (vals[128:] * 0.25).to(torch.bfloat16)
+        b.k_new[row, 0] = vals[128:].to(torch.bfloat16)      # K goes through every code as well
+        b.k_new[row, 1] = (vals[:128] * 0.5).to(torch.bfloat16)
+    check(b, tol=0.0 if q_len == 1 else None, what="single-key rows")
+
+
+def test_append_only_entry_point_bit_exact():
+    import paper_2512_03416_amd as ts
+    g = gpu()
+    for shape in (AttnShape(4, 1, 64, "f32", "f32"), AttnShape(8, 2, 128, "bf16", "bf16"),
+                  AttnShape(8, 2, 128, "bf16", "fp8")):
+        b = make_batch(shape, [1, 37, 64, 3, 0, 500], [70, 37, 112, 16, 5, 777], seed=53, pool_rule=1.7)
+        print(f"[case] append_only {shape}", flush=True)
+        _, rk, rv = oracle.run_batch(b)
+        b = g.to_dev(b)
+        ctx = ts.Context(g.make_desc(b))
+        gk, gv = g.new_caches(b)
+        bt = torch.from_numpy(b.block_table).cuda()
+        pre = b.prefix_lens
+        ctx.kv_append(b.k_prefix, b.v_prefix, gk, gv, b.k_scale, b.v_scale, bt, pre, pre)
+        ctx.kv_append(b.k_new, b.v_new, gk, gv, b.k_scale, b.v_scale, bt, b.q_lens, b.ctx_lens)
+        torch.cuda.synchronize()
+        assert np.array_equal(g.cache_raw(gk, shape.kv_dtype), rk)
+        assert np.array_equal(g.cache_raw(gv, shape.kv_dtype), rv)
+        ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# boundary behaviour on the GPU
+# ---------------------------------------------------------------------------------------------
+
+def test_errors_have_no_side_effects_and_empty_batches_are_fine():
+    import paper_2512_03416_amd as ts
+    from paper_2512_03416_amd import binding
+    g = gpu()
+    b = g.to_dev(make_batch(AttnShape(8, 2, 128, "bf16", "bf16"), [1, 5], [20, 30], seed=61))
+    ctx = ts.Context(g.make_desc(b))
+    kc, vc = g.new_caches(b)
+    bt = torch.from_numpy(b.block_table).cuda()
+    out = torch.zeros_like(b.q)
+    before = kc.clone()
+    for ql, cl in (([1, 31], [20, 30]), ([-1, 5], [20, 30]), ([1, 5], [20, 16 * b.max_pages_per_seq + 1])):
+        with pytest.raises(ts.TokenScaleError) as e:
+            ctx.mixed_paged_attention(b.q, b.k_new, b.v_new, kc, vc, None, None, bt, ql, cl, 0.0, out)
+        assert e.value.code == binding.TS_ERR_INVALID_ARG and ctx.last_error()
+    with pytest.raises(ts.TokenScaleError):
+        ctx.mixed_paged_attention(b.q, b.k_new, None, kc, vc, None, None, bt, b.q_lens, b.ctx_lens, 0.0, out)
+    with pytest.raises(ts.TokenScaleError):
+        ctx.set_option("no_such_option", 1)
+    torch.cuda.synchronize()
+    assert torch.equal(kc, before) and float(out.float().abs().sum()) == 0.0
+    # empty batches
+    ctx.mixed_paged_attention(b.q, b.k_new, b.v_new, kc, vc, None, None, bt, [], [], 0.0, out)
+    ctx.mixed_paged_attention(b.q, b.k_new, b.v_new, kc, vc, None, None, bt, [0, 0], [3, 0], 0.0, out)
+    ctx.kv_append(b.k_new, b.v_new, kc, vc, None, None, bt, [0, 0], [3, 0])
+    torch.cuda.synchronize()
+    assert torch.equal(kc, before)
+    ctx.close()
+
+
+def test_run_to_run_identical_and_default_scale():
+    g = gpu()
+    shape = AttnShape(32, 8, 128, "bf16", "bf16")
+    mk = lambda: make_batch(shape, [1, 1, 300, 1], [3000, 555, 420, 64], seed=62, value_mult=0.5)
+    o1, k1, _ = g.run_batch(mk(), options={"decode_split_pages": 8})
+    o2, k2, _ = g.run_batch(mk(), options={"decode_split_pages": 8})
+    assert np.array_equal(o1, o2) and np.array_equal(k1, k2)
+    b = mk()
+    b.sm_scale = 0.0                       # <= 0 selects 1/sqrt(D)
+    o3, _, _ = g.run_batch(b, options={"decode_split_pages": 8})
+    assert np.array_equal(o1, o3)
+
+
+def test_token_velocity_counters():
+    import time
+    import paper_2512_03416_amd as ts
+    g = gpu()
+    b = g.to_dev(make_batch(AttnShape(8, 2, 128, "bf16", "bf16"), [1, 1, 40, 1, 7], [20, 30, 40, 5, 9], seed=63))
+    ctx = ts.Context(g.make_desc(b))
+    kc, vc = g.new_caches(b)
+    bt = torch.from_numpy(b.block_table).cuda()
+    out = torch.zeros_like(b.q)
+    v0 = ctx.token_velocity()
+    assert v0.passes == 0 and v0.window_s == 0.0 and v0.decode_tok_per_s == 0.0
+    for _ in range(3):
+        ctx.mixed_paged_attention(b.q, b.k_new, b.v_new, kc, vc, None, None, bt, b.q_lens, b.ctx_lens, 0.0, out)
+    time.sleep(0.05)
+    v = ctx.token_velocity(reset=True, sync=True)
+    assert (v.passes, v.decode_tokens, v.prefill_tokens) == (3, 9, 141)
+    assert v.window_s >= 0.05
+    assert abs(v.decode_tok_per_s - 9 / v.window_s) < 1e-6 * v.decode_tok_per_s + 1e-9
+    assert abs(v.prefill_tok_per_s - 141 / v.window_s) < 1e-6 * v.prefill_tok_per_s + 1e-9
+    assert ctx.token_velocity().passes == 0
+    ctx.close()

@@ -1,0 +1,109 @@
+"""CPU-only checks of the boundary: exported symbols, descriptor/batch validation, planner."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2512_03416_amd as ts
+from paper_2512_03416_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "tokenscale.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ts_[a-z_0-9]+)\s*\(", hdr))
+    assert {"ts_kv_append", "ts_mixed_paged_attention", "ts_token_velocity"} <= declared
+    lib = ctypes.CDLL(ts.library_path())
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(binding.EXPORTS)
+
+
+def D(**kw):
+    base = dict(Hq=32, Hkv=8, D=128, q_dtype="bf16", kv_dtype="bf16", num_pages=1000, max_pages_per_seq=64)
+    base.update(kw)
+    return ts.Desc.make(**base)
+
+
+def test_check_desc_accepts_and_rejects():
+    assert ts.check_desc(D()) == 0
+    assert ts.check_desc(D(q_dtype="f32", kv_dtype="f32", D=64, Hq=4, Hkv=1)) == 0
+    assert ts.check_desc(D(kv_dtype="fp8", Hq=64)) == 0
+    assert ts.check_desc(D(page_size=32)) == binding.TS_ERR_INVALID_ARG
+    assert ts.check_desc(D(Hq=30)) == binding.TS_ERR_INVALID_ARG
+    assert ts.check_desc(D(num_pages=0)) == binding.TS_ERR_INVALID_ARG
+    assert ts.check_desc(D(D=96)) == binding.TS_ERR_UNSUPPORTED
+    assert ts.check_desc(D(q_dtype="f32", kv_dtype="bf16")) == binding.TS_ERR_UNSUPPORTED
+    assert ts.check_desc(D(q_dtype=7)) == binding.TS_ERR_INVALID_ARG
+    assert ts.check_desc(D(Hq=8 * 17)) == binding.TS_ERR_UNSUPPORTED
+
+
+def test_cache_bytes():
+    assert ts.cache_bytes(D()) == 1000 * 8 * 16 * 128 * 2
+    assert ts.cache_bytes(D(kv_dtype="fp8")) == 1000 * 8 * 16 * 128
+    assert ts.cache_bytes(D(q_dtype="f32", kv_dtype="f32", D=64)) == 1000 * 8 * 16 * 64 * 4
+    assert ts.cache_bytes(D(D=96)) == 0
+
+
+@pytest.mark.parametrize("ql,cl", [([-1], [4]), ([5], [4]), ([1], [64 * 16 + 1])])
+def test_plan_rejects_bad_lengths(ql, cl):
+    with pytest.raises(ts.TokenScaleError) as e:
+        ts.plan_describe(D(), ql, cl)
+    assert e.value.code == binding.TS_ERR_INVALID_ARG
+
+
+def test_plan_counts_and_decode_items_cover_every_page_once():
+    rng = np.random.default_rng(5)
+    ctx = rng.integers(1, 1024, size=40)
+    ql = np.ones(40, dtype=np.int32)
+    ql[::7] = 0
+    ql[3] = 37
+    ctx[3] = 112
+    ql[9] = 300
+    ctx[9] = 300
+    for split in (0, 8, 13, 128):
+        info = ts.plan_describe(D(), ql, ctx, split)
+        n_dec = int((ql == 1).sum())
+        assert info.total_tokens == ql.sum() and info.decode_tokens == n_dec
+        assert info.prefill_tokens == 337
+        assert info.n_generic_rows == 0
+        assert info.tile_tokens == 32
+        assert info.n_prefill_tiles == -(-37 // 32) + -(-300 // 32)
+        items = ts.plan_decode_items(D(), ql, ctx, split)
+        assert len(items) == info.n_decode_items
+        cover = {}
+        for row, seq, n_keys, pb, pe in items:
+            assert ql[seq] == 1 and n_keys == ctx[seq] and 0 <= pb < pe <= -(-n_keys // 16)
+            assert pe - pb <= max(info.split_pages, 1) and pe - pb <= 128
+            assert row == ql[:seq].sum()
+            cover.setdefault(seq, []).extend(range(pb, pe))
+        assert set(cover) == {s for s in range(40) if ql[s] == 1}
+        for seq, pages in cover.items():
+            assert sorted(pages) == list(range(-(-ctx[seq] // 16)))
+        lens = items[:, 4] - items[:, 3]
+        assert np.all(np.diff(lens) <= 0)                 # longest first
+        n_split_rows = sum(1 for s in cover if len([1 for it in items if it[1] == s]) > 1)
+        assert info.n_combine_rows == n_split_rows
+        assert info.partial_slots == sum(len([1 for it in items if it[1] == s]) for s in cover
+                                         if len([1 for it in items if it[1] == s]) > 1)
+
+
+def test_plan_routes_fp32_and_head_dim_64_to_generic_rows():
+    d = D(q_dtype="f32", kv_dtype="f32", D=64, Hq=4, Hkv=1)
+    info = ts.plan_describe(d, [1, 37, 64], [5, 37, 112])
+    assert info.n_generic_rows == 102 and info.n_decode_items == 0 and info.n_prefill_tiles == 0
+    info = ts.plan_describe(D(D=64), [1, 4], [5, 4])
+    assert info.n_generic_rows == 5
+
+
+def test_create_without_gpu_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(ts.TokenScaleError) as e:
+        ts.Context(D())
+    assert e.value.code == binding.TS_ERR_HIP

@@ -243,3 +243,34 @@ def config5(seed: int = 4, device: str = "cpu", n_decode: int = 512, n_chunks: i
     ctx = list(dec) + [chunk] * n_chunks
     return make_batch(shape, q_lens, ctx, seed=seed, pool_rule=1.25, value_mult=1.0, device=device,
                       name="cfg5_70b_fp8kv")
+
+
+def select_sequences(batch: Batch, idx: Sequence[int], seed: int = 0) -> Batch:
+    """The sub-batch made of the given sequences (same logical tensors, a fresh page table of its
+    own).  Pure data plumbing: lets a bounded sample of a large batch be handed to another consumer."""
+    idx = [int(i) for i in idx]
+    pre = batch.prefix_lens
+    q_off = np.concatenate([[0], np.cumsum(batch.q_lens)])
+    p_off = np.concatenate([[0], np.cumsum(pre)])
+
+    def take(t, off):
+        parts = [t[int(off[i]):int(off[i + 1])] for i in idx]
+        return torch.cat(parts).contiguous() if parts else t[:0]
+
+    q_lens = batch.q_lens[idx]
+    ctx = batch.ctx_lens[idx]
+    need = int(sum(pages_for(c) for c in ctx))
+    rng = np.random.default_rng(seed)
+    bt = deal_block_table(ctx, max(need, 1), rng)
+    return Batch(batch.shape, q_lens.astype(np.int32), ctx.astype(np.int32), bt, max(need, 1),
+                 take(batch.q, q_off), take(batch.k_new, q_off), take(batch.v_new, q_off),
+                 take(batch.k_prefix, p_off), take(batch.v_prefix, p_off), batch.k_scale, batch.v_scale,
+                 batch.sm_scale, batch.name + "_sample")
+
+
+def to_cpu(batch: Batch) -> Batch:
+    for name in ("q", "k_new", "v_new", "k_prefix", "v_prefix", "k_scale", "v_scale"):
+        t = getattr(batch, name)
+        if t is not None:
+            setattr(batch, name, t.cpu())
+    return batch
