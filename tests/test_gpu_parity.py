@@ -21,13 +21,18 @@ def gpu():
     return gpu_harness
 
 
+def same_bytes(a, b):
+    """Bit-exact comparison (the 0xFF poison is a NaN in every element type)."""
+    return np.array_equal(np.ascontiguousarray(a).view(np.uint8), np.ascontiguousarray(b).view(np.uint8))
+
+
 def check(batch, options=None, fused_append=True, tol=None, what=""):
     print(f"[case] {batch.name} {what} shape={batch.shape} S={batch.num_seqs} T={batch.total_q} "
           f"opts={options}", flush=True)
     ref, rk, rv = oracle.run_batch(W.to_cpu(batch))
     out, gk, gv = gpu().run_batch(batch, options=options, fused_append=fused_append)
-    assert np.array_equal(gk, rk), "K cache differs from the oracle's"
-    assert np.array_equal(gv, rv), "V cache differs from the oracle's"
+    assert same_bytes(gk, rk), "K cache differs from the oracle's"
+    assert same_bytes(gv, rv), "V cache differs from the oracle's"
     assert out.shape == ref.shape
     assert np.all(np.isfinite(out)), "non-finite output"
     err = float(np.max(np.abs(out - ref))) if out.size else 0.0
@@ -152,21 +157,22 @@ def test_fp8_append_exhaustive_bf16_inputs():
         bt = torch.from_numpy(b.block_table).cuda()
         ctx.kv_append(b.k_new, b.v_new, gk, gv, b.k_scale, b.v_scale, bt, b.q_lens, b.ctx_lens)
         torch.cuda.synchronize()
-        assert np.array_equal(g.cache_raw(gk, "fp8"), kc)
-        assert np.array_equal(g.cache_raw(gv, "fp8"), vc)
+        assert same_bytes(g.cache_raw(gk, "fp8"), kc)
+        assert same_bytes(g.cache_raw(gv, "fp8"), vc)
         ctx.close()
         W.to_cpu(b)
 
 
 @pytest.mark.parametrize("q_len", [1, 3])
 def test_fp8_every_code_dequantises_exactly(q_len):
-    """A row that sees one key returns that key's value: run every finite e4m3 code through V."""
+    """A row that sees one key returns that key's value: run every finite e4m3 code through K and V,
+    through the decode kernel (q_len 1) and the prefill kernel (first row of a chunk)."""
     shape = AttnShape(2, 2, 128, "bf16", "fp8")
     codes = [c for c in range(256) if (c & 0x7F) != 0x7F]
     vals = torch.tensor([oracle.e4m3_to_double(c) for c in codes], dtype=torch.float32)   # exact in bf16
     vals = torch.cat([vals, vals[:2]])                                                   # 256 values
     S = 2
-    b = make_batch(shape, [q_len] * S, [q_len] * S, seed=52)
+    b = make_batch(shape, [q_len] * S, [q_len] * S, seed=52, value_mult=0.05)
     b.k_scale = torch.tensor([1.0, 0.5])
     b.v_scale = torch.tensor([1.0, 0.25])
     for s in range(S):
@@ -175,7 +181,14 @@ def test_fp8_every_code_dequantises_exactly(q_len):
         b.v_new[row, 1] = (vals[128:] * 0.25).to(torch.bfloat16)
         b.k_new[row, 0] = vals[128:].to(torch.bfloat16)      # K goes through every code as well
         b.k_new[row, 1] = (vals[:128] * 0.5).to(torch.bfloat16)
-    check(b, tol=0.0 if q_len == 1 else None, what="single-key rows")
+    print(f"[case] fp8 single-key rows q_len={q_len}", flush=True)
+    ref, rk, rv = oracle.run_batch(W.to_cpu(b))
+    out, gk, gv = gpu().run_batch(b)
+    assert same_bytes(gk, rk) and same_bytes(gv, rv)
+    first = [s * q_len for s in range(S)]
+    assert np.array_equal(out[first], ref[first])            # weight 1 on one key: exact
+    rel = np.abs(out - ref) / np.maximum(1.0, np.abs(ref))
+    assert float(rel.max()) <= 6e-2
 
 
 def test_append_only_entry_point_bit_exact():
@@ -194,8 +207,8 @@ def test_append_only_entry_point_bit_exact():
         ctx.kv_append(b.k_prefix, b.v_prefix, gk, gv, b.k_scale, b.v_scale, bt, pre, pre)
         ctx.kv_append(b.k_new, b.v_new, gk, gv, b.k_scale, b.v_scale, bt, b.q_lens, b.ctx_lens)
         torch.cuda.synchronize()
-        assert np.array_equal(g.cache_raw(gk, shape.kv_dtype), rk)
-        assert np.array_equal(g.cache_raw(gv, shape.kv_dtype), rv)
+        assert same_bytes(g.cache_raw(gk, shape.kv_dtype), rk)
+        assert same_bytes(g.cache_raw(gv, shape.kv_dtype), rv)
         ctx.close()
 
 

@@ -39,7 +39,8 @@ def _sampled_check(batch, seq_sample, row_stride, tol):
         got = out[q_off[s]:q_off[s] + ql]
         want = ref[o:o + ql]
         sel = ~np.isnan(want[:, 0, 0])
-        worst = max(worst, float(np.max(np.abs(got[sel] - want[sel]))))
+        if sel.any():
+            worst = max(worst, float(np.max(np.abs(got[sel] - want[sel]))))
         n_rows += int(sel.sum())
         o += ql
     print(f"       {n_rows} sampled rows, max abs err {worst:.3e} (bar {tol})", flush=True)
@@ -57,4 +58,4 @@ def test_config2_decode_full_size_sampled():
 def test_config4_burst_full_size_sampled():
     b = W.config4(device="cuda")
     dec = np.random.default_rng(8).choice(128, size=6, replace=False).tolist()
-    _sampled_check(b, sorted(dec) + [128, 131], 61, 2e-2)     # every 61st row of two of the chunks
+    _sampled_check(b, sorted(dec) + [128, 131], 7, 2e-2)      # every 7th row of the sample, two chunks included
