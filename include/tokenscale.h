@@ -149,7 +149,7 @@ int ts_token_velocity(ts_ctx *ctx, ts_velocity *out, int flags);
 const char *ts_last_error(const ts_ctx *ctx);
 
 /* Tuning knobs (all optional).  Names:
- *   "decode_split_pages"  pages per decode split-K item (0 = choose from the batch)
+ *   "decode_split_pages"  longest page range of one decode item (0 = choose from the batch)
  *   "prefill_path"        0 = MFMA tiles where supported, 1 = force the generic row kernel
  *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave (process-wide)
  *   "kernel_timing"       1 = record HIP events around every launch (see ts_kernel_times)

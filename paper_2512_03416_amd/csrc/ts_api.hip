@@ -321,7 +321,7 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
 {
     if (!c || !name) return TS_ERR_INVALID_ARG;
     if (!strcmp(name, "decode_split_pages")) {
-        if (value < 0 || value > 128) return fail(c, TS_ERR_INVALID_ARG, "decode_split_pages must be 0..128");
+        if (value < 0 || value > (1 << 20)) return fail(c, TS_ERR_INVALID_ARG, "decode_split_pages out of range");
         c->opt.split_pages = (int32_t)value;
         return TS_OK;
     }
@@ -387,6 +387,10 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
         return fail(c, TS_ERR_INVALID_ARG, "k_new and v_new must both be given or both be NULL");
     if (!(sm_scale == sm_scale)) return fail(c, TS_ERR_INVALID_ARG, "sm_scale is NaN");
     DeviceGuard guard(c->device);
+    if (desc_uses_mfma(c->desc)) {
+        const int slots = decode_resident_workgroups(c->desc.kv_dtype);
+        if (slots > 0) c->opt.wg_slots = slots;
+    }
     build_plan(c->desc, q_lens, ctx_lens, num_seqs, c->opt, &c->plan);
     const Plan& p = c->plan;
     if (p.info.total_tokens == 0) return TS_OK;

@@ -17,6 +17,19 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr float kLog2e = 1.4426950408889634f;
 
+// Read-only work lists and page tables are read through the constant address space: a load from
+// a wave-uniform address then goes through the scalar cache (its own counter, out of order with
+// respect to the vector-memory queue) even in kernels that also store to global memory.
+#define TS_CONSTANT __attribute__((address_space(4)))
+template <typename T>
+__device__ __forceinline__ const T TS_CONSTANT* as_constant(const T* p)
+{
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+    return (const T TS_CONSTANT*)p;
+#pragma clang diagnostic pop
+}
+
 // bf16 bits <-> float
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
 

@@ -65,6 +65,7 @@ struct Plan {
 
 struct PlanOptions {
     int32_t split_pages = 0;    // 0 = auto
+    int32_t wg_slots = 768;     // decode workgroups resident at once (256 CUs x 3)
     bool generic_only = false;  // every row through the generic kernel
     bool prefill_generic = false;
     int32_t tile_tokens = 0;    // query tokens per prefill tile
@@ -121,6 +122,7 @@ int launch_append(const AppendArgs& a, void* stream);
 int launch_rows(const AttnArgs& a, void* stream);
 int launch_decode(const AttnArgs& a, void* stream);
 int launch_combine(const AttnArgs& a, void* stream);
+int decode_resident_workgroups(int kv_dtype);   // on the current device, 0 if unknown
 int launch_prefill(const AttnArgs& a, void* stream);
 
 }  // namespace ts

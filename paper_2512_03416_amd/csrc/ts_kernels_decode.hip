@@ -4,8 +4,9 @@
 // the scan is bound by HBM bandwidth (the paper's "memory-intensive decode" whose spare compute
 // lets a decoder absorb prefill work, Sec. 1, Sec. 3.4).  The kernel is therefore built around
 // the loads:
-//   - one wavefront owns one item = (decode row, KV head, range of <= 128 pages); no LDS, no
-//     barriers, so many independent waves per CU keep loads in flight;
+//   - one workgroup of 4 wavefronts owns one item = (decode row, KV head, page range), the waves
+//     taking every 4th page; they share nothing until the end of the item, so many independent
+//     waves per CU keep loads in flight;
 //   - every (page, KV head) tile is one contiguous 4 KB (bf16) / 2 KB (fp8) block; each load
 //     instruction of the wave reads a contiguous 1 KB (K) or 512 B / 256 B (V) run of it, already
 //     in matrix-operand order, straight into registers;
@@ -99,104 +100,153 @@ template <typename KT> __device__ __forceinline__ int q_dim0(int b, int r)
     else return 16 * (4 * (b >> 1) + r) + 8 * (b & 1);
 }
 
+// One workgroup of kDecWaves waves per item = (decode row, KV head, page range).  Wave w streams the
+// pages begin+w, begin+w+kDecWaves, ... so the waves read neighbouring tiles at the same time; at
+// the end their (max, sum, O) states meet in LDS and wave 0 merges them in wave order.  A row that
+// fits one item is finished here (no partial ever goes to HBM: stores into the middle of a saturated
+// read stream were measured to cost ~10x their byte share); only rows longer than one workgroup's
+// fair share are cut into several items whose partials go through combine_kernel.
+constexpr int kDecWaves = 4;
+
+struct DecMerge {                          // LDS image of the non-leading waves' state
+    float o[kDecWaves - 1][8][64][4];      // acc[b] of every lane
+    float m[kDecWaves - 1][16];
+    float l[kDecWaves - 1][16];
+};
+
 template <typename KT, int NBUF>
-__global__ __launch_bounds__(64) void decode_kernel(AttnArgs a)
+__global__ __launch_bounds__(64 * kDecWaves) void decode_kernel(AttnArgs a)
 {
     constexpr int D = 128, KB = 4, DB = 8;
-    const DecItem it = a.dec[blockIdx.x];
-    const int g = blockIdx.y;
-    const int lane = threadIdx.x, r = lane >> 4, n = lane & 15;
+    __shared__ DecMerge mg;
+    // KV heads vary fastest over the grid: the Hkv workgroups of one item start together and read
+    // the Hkv adjacent tiles of each page (one contiguous run of the cache) at about the same time
+    const int g = blockIdx.x % a.geo.Hkv;
+    const int32_t TS_CONSTANT* itp = as_constant((const int32_t*)(a.dec + blockIdx.x / a.geo.Hkv));
+    const int it_row = itp[0], it_seq = itp[1], it_keys = itp[2], it_pb = itp[3], it_pe = itp[4], it_part = itp[5];
+    // (readfirstlane tells the compiler the wave index is uniform, which keeps everything derived
+    // from it -- the page-id loads above all -- on the scalar unit)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, r = lane >> 4, n = lane & 15;
     const int Hq = a.geo.Hq, Hkv = a.geo.Hkv, G = a.geo.G;
 
-    // Q^T operand: column n is query head g*G + n; columns >= G repeat the group's last head
-    // (their results are finite and never stored)
-    bf16x8 qb[KB];
-    {
-        const uint16_t* qrow = (const uint16_t*)a.q + ((int64_t)it.row * Hq + g * G + min(n, G - 1)) * D;
-#pragma unroll
-        for (int b = 0; b < KB; ++b) qb[b] = as_bf16x8(*(const uint4*)(qrow + q_dim0<KT>(b, r)));
-    }
-    const float kscale = (sizeof(KT) == 1) ? a.k_scale[g] : 1.0f;
-    const float c = a.sm_scale * kscale * kLog2e;
-
-    // page ids of this item: lane j holds the id of the item's page j (and j + 64)
-    const int np = it.page_end - it.page_begin;
-    const int32_t* bt = a.block_table + (int64_t)it.seq * a.geo.max_pages + it.page_begin;
-    const int ids0 = bt[min(lane, np - 1)];
-    const int ids1 = bt[min(lane + 64, np - 1)];
-    auto tile_of = [&](int pi) -> int64_t {
-        pi = min(pi, np - 1);
-        const int id = (pi < 64) ? __builtin_amdgcn_readlane(ids0, pi) : __builtin_amdgcn_readlane(ids1, pi - 64);
-        return (int64_t)id * Hkv + g;
-    };
-
-    const char* kc = (const char*)a.k_cache;
-    const char* vc = (const char*)a.v_cache;
-    KVTile<KT> buf[NBUF];
-#pragma unroll
-    for (int j = 0; j < NBUF; ++j) load_tile(buf[j], kc, vc, tile_of(j), lane);
+    // this wave's pages: it_pb + wave + kDecWaves * k, k = 0 .. np-1
+    const int np = max(0, (it_pe - it_pb - wave + kDecWaves - 1) / kDecWaves);
+    const int32_t TS_CONSTANT* bt = as_constant(a.block_table) + (int64_t)it_seq * a.geo.max_pages + it_pb + wave;
 
     f32x4 acc[DB];
 #pragma unroll
     for (int b = 0; b < DB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_ref = -INFINITY, l = 0.0f;
 
-    for (int base = 0; base < np; base += NBUF) {
+    if (np > 0) {                                                 // wave-uniform
+        // Q^T operand: column n is query head g*G + n; columns >= G repeat the group's last head
+        // (their results are finite and never stored)
+        bf16x8 qb[KB];
+        {
+            const uint16_t* qrow = (const uint16_t*)a.q + ((int64_t)it_row * Hq + g * G + min(n, G - 1)) * D;
 #pragma unroll
-        for (int j = 0; j < NBUF; ++j) {
-            const int pi = base + j;
-            if (pi < np) {                                        // wave-uniform
-                const KVTile<KT>& t = buf[j];
-                f32x4 s = qk_tile(t, qb);
-                float t0 = s[0] * c, t1 = s[1] * c, t2 = s[2] * c, t3 = s[3] * c;
-                const int tok0 = (it.page_begin + pi) * kPage + 4 * r;
-                const int nvalid = it.n_keys - tok0;              // tokens tok0 .. tok0+3 valid if < nvalid
-                const bool tail = (it.page_begin + pi + 1) * kPage > it.n_keys;   // wave-uniform
-                if (tail) {
-                    t0 = nvalid > 0 ? t0 : -INFINITY; t1 = nvalid > 1 ? t1 : -INFINITY;
-                    t2 = nvalid > 2 ? t2 : -INFINITY; t3 = nvalid > 3 ? t3 : -INFINITY;
-                }
-                const float lmax = fmaxf(fmaxf(t0, t1), fmaxf(t2, t3));
-                if (__any(lmax > m_ref + kRaise)) {               // raise the reference (rare)
-                    float full = fmaxf(lmax, __shfl_xor(lmax, 16, 64));
-                    full = fmaxf(full, __shfl_xor(full, 32, 64));
-                    const float m_new = fmaxf(m_ref, full);
-                    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);     // exp2(-inf) = 0 on the first page
+            for (int b = 0; b < KB; ++b) qb[b] = as_bf16x8(*(const uint4*)(qrow + q_dim0<KT>(b, r)));
+        }
+        const float kscale = (sizeof(KT) == 1) ? a.k_scale[g] : 1.0f;
+        const float c = a.sm_scale * kscale * kLog2e;
+        const char* kc = (const char*)a.k_cache;
+        const char* vc = (const char*)a.v_cache;
+
+        // page ids come through the scalar cache, one fetch ahead of their use
+        int next_k = 0;
+        int next_id = bt[0];
+        auto fetch = [&](KVTile<KT>& t) {
+            load_tile(t, kc, vc, (int64_t)next_id * Hkv + g, lane);
+            next_k = min(next_k + 1, np - 1);                     // past the end: stay on the last page
+            next_id = bt[kDecWaves * next_k];
+        };
+        KVTile<KT> buf[NBUF];
 #pragma unroll
-                    for (int b = 0; b < DB; ++b) acc[b] *= alpha;
-                    l *= alpha;
-                    m_ref = m_new;
-                }
-                const float p0 = __builtin_amdgcn_exp2f(t0 - m_ref), p1 = __builtin_amdgcn_exp2f(t1 - m_ref);
-                const float p2 = __builtin_amdgcn_exp2f(t2 - m_ref), p3 = __builtin_amdgcn_exp2f(t3 - m_ref);
-                l += (p0 + p1) + (p2 + p3);
-                const bf16x2 pa = __builtin_convertvector(f32x2{p0, p1}, bf16x2);
-                const bf16x2 pb = __builtin_convertvector(f32x2{p2, p3}, bf16x2);
-                uint2 pw;
-                pw.x = __builtin_bit_cast(uint32_t, pa);
-                pw.y = __builtin_bit_cast(uint32_t, pb);
-                const s16x4 pv = as_s16x4(pw);
-                uint64_t keep = ~0ull;                            // zero V of slots past n_keys (poison)
-                if (tail) keep = nvalid >= 4 ? ~0ull : (nvalid <= 0 ? 0ull : ((1ull << (16 * nvalid)) - 1ull));
+        for (int j = 0; j < NBUF; ++j) fetch(buf[j]);
+
+        for (int base = 0; base < np; base += NBUF) {
 #pragma unroll
-                for (int b = 0; b < DB; ++b) {
-                    uint2 vv = v_operand(t, b);
-                    if (tail) { vv.x &= (uint32_t)keep; vv.y &= (uint32_t)(keep >> 32); }
-                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(as_s16x4(vv), pv, acc[b], 0, 0, 0);
+            for (int j = 0; j < NBUF; ++j) {
+                const int k = base + j;
+                if (k < np) {                                     // wave-uniform
+                    const KVTile<KT>& t = buf[j];
+                    const int page = it_pb + wave + kDecWaves * k;
+                    f32x4 s = qk_tile(t, qb);
+                    float t0 = s[0] * c, t1 = s[1] * c, t2 = s[2] * c, t3 = s[3] * c;
+                    const int nvalid = it_keys - (page * kPage + 4 * r);   // tokens tok0 .. tok0+3 valid if < nvalid
+                    const bool tail = (page + 1) * kPage > it_keys;        // wave-uniform
+                    if (tail) {
+                        t0 = nvalid > 0 ? t0 : -INFINITY; t1 = nvalid > 1 ? t1 : -INFINITY;
+                        t2 = nvalid > 2 ? t2 : -INFINITY; t3 = nvalid > 3 ? t3 : -INFINITY;
+                    }
+                    const float lmax = fmaxf(fmaxf(t0, t1), fmaxf(t2, t3));
+                    if (__any(lmax > m_ref + kRaise)) {           // raise the reference (rare)
+                        float full = fmaxf(lmax, __shfl_xor(lmax, 16, 64));
+                        full = fmaxf(full, __shfl_xor(full, 32, 64));
+                        const float m_new = fmaxf(m_ref, full);
+                        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // 0 on the first page
+#pragma unroll
+                        for (int b = 0; b < DB; ++b) acc[b] *= alpha;
+                        l *= alpha;
+                        m_ref = m_new;
+                    }
+                    const float p0 = __builtin_amdgcn_exp2f(t0 - m_ref), p1 = __builtin_amdgcn_exp2f(t1 - m_ref);
+                    const float p2 = __builtin_amdgcn_exp2f(t2 - m_ref), p3 = __builtin_amdgcn_exp2f(t3 - m_ref);
+                    l += (p0 + p1) + (p2 + p3);
+                    uint2 pw;
+                    pw.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p0, p1}, bf16x2));
+                    pw.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p2, p3}, bf16x2));
+                    const s16x4 pv = as_s16x4(pw);
+                    uint64_t keep = ~0ull;                        // zero V of slots past n_keys (poison)
+                    if (tail) keep = nvalid >= 4 ? ~0ull : (nvalid <= 0 ? 0ull : ((1ull << (16 * nvalid)) - 1ull));
+#pragma unroll
+                    for (int b = 0; b < DB; ++b) {
+                        uint2 vv = v_operand(t, b);
+                        if (tail) { vv.x &= (uint32_t)keep; vv.y &= (uint32_t)(keep >> 32); }
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(as_s16x4(vv), pv, acc[b], 0, 0, 0);
+                    }
                 }
+                fetch(buf[j]);                                    // refill (clamped to the wave's last page)
             }
-            load_tile(buf[j], kc, vc, tile_of(pi + NBUF), lane);  // refill (clamped to the last page)
         }
     }
 
     float l_tot = l + __shfl_xor(l, 16, 64);
     l_tot += __shfl_xor(l_tot, 32, 64);
+
+    // ---- merge the waves' states (wave order, so the result is reproducible) ----------------------
+    if (wave > 0) {
+#pragma unroll
+        for (int b = 0; b < DB; ++b) *(f32x4*)mg.o[wave - 1][b][lane] = acc[b];
+        if (r == 0) { mg.m[wave - 1][n] = m_ref; mg.l[wave - 1][n] = l_tot; }
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    float M = m_ref;
+#pragma unroll
+    for (int w = 0; w < kDecWaves - 1; ++w) M = fmaxf(M, mg.m[w][n]);
+    // wave 0 always holds the item's first page, so M is finite
+    {
+        const float w0 = __builtin_amdgcn_exp2f(m_ref - M);
+#pragma unroll
+        for (int b = 0; b < DB; ++b) acc[b] *= w0;
+        l_tot *= w0;
+    }
+#pragma unroll
+    for (int w = 0; w < kDecWaves - 1; ++w) {
+        const float ww = __builtin_amdgcn_exp2f(mg.m[w][n] - M);  // exp2(-inf) = 0 for a wave without pages
+        l_tot += mg.l[w][n] * ww;
+#pragma unroll
+        for (int b = 0; b < DB; ++b) acc[b] += *(const f32x4*)mg.o[w][b][lane] * ww;
+    }
+
     if (n < G) {
         const int h = g * G + n;
-        if (it.part < 0) {
+        if (it_part < 0) {
             const float vscale = (sizeof(KT) == 1) ? a.v_scale[g] : 1.0f;
             const float inv = vscale / l_tot;
-            uint16_t* o = (uint16_t*)a.out + ((int64_t)it.row * Hq + h) * D + 4 * r;
+            uint16_t* o = (uint16_t*)a.out + ((int64_t)it_row * Hq + h) * D + 4 * r;
 #pragma unroll
             for (int b = 0; b < DB; ++b) {
                 const bf16x2 x = __builtin_convertvector(f32x2{acc[b][0] * inv, acc[b][1] * inv}, bf16x2);
@@ -207,12 +257,12 @@ __global__ __launch_bounds__(64) void decode_kernel(AttnArgs a)
                 *(uint2*)(o + 16 * b) = w;
             }
         } else {
-            float* o = a.part_o + ((int64_t)it.part * Hq + h) * D + 4 * r;
+            float* o = a.part_o + ((int64_t)it_part * Hq + h) * D + 4 * r;
 #pragma unroll
             for (int b = 0; b < DB; ++b) *(f32x4*)(o + 16 * b) = acc[b];
             if (r == 0) {
-                float* ml = a.part_ml + ((int64_t)it.part * Hq + h) * 2;
-                ml[0] = m_ref;
+                float* ml = a.part_ml + ((int64_t)it_part * Hq + h) * 2;
+                ml[0] = M;
                 ml[1] = l_tot;
             }
         }
@@ -239,19 +289,47 @@ __global__ __launch_bounds__(128) void combine_kernel(AttnArgs a)
     ((uint16_t*)a.out)[((int64_t)it.row * Hq + h) * D + d] = (uint16_t)float_to_bf16_bits(o * vscale / L);
 }
 
-static int g_decode_nbuf = 3;
+static int g_decode_nbuf = 2;
 void set_decode_nbuf(int n) { g_decode_nbuf = n; }
 
 template <typename KT>
 static int launch_decode_t(const AttnArgs& a, hipStream_t st)
 {
-    dim3 grid((unsigned)a.n_dec, (unsigned)a.geo.Hkv), block(64);
+    dim3 grid((unsigned)a.n_dec * (unsigned)a.geo.Hkv), block(64 * kDecWaves);
     switch (g_decode_nbuf) {
-    case 2: hipLaunchKernelGGL((decode_kernel<KT, 2>), grid, block, 0, st, a); break;
+    case 3: hipLaunchKernelGGL((decode_kernel<KT, 3>), grid, block, 0, st, a); break;
     case 4: hipLaunchKernelGGL((decode_kernel<KT, 4>), grid, block, 0, st, a); break;
-    default: hipLaunchKernelGGL((decode_kernel<KT, 3>), grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL((decode_kernel<KT, 2>), grid, block, 0, st, a); break;
     }
     return (int)hipGetLastError();
+}
+
+template <typename KT>
+static int resident_t(int nbuf)
+{
+    int per_cu = 0;
+    hipError_t e;
+    switch (nbuf) {
+    case 3: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 3>, 64 * kDecWaves, 0); break;
+    case 4: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 4>, 64 * kDecWaves, 0); break;
+    default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 2>, 64 * kDecWaves, 0); break;
+    }
+    return e == hipSuccess ? per_cu : 0;
+}
+
+int decode_resident_workgroups(int kv_dtype)
+{
+    static int cache[2][5] = {};
+    const int k = kv_dtype == TS_FP8_E4M3 ? 1 : 0;
+    int& slot = cache[k][g_decode_nbuf];
+    if (slot == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        slot = cus * (k ? resident_t<uint8_t>(g_decode_nbuf) : resident_t<uint16_t>(g_decode_nbuf));
+    }
+    return slot;
 }
 
 int launch_decode(const AttnArgs& a, void* stream)

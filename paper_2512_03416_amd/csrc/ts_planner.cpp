@@ -85,14 +85,19 @@ int validate_batch(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* 
     return TS_OK;
 }
 
-static int32_t auto_split_pages(int64_t decode_tiles)
+// Pages per decode item.  A row that fits one item is finished by its workgroup without any
+// partial result in HBM, so rows are cut only (a) when they exceed one workgroup slot's fair share
+// of the batch (they would otherwise finish last), or (b) when the batch has too few rows to
+// occupy every slot.
+static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int64_t n_rows, int Hkv,
+                                int32_t wg_slots)
 {
-    // Enough items to keep every SIMD of 256 CUs busy with several waves and leave a tail to
-    // balance, but long enough that the prologue (query load, first page latency) and the
-    // partial write are amortised.
-    const int64_t want_waves = 8192;
-    int64_t L = (decode_tiles + want_waves - 1) / want_waves;
-    return (int32_t)std::min<int64_t>(128, std::max<int64_t>(8, L));
+    const int64_t slots = std::max<int32_t>(1, wg_slots);
+    int64_t L = std::max<int64_t>(32, (decode_tiles + slots - 1) / slots);
+    const int64_t want_items = (3 * slots / 2 + Hkv - 1) / Hkv;        // per KV head
+    if (n_rows < want_items && decode_pages > 0)
+        L = std::min<int64_t>(L, std::max<int64_t>(8, (decode_pages + want_items - 1) / want_items));
+    return (int32_t)std::min<int64_t>(L, 1 << 20);
 }
 
 void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx_lens, int num_seqs,
@@ -104,13 +109,14 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     const int Hkv = d.num_kv_heads;
     p.seqs.resize((size_t)num_seqs + 1);
     int32_t off = 0;
-    int64_t decode_tiles = 0;
+    int64_t decode_tiles = 0, decode_pages = 0;
     for (int s = 0; s < num_seqs; ++s) {
         p.seqs[s] = SeqMeta{off, q_lens[s], ctx_lens[s], ctx_lens[s] - q_lens[s]};
         off += q_lens[s];
         p.info.ctx_pages += (ctx_lens[s] + kPage - 1) / kPage;
         if (q_lens[s] == 1) {
             p.info.decode_tokens += 1;
+            decode_pages += (ctx_lens[s] + kPage - 1) / kPage;
             decode_tiles += (int64_t)((ctx_lens[s] + kPage - 1) / kPage) * Hkv;
         } else {
             p.info.prefill_tokens += q_lens[s];
@@ -119,7 +125,9 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     p.seqs[num_seqs] = SeqMeta{off, 0, 0, 0};
     p.info.total_tokens = off;
 
-    const int32_t L = opt.split_pages > 0 ? opt.split_pages : auto_split_pages(decode_tiles);
+    const int32_t L = opt.split_pages > 0
+                          ? opt.split_pages
+                          : auto_split_pages(decode_tiles, decode_pages, p.info.decode_tokens, Hkv, opt.wg_slots);
     const int32_t TT = opt.tile_tokens > 0 ? opt.tile_tokens : prefill_tile_tokens(d);
     p.info.split_pages = L;
     p.info.tile_tokens = TT;

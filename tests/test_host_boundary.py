@@ -78,7 +78,7 @@ def test_plan_counts_and_decode_items_cover_every_page_once():
         cover = {}
         for row, seq, n_keys, pb, pe in items:
             assert ql[seq] == 1 and n_keys == ctx[seq] and 0 <= pb < pe <= -(-n_keys // 16)
-            assert pe - pb <= max(info.split_pages, 1) and pe - pb <= 128
+            assert pe - pb <= max(info.split_pages, 1)
             assert row == ql[:seq].sum()
             cover.setdefault(seq, []).extend(range(pb, pe))
         assert set(cover) == {s for s in range(40) if ql[s] == 1}
