@@ -135,6 +135,7 @@ def main():
     ap.add_argument("--calibrate", action="store_true", help="also time the plain copy/read kernels")
     ap.add_argument("--split-pages", type=int, default=0)
     ap.add_argument("--prefetch-tiles", type=int, default=0)
+    ap.add_argument("--xcd-count", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -158,6 +159,8 @@ def main():
         ctx.set_option("decode_split_pages", args.split_pages)
     if args.prefetch_tiles:
         ctx.set_option("decode_prefetch_tiles", args.prefetch_tiles)
+    if args.xcd_count:
+        ctx.set_option("xcd_count", args.xcd_count)
     nbytes = ts.cache_bytes(desc)
     kc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
     vc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")

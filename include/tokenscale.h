@@ -152,6 +152,7 @@ const char *ts_last_error(const ts_ctx *ctx);
  *   "decode_split_pages"  longest page range of one decode item (0 = choose from the batch)
  *   "prefill_path"        0 = MFMA tiles where supported, 1 = force the generic row kernel
  *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave (process-wide)
+ *   "xcd_count"           accelerator dies the prefill launch order is laid out for (default 8)
  *   "kernel_timing"       1 = record HIP events around every launch (see ts_kernel_times)
  * Unknown names give TS_ERR_INVALID_ARG. */
 int ts_set_option(ts_ctx *ctx, const char *name, int64_t value);

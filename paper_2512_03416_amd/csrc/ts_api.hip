@@ -142,7 +142,7 @@ int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out)
 }
 
 struct WorkLayout {
-    size_t seqs, dec, cmb, pf, rows, total;
+    size_t seqs, dec, cmb, pf, pfmap, rows, total;
 };
 
 WorkLayout layout_of(const Plan& p)
@@ -153,6 +153,7 @@ WorkLayout layout_of(const Plan& p)
     w.dec = o;  o = align16(o + p.dec.size() * sizeof(DecItem));
     w.cmb = o;  o = align16(o + p.cmb.size() * sizeof(CmbItem));
     w.pf = o;   o = align16(o + p.pf.size() * sizeof(PfItem));
+    w.pfmap = o; o = align16(o + p.pfmap.size() * sizeof(PfSlot));
     w.rows = o; o = align16(o + p.rows.size() * sizeof(RowItem));
     w.total = o;
     return w;
@@ -171,6 +172,7 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
     if (!p.dec.empty()) memcpy(h + w.dec, p.dec.data(), p.dec.size() * sizeof(DecItem));
     if (!p.cmb.empty()) memcpy(h + w.cmb, p.cmb.data(), p.cmb.size() * sizeof(CmbItem));
     if (!p.pf.empty()) memcpy(h + w.pf, p.pf.data(), p.pf.size() * sizeof(PfItem));
+    if (!p.pfmap.empty()) memcpy(h + w.pfmap, p.pfmap.data(), p.pfmap.size() * sizeof(PfSlot));
     if (!p.rows.empty()) memcpy(h + w.rows, p.rows.data(), p.rows.size() * sizeof(RowItem));
     TS_HIP(c, hipMemcpyAsync(c->d_work, h, w.total, hipMemcpyHostToDevice, st));
     TS_HIP(c, hipEventRecord(slot->ev, st));
@@ -306,7 +308,8 @@ extern "C" int ts_reserve(ts_ctx* c, int64_t max_tokens, int64_t max_seqs, int64
     // per sequence, a prefill tile per 8 tokens.
     const size_t items = (size_t)max_ctx_pages / 8 + (size_t)max_seqs + (size_t)max_tokens;
     const size_t bytes = ((size_t)max_seqs + 1) * sizeof(SeqMeta) + items * (sizeof(DecItem) + sizeof(CmbItem)) +
-                         (size_t)max_tokens * (sizeof(RowItem) + sizeof(PfItem)) + 256;
+                         (size_t)max_tokens * (sizeof(RowItem) + sizeof(PfItem)) +
+                         (size_t)max_tokens * c->desc.num_kv_heads * 2 * sizeof(PfSlot) + 4096;
     int rc = ensure_work(c, bytes);
     if (rc != TS_OK) return rc;
     for (int i = 0; i < kRing; ++i) {
@@ -335,6 +338,11 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         set_decode_nbuf((int)value);
         return TS_OK;
     }
+    if (!strcmp(name, "xcd_count")) {
+        if (value < 1 || value > 64) return fail(c, TS_ERR_INVALID_ARG, "xcd_count must be 1..64");
+        c->opt.xcds = (int32_t)value;
+        return TS_OK;
+    }
     if (!strcmp(name, "kernel_timing")) {
         c->timing = value != 0;
         return TS_OK;
@@ -357,7 +365,7 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     if (c->plan.info.total_tokens == 0) return TS_OK;
     if (!k_new || !v_new) return fail(c, TS_ERR_INVALID_ARG, "k_new / v_new is NULL");
     // only the sequence table is needed on the device
-    c->plan.dec.clear(); c->plan.cmb.clear(); c->plan.pf.clear(); c->plan.rows.clear();
+    c->plan.dec.clear(); c->plan.cmb.clear(); c->plan.pf.clear(); c->plan.rows.clear(); c->plan.pfmap.clear();
     const WorkLayout w = layout_of(c->plan);
     hipStream_t st = (hipStream_t)stream;
     rc = upload_plan(c, st, w);
@@ -422,6 +430,7 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     a.dec = (const DecItem*)(c->d_work + w.dec);   a.n_dec = (int32_t)p.dec.size();
     a.cmb = (const CmbItem*)(c->d_work + w.cmb);   a.n_cmb = (int32_t)p.cmb.size();
     a.pf = (const PfItem*)(c->d_work + w.pf);      a.n_pf = (int32_t)p.pf.size();
+    a.pfmap = (const PfSlot*)(c->d_work + w.pfmap); a.n_pfmap = (int32_t)p.pfmap.size();
     a.rows = (const RowItem*)(c->d_work + w.rows); a.n_rows = (int32_t)p.rows.size();
     a.part_o = c->d_part_o; a.part_ml = c->d_part_ml;
 

@@ -47,6 +47,11 @@ struct PfItem {           // a causal tile of a prefill chunk; launched once per
     int32_t pad;
 };
 
+struct PfSlot {           // workgroup -> (prefill tile, KV head); item < 0 = nothing to do
+    int32_t item;
+    int32_t head_kv;
+};
+
 struct RowItem {          // one query row for the generic kernel
     int32_t row;
     int32_t seq;
@@ -59,6 +64,7 @@ struct Plan {
     std::vector<DecItem> dec;
     std::vector<CmbItem> cmb;
     std::vector<PfItem> pf;
+    std::vector<PfSlot> pfmap;       // launch order of the prefill workgroups (XCD-aware)
     std::vector<RowItem> rows;
     ts_plan_info info{};
 };
@@ -66,6 +72,7 @@ struct Plan {
 struct PlanOptions {
     int32_t split_pages = 0;    // 0 = auto
     int32_t wg_slots = 768;     // decode workgroups resident at once (256 CUs x 3)
+    int32_t xcds = 8;           // accelerator dies; workgroup i is dispatched to die i % xcds
     bool generic_only = false;  // every row through the generic kernel
     bool prefill_generic = false;
     int32_t tile_tokens = 0;    // query tokens per prefill tile
@@ -112,6 +119,7 @@ struct AttnArgs {
     const DecItem* dec; int32_t n_dec;
     const CmbItem* cmb; int32_t n_cmb;
     const PfItem* pf;   int32_t n_pf;
+    const PfSlot* pfmap; int32_t n_pfmap;
     const RowItem* rows; int32_t n_rows;
     // split-K partials: o [slot][Hq][D] fp32 (unnormalised), ml [slot][Hq][2] = (max, sum) in log2 units
     float* part_o; float* part_ml;

@@ -34,63 +34,33 @@ __device__ __forceinline__ uint2 fp8x4_bf16x4(uint32_t w)
     return r;
 }
 
-// keep the first n (0..8) 16-bit elements of a 16-byte vector
+// keep the first n (0..8) 16-bit elements of a 16-byte vector (plain register arithmetic: local
+// arrays here end up in scratch memory and serialise the prefetch)
+__device__ __forceinline__ uint32_t mask16(int left) { return left >= 2 ? 0xffffffffu : (left == 1 ? 0xffffu : 0u); }
 __device__ __forceinline__ uint4 keep_first16(uint4 v, int n)
 {
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t o[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int left = n - 2 * i;
-        o[i] = left >= 2 ? w[i] : (left == 1 ? (w[i] & 0xffffu) : 0u);
-    }
-    return make_uint4(o[0], o[1], o[2], o[3]);
+    return make_uint4(v.x & mask16(n), v.y & mask16(n - 2), v.z & mask16(n - 4), v.w & mask16(n - 6));
 }
 // keep the first n (0..16) bytes of a 16-byte vector
+__device__ __forceinline__ uint32_t mask8(int left)
+{
+    return left >= 4 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << (8 * left)) - 1u));
+}
 __device__ __forceinline__ uint4 keep_first8(uint4 v, int n)
 {
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t o[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int left = n - 4 * i;
-        o[i] = left >= 4 ? w[i] : (left <= 0 ? 0u : (w[i] & ((1u << (8 * left)) - 1u)));
-    }
-    return make_uint4(o[0], o[1], o[2], o[3]);
+    return make_uint4(v.x & mask8(n), v.y & mask8(n - 4), v.z & mask8(n - 8), v.w & mask8(n - 12));
 }
 
 template <typename KT> struct Stage;                       // one thread's share of a 64-token stage
-template <> struct Stage<uint16_t> { uint4 k[4]; uint4 v[4]; };
-template <> struct Stage<uint8_t>  { uint4 k[2]; uint4 v[2]; };
+// (named members, no arrays: an array member that is ever indexed by a loop variable which the
+// optimiser fails to fold sends the whole object to scratch memory)
+template <> struct Stage<uint16_t> { uint4 k0, k1, k2, k3, v0, v1, v2, v3; };
+template <> struct Stage<uint8_t>  { uint4 k0, k1, v0, v1; };
 
 // LDS image of a stage (bf16 in both cases):
 //   K: 4 pages x [16 dim-chunks][16 tokens][8]          = 4 x 4096 bytes
 //   V: [2 page pairs][8 dim blocks][4 r][16 m][2 pages][4 tokens] = 16384 bytes
 struct __align__(16) StageLds { unsigned char k[4 * 4096]; unsigned char v[16384]; };
-
-template <typename KT>
-__device__ __forceinline__ void stage_fetch(Stage<KT>& st, const AttnArgs& a, const int32_t* bt, int kv0,
-                                            int last_page, int g, int tid)
-{
-    const char* kc = (const char*)a.k_cache;
-    const char* vc = (const char*)a.v_cache;
-    if constexpr (sizeof(KT) == 2) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {                      // thread copies 16 bytes of each page's tiles
-            const int64_t tile = (int64_t)bt[min(kv0 / kPage + i, last_page)] * a.geo.Hkv + g;
-            st.k[i] = *(const uint4*)(kc + tile * 4096 + tid * 16);
-            st.v[i] = *(const uint4*)(vc + tile * 4096 + tid * 16);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {                      // 4 pages x 2048 bytes = 512 chunks
-            const int ci = i * 256 + tid, pg = ci >> 7;
-            const int64_t tile = (int64_t)bt[min(kv0 / kPage + pg, last_page)] * a.geo.Hkv + g;
-            st.k[i] = *(const uint4*)(kc + tile * 2048 + (ci & 127) * 16);
-            st.v[i] = *(const uint4*)(vc + tile * 2048 + (ci & 127) * 16);
-        }
-    }
-}
 
 __device__ __forceinline__ int v_lds_offset(int page_in_stage, int dim, int r)
 {
@@ -98,39 +68,75 @@ __device__ __forceinline__ int v_lds_offset(int page_in_stage, int dim, int r)
     return ((((pp * 8 + blk) * 4 + r) * 16 + m) * 2 + ab) * 8;
 }
 
-template <typename KT>
-__device__ __forceinline__ void stage_store(const Stage<KT>& st, StageLds& lds, int kv0, int ctx_len, int tid)
+// ---- bf16 cache: each thread copies 16 bytes of every page's K tile and V tile ------------------
+__device__ __forceinline__ void fetch_page_bf16(uint4& k, uint4& v, const AttnArgs& a, const int32_t* bt,
+                                                int page_idx, int last_page, int g, int tid)
 {
-    if constexpr (sizeof(KT) == 2) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *(uint4*)(lds.k + i * 4096 + tid * 16) = st.k[i];
-            // V chunk: dim = tid/2, tokens 8*hf .. 8*hf+7 of page i
-            const int dim = tid >> 1, hf = tid & 1;
-            const int nvalid = ctx_len - (kv0 + i * kPage + 8 * hf);      // poison past ctx_len -> 0
-            const uint4 v = nvalid >= 8 ? st.v[i] : keep_first16(st.v[i], max(nvalid, 0));
-            *(uint2*)(lds.v + v_lds_offset(i, dim, 2 * hf)) = make_uint2(v.x, v.y);
-            *(uint2*)(lds.v + v_lds_offset(i, dim, 2 * hf + 1)) = make_uint2(v.z, v.w);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int ci = i * 256 + tid, pg = ci >> 7, c = ci & 127;
-            // K chunk: 16 dims (chunk c/16) of token c%16 -> two bf16 chunks of 8 dims
-            const int c16 = c >> 4, tok = c & 15;
-            const uint2 a0 = fp8x4_bf16x4(st.k[i].x), a1 = fp8x4_bf16x4(st.k[i].y);
-            const uint2 a2 = fp8x4_bf16x4(st.k[i].z), a3 = fp8x4_bf16x4(st.k[i].w);
-            *(uint4*)(lds.k + pg * 4096 + ((2 * c16) * 16 + tok) * 16) = make_uint4(a0.x, a0.y, a1.x, a1.y);
-            *(uint4*)(lds.k + pg * 4096 + ((2 * c16 + 1) * 16 + tok) * 16) = make_uint4(a2.x, a2.y, a3.x, a3.y);
-            // V chunk: dim c, 16 tokens of page pg
-            const int nvalid = ctx_len - (kv0 + pg * kPage);
-            const uint4 v = nvalid >= 16 ? st.v[i] : keep_first8(st.v[i], max(nvalid, 0));
-            *(uint2*)(lds.v + v_lds_offset(pg, c, 0)) = fp8x4_bf16x4(v.x);
-            *(uint2*)(lds.v + v_lds_offset(pg, c, 1)) = fp8x4_bf16x4(v.y);
-            *(uint2*)(lds.v + v_lds_offset(pg, c, 2)) = fp8x4_bf16x4(v.z);
-            *(uint2*)(lds.v + v_lds_offset(pg, c, 3)) = fp8x4_bf16x4(v.w);
-        }
-    }
+    const int64_t tile = (int64_t)bt[min(page_idx, last_page)] * a.geo.Hkv + g;
+    k = *(const uint4*)((const char*)a.k_cache + tile * 4096 + tid * 16);
+    v = *(const uint4*)((const char*)a.v_cache + tile * 4096 + tid * 16);
+}
+__device__ __forceinline__ void stage_fetch(Stage<uint16_t>& st, const AttnArgs& a, const int32_t* bt, int kv0,
+                                            int last_page, int g, int tid)
+{
+    const int p0 = kv0 / kPage;
+    fetch_page_bf16(st.k0, st.v0, a, bt, p0 + 0, last_page, g, tid);
+    fetch_page_bf16(st.k1, st.v1, a, bt, p0 + 1, last_page, g, tid);
+    fetch_page_bf16(st.k2, st.v2, a, bt, p0 + 2, last_page, g, tid);
+    fetch_page_bf16(st.k3, st.v3, a, bt, p0 + 3, last_page, g, tid);
+}
+__device__ __forceinline__ void store_page_bf16(uint4 k, uint4 v, StageLds& lds, int i, int kv0, int ctx_len, int tid)
+{
+    *(uint4*)(lds.k + i * 4096 + tid * 16) = k;
+    // V chunk: dim = tid/2, tokens 8*hf .. 8*hf+7 of page i
+    const int dim = tid >> 1, hf = tid & 1;
+    const int nvalid = ctx_len - (kv0 + i * kPage + 8 * hf);              // poison past ctx_len -> 0
+    if (nvalid < 8) v = keep_first16(v, max(nvalid, 0));
+    *(uint2*)(lds.v + v_lds_offset(i, dim, 2 * hf)) = make_uint2(v.x, v.y);
+    *(uint2*)(lds.v + v_lds_offset(i, dim, 2 * hf + 1)) = make_uint2(v.z, v.w);
+}
+__device__ __forceinline__ void stage_store(const Stage<uint16_t>& st, StageLds& lds, int kv0, int ctx_len, int tid)
+{
+    store_page_bf16(st.k0, st.v0, lds, 0, kv0, ctx_len, tid);
+    store_page_bf16(st.k1, st.v1, lds, 1, kv0, ctx_len, tid);
+    store_page_bf16(st.k2, st.v2, lds, 2, kv0, ctx_len, tid);
+    store_page_bf16(st.k3, st.v3, lds, 3, kv0, ctx_len, tid);
+}
+
+// ---- fp8 cache: 4 pages x 2048 bytes = 512 chunks of 16 bytes, two per thread, widened to bf16 ----
+__device__ __forceinline__ void fetch_chunk_fp8(uint4& k, uint4& v, const AttnArgs& a, const int32_t* bt,
+                                                int kv0, int ci, int last_page, int g)
+{
+    const int64_t tile = (int64_t)bt[min(kv0 / kPage + (ci >> 7), last_page)] * a.geo.Hkv + g;
+    k = *(const uint4*)((const char*)a.k_cache + tile * 2048 + (ci & 127) * 16);
+    v = *(const uint4*)((const char*)a.v_cache + tile * 2048 + (ci & 127) * 16);
+}
+__device__ __forceinline__ void stage_fetch(Stage<uint8_t>& st, const AttnArgs& a, const int32_t* bt, int kv0,
+                                            int last_page, int g, int tid)
+{
+    fetch_chunk_fp8(st.k0, st.v0, a, bt, kv0, tid, last_page, g);
+    fetch_chunk_fp8(st.k1, st.v1, a, bt, kv0, 256 + tid, last_page, g);
+}
+__device__ __forceinline__ void store_chunk_fp8(uint4 k, uint4 v, StageLds& lds, int ci, int kv0, int ctx_len)
+{
+    const int pg = ci >> 7, c = ci & 127;
+    // K chunk: 16 dims (chunk c/16) of token c%16 -> two bf16 chunks of 8 dims
+    const int c16 = c >> 4, tok = c & 15;
+    const uint2 a0 = fp8x4_bf16x4(k.x), a1 = fp8x4_bf16x4(k.y), a2 = fp8x4_bf16x4(k.z), a3 = fp8x4_bf16x4(k.w);
+    *(uint4*)(lds.k + pg * 4096 + ((2 * c16) * 16 + tok) * 16) = make_uint4(a0.x, a0.y, a1.x, a1.y);
+    *(uint4*)(lds.k + pg * 4096 + ((2 * c16 + 1) * 16 + tok) * 16) = make_uint4(a2.x, a2.y, a3.x, a3.y);
+    // V chunk: dim c, 16 tokens of page pg
+    const int nvalid = ctx_len - (kv0 + pg * kPage);
+    if (nvalid < 16) v = keep_first8(v, max(nvalid, 0));
+    *(uint2*)(lds.v + v_lds_offset(pg, c, 0)) = fp8x4_bf16x4(v.x);
+    *(uint2*)(lds.v + v_lds_offset(pg, c, 1)) = fp8x4_bf16x4(v.y);
+    *(uint2*)(lds.v + v_lds_offset(pg, c, 2)) = fp8x4_bf16x4(v.z);
+    *(uint2*)(lds.v + v_lds_offset(pg, c, 3)) = fp8x4_bf16x4(v.w);
+}
+__device__ __forceinline__ void stage_store(const Stage<uint8_t>& st, StageLds& lds, int kv0, int ctx_len, int tid)
+{
+    store_chunk_fp8(st.k0, st.v0, lds, tid, kv0, ctx_len);
+    store_chunk_fp8(st.k1, st.v1, lds, 256 + tid, kv0, ctx_len);
 }
 
 template <typename KT>
@@ -138,8 +144,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(AttnArgs a)
 {
     constexpr int D = 128, KB = 4, DB = 8, NT = 2;
     __shared__ StageLds lds;
-    const PfItem it = a.pf[blockIdx.x];
-    const int g = blockIdx.y;
+    const int32_t TS_CONSTANT* slot = as_constant((const int32_t*)(a.pfmap + blockIdx.x));
+    const int item_idx = slot[0], g = slot[1];
+    if (item_idx < 0) return;                               // padding of the die-aware launch order
+    const PfItem it = a.pf[item_idx];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane >> 4, n = lane & 15;
     const int Hq = a.geo.Hq, G = a.geo.G;
 
@@ -292,7 +300,7 @@ int launch_prefill(const AttnArgs& a, void* stream)
 {
     if (a.n_pf <= 0) return (int)hipSuccess;
     if (a.geo.D != 128 || a.geo.q_dtype != TS_BF16) return (int)hipErrorInvalidValue;
-    dim3 grid((unsigned)a.n_pf, (unsigned)a.geo.Hkv), block(256);
+    dim3 grid((unsigned)a.n_pfmap), block(256);
     hipStream_t st = (hipStream_t)stream;
     if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_kernel<uint16_t>), grid, block, 0, st, a);
     else if (a.geo.kv_dtype == TS_FP8_E4M3) hipLaunchKernelGGL((prefill_kernel<uint8_t>), grid, block, 0, st, a);

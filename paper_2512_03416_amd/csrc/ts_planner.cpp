@@ -100,6 +100,53 @@ static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int6
     return (int32_t)std::min<int64_t>(L, 1 << 20);
 }
 
+// Launch order of the prefill workgroups.  Workgroups are dispatched to the accelerator dies
+// round-robin (workgroup i runs on die i % xcds) and every die has its own L2.  All tiles of one
+// (chunk, KV head) stream read the same K/V pages, so a stream is pinned to one die and its tiles
+// are launched next to each other: they walk the stream's pages almost in step, and the pages are
+// fetched from HBM about once instead of once per tile.  Streams are spread over the dies by
+// decreasing work (greedy), longest tiles of a stream first.
+static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds)
+{
+    p.pfmap.clear();
+    if (p.pf.empty()) return;
+    struct Stream { int32_t seq; int32_t g; int64_t work; std::vector<int32_t> items; };
+    std::vector<Stream> streams;
+    {
+        std::vector<int32_t> order(p.pf.size());
+        for (size_t i = 0; i < order.size(); ++i) order[i] = (int32_t)i;
+        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return p.pf[a].seq < p.pf[b].seq; });
+        size_t i = 0;
+        while (i < order.size()) {
+            size_t j = i;
+            int64_t work = 0;
+            std::vector<int32_t> items;
+            while (j < order.size() && p.pf[order[j]].seq == p.pf[order[i]].seq) {
+                const PfItem& it = p.pf[order[j]];
+                work += it.prefix + it.tok_begin + it.tok_count;
+                items.push_back(order[j]);       // p.pf is sorted longest first, the stable sort keeps that
+                ++j;
+            }
+            for (int g = 0; g < Hkv; ++g) streams.push_back(Stream{p.pf[order[i]].seq, g, work, items});
+            i = j;
+        }
+    }
+    std::stable_sort(streams.begin(), streams.end(), [](const Stream& a, const Stream& b) { return a.work > b.work; });
+    std::vector<std::vector<PfSlot>> per(xcds);
+    std::vector<int64_t> load(xcds, 0);
+    for (const Stream& st : streams) {
+        int best = 0;
+        for (int x = 1; x < xcds; ++x) if (load[x] < load[best]) best = x;
+        load[best] += st.work;
+        for (int32_t it : st.items) per[best].push_back(PfSlot{it, st.g});
+    }
+    size_t longest = 0;
+    for (auto& v : per) longest = std::max(longest, v.size());
+    p.pfmap.assign(longest * xcds, PfSlot{-1, 0});
+    for (int x = 0; x < xcds; ++x)
+        for (size_t k = 0; k < per[x].size(); ++k) p.pfmap[k * xcds + x] = per[x][k];
+}
+
 void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx_lens, int num_seqs,
                 const PlanOptions& opt, Plan* plan)
 {
@@ -165,6 +212,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     std::stable_sort(p.pf.begin(), p.pf.end(), [](const PfItem& a, const PfItem& b) {
         return (a.prefix + a.tok_begin + a.tok_count) > (b.prefix + b.tok_begin + b.tok_count);
     });
+    map_prefill_to_xcds(p, Hkv, std::max(1, opt.xcds));
     std::stable_sort(p.rows.begin(), p.rows.end(),
                      [](const RowItem& a, const RowItem& b) { return a.n_keys > b.n_keys; });
     p.info.n_decode_items = (int32_t)p.dec.size();
