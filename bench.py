@@ -215,7 +215,7 @@ def main():
 
     work = algorithmic_work(batch)
     tot = {k: v[0] * v[1] for k, v in ktimes.items()}
-    dominant = max(("decode", "prefill", "rows"), key=lambda k: tot.get(k, 0.0))
+    dominant = max(("decode", "prefill", "rows", "mixed"), key=lambda k: tot.get(k, 0.0))
     dom_ms = ktimes[dominant][1]
     if dominant == "decode":
         ach = work["decode_bytes"] / (dom_ms * 1e-3) / 1e9
@@ -227,6 +227,22 @@ def main():
         roof = dict(bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=ach / PEAK_BF16_TFLOPS, traffic=None, kernel="prefill_kernel", kernel_ms=dom_ms,
                     algorithmic_flops=work["prefill_flops"])
+    elif dominant == "mixed":
+        # the persistent kernel runs both kinds: price it against whichever floor is higher
+        t_hbm = (work["decode_bytes"] + work["prefill_bytes"]) / (PEAK_HBM_GBS * 1e9)
+        t_mfma = work["prefill_flops"] / (PEAK_BF16_TFLOPS * 1e12)
+        if t_mfma >= t_hbm:
+            ach = work["prefill_flops"] / (dom_ms * 1e-3) / 1e12
+            roof = dict(bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                        frac=ach / PEAK_BF16_TFLOPS, traffic=None, kernel="mixed_kernel", kernel_ms=dom_ms,
+                        algorithmic_flops=work["prefill_flops"],
+                        algorithmic_bytes=work["decode_bytes"] + work["prefill_bytes"])
+        else:
+            ach = (work["decode_bytes"] + work["prefill_bytes"]) / (dom_ms * 1e-3) / 1e9
+            roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
+                        traffic=None, kernel="mixed_kernel", kernel_ms=dom_ms,
+                        algorithmic_flops=work["prefill_flops"],
+                        algorithmic_bytes=work["decode_bytes"] + work["prefill_bytes"])
     else:
         bytes_all = work["decode_bytes"] + work["prefill_bytes"]
         ach = bytes_all / (dom_ms * 1e-3) / 1e9

@@ -14,7 +14,9 @@
  *     The caller owns every buffer and the stream; the library owns only its scratch.
  *   - GPU calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and never synchronise the device, except when scratch has to grow (see
- *     ts_reserve).  One context serves one stream at a time.
+ *     ts_reserve).  A context's calls may move from one stream to another: the first call
+ *     on the new stream waits (on the device) for the context's previous call; calls that
+ *     overlap in time on two streams need two contexts.
  *   - HOST arrays are consumed before the call returns.
  *   - Return value 0 = TS_OK, negative = error; ts_last_error() gives the text.  Everything
  *     that can be checked from host data is checked before any launch: a failing call has no
@@ -152,6 +154,8 @@ const char *ts_last_error(const ts_ctx *ctx);
  *   "decode_split_pages"  longest page range of one decode item (0 = choose from the batch)
  *   "prefill_path"        0 = MFMA tiles where supported, 1 = force the generic row kernel
  *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave (process-wide)
+ *   "mixed_persistent"    1 (default) = decode items and prefill tiles of a mixed batch share one
+ *                         persistent launch; 0 = decode kernel, then prefill kernel
  *   "xcd_count"           accelerator dies the prefill launch order is laid out for (default 8)
  *   "kernel_timing"       1 = record HIP events around every launch (see ts_kernel_times)
  * Unknown names give TS_ERR_INVALID_ARG. */
@@ -161,7 +165,8 @@ int ts_set_option(ts_ctx *ctx, const char *name, int64_t value);
  * (enable with ts_set_option(ctx, "kernel_timing", 1); costs two event records per launch).
  * ts_kernel_times waits for the recorded events, then reports, per kernel, the number of timed
  * launches and their mean duration in milliseconds since the last reset. */
-enum { TS_K_APPEND = 0, TS_K_DECODE = 1, TS_K_COMBINE = 2, TS_K_PREFILL = 3, TS_K_ROWS = 4, TS_K_COUNT = 5 };
+enum { TS_K_APPEND = 0, TS_K_DECODE = 1, TS_K_COMBINE = 2, TS_K_PREFILL = 3, TS_K_ROWS = 4, TS_K_MIXED = 5,
+       TS_K_COUNT = 6 };
 typedef struct {
     uint64_t launches[TS_K_COUNT];
     double mean_ms[TS_K_COUNT];
@@ -192,12 +197,21 @@ typedef struct {
 int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
                      int num_seqs, int32_t split_pages, ts_plan_info *out);
 
-/* Host only.  Copies the decode items of the plan as int32 quintuples
- * (row, seq, n_keys, page_begin, page_end) into items_out (capacity in items); returns the
- * number of items, or a negative error. */
-int64_t ts_plan_decode_items(const ts_attn_desc *desc, const int32_t *q_lens,
-                             const int32_t *ctx_lens, int num_seqs, int32_t split_pages,
-                             int32_t *items_out, int64_t capacity);
+/* Host only.  Copies one of the planner's work lists as flat int32 records into out (capacity in
+ * int32 words); returns the number of records, or a negative error.  Lists and record layouts:
+ *   TS_LIST_DECODE  (row, seq, n_keys, page_begin, page_end, partial_slot or -1, 0, 0)
+ *   TS_LIST_COMBINE (row, partial_begin, n_split, 0)
+ *   TS_LIST_PREFILL (seq, row0, q_len, prefix, tok_begin, tok_count, ctx_len, 0)
+ *   TS_LIST_PFMAP   (prefill tile or -1, kv_head)       launch order, workgroup i -> die i % 8
+ *   TS_LIST_ROWS    (row, seq, n_keys, 0)
+ *   TS_LIST_QUEUE   (kind 0 decode / 1 prefill, item, kv_head, 0)   per-die queues, concatenated
+ *   TS_LIST_QOFF    (offset)                                        n_dies + 1 offsets into the queue
+ * wg_slots = 0 uses the default number of resident decode workgroups. */
+enum { TS_LIST_DECODE = 0, TS_LIST_COMBINE = 1, TS_LIST_PREFILL = 2, TS_LIST_PFMAP = 3, TS_LIST_ROWS = 4,
+       TS_LIST_QUEUE = 5, TS_LIST_QOFF = 6 };
+int64_t ts_plan_export(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
+                       int num_seqs, int32_t split_pages, int32_t wg_slots, int which,
+                       int32_t *out, int64_t capacity);
 
 #ifdef __cplusplus
 }

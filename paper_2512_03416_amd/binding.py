@@ -16,10 +16,10 @@ TS_VELOCITY_RESET, TS_VELOCITY_SYNC = 1, 2
 
 EXPORTS = ["ts_check_desc", "ts_cache_bytes", "ts_create", "ts_destroy", "ts_reserve", "ts_kv_append",
            "ts_mixed_paged_attention", "ts_token_velocity", "ts_last_error", "ts_set_option",
-           "ts_plan_describe", "ts_plan_decode_items", "ts_kernel_times", "ts_calib_copy",
+           "ts_plan_describe", "ts_plan_export", "ts_kernel_times", "ts_calib_copy",
            "ts_calib_read"]
 
-KERNEL_NAMES = ["append", "decode", "combine", "prefill", "rows"]
+KERNEL_NAMES = ["append", "decode", "combine", "prefill", "rows", "mixed"]
 
 
 class TokenScaleError(RuntimeError):
@@ -48,7 +48,7 @@ class Velocity(ctypes.Structure):
 
 
 class KernelStats(ctypes.Structure):
-    _fields_ = [("launches", ctypes.c_uint64 * 5), ("mean_ms", ctypes.c_double * 5)]
+    _fields_ = [("launches", ctypes.c_uint64 * 6), ("mean_ms", ctypes.c_double * 6)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -101,9 +101,9 @@ def load_library():
     lib.ts_plan_describe.argtypes = [ctypes.POINTER(Desc), i32p, i32p, ctypes.c_int, ctypes.c_int32,
                                      ctypes.POINTER(PlanInfo)]
     lib.ts_plan_describe.restype = ctypes.c_int
-    lib.ts_plan_decode_items.argtypes = [ctypes.POINTER(Desc), i32p, i32p, ctypes.c_int, ctypes.c_int32,
-                                         i32p, ctypes.c_int64]
-    lib.ts_plan_decode_items.restype = ctypes.c_int64
+    lib.ts_plan_export.argtypes = [ctypes.POINTER(Desc), i32p, i32p, ctypes.c_int, ctypes.c_int32,
+                                   ctypes.c_int32, ctypes.c_int, i32p, ctypes.c_int64]
+    lib.ts_plan_export.restype = ctypes.c_int64
     lib.ts_kernel_times.argtypes = [vp, ctypes.POINTER(KernelStats), ctypes.c_int]
     lib.ts_kernel_times.restype = ctypes.c_int
     lib.ts_calib_copy.argtypes = [vp, vp, vp, ctypes.c_int64]
@@ -153,18 +153,28 @@ def plan_describe(desc: Desc, q_lens, ctx_lens, split_pages: int = 0) -> PlanInf
     return info
 
 
-def plan_decode_items(desc: Desc, q_lens, ctx_lens, split_pages: int = 0) -> np.ndarray:
+PLAN_LISTS = {"decode": (0, 8), "combine": (1, 4), "prefill": (2, 8), "pfmap": (3, 2), "rows": (4, 4),
+              "queue": (5, 4), "qoff": (6, 1)}
+
+
+def plan_export(desc: Desc, q_lens, ctx_lens, which: str, split_pages: int = 0, wg_slots: int = 0) -> np.ndarray:
+    """One of the planner's work lists as an int32 array [records, words] (see tokenscale.h)."""
     ql, cl = _i32(q_lens), _i32(ctx_lens)
     lib = load_library()
-    n = lib.ts_plan_decode_items(ctypes.byref(desc), _np_ptr(ql), _np_ptr(cl), len(ql), split_pages,
-                                 ctypes.c_void_p(0), 0)
+    code, words = PLAN_LISTS[which]
+    n = lib.ts_plan_export(ctypes.byref(desc), _np_ptr(ql), _np_ptr(cl), len(ql), split_pages, wg_slots, code,
+                           ctypes.c_void_p(0), 0)
     if n < 0:
-        raise TokenScaleError(int(n), "ts_plan_decode_items")
-    items = np.zeros((int(n), 5), dtype=np.int32)
+        raise TokenScaleError(int(n), "ts_plan_export")
+    out = np.zeros((int(n), words), dtype=np.int32)
     if n:
-        lib.ts_plan_decode_items(ctypes.byref(desc), _np_ptr(ql), _np_ptr(cl), len(ql), split_pages,
-                                 _np_ptr(items), int(n))
-    return items
+        lib.ts_plan_export(ctypes.byref(desc), _np_ptr(ql), _np_ptr(cl), len(ql), split_pages, wg_slots, code,
+                           _np_ptr(out), int(n) * words)
+    return out
+
+
+def plan_decode_items(desc: Desc, q_lens, ctx_lens, split_pages: int = 0) -> np.ndarray:
+    return plan_export(desc, q_lens, ctx_lens, "decode", split_pages)[:, :5]
 
 
 class Context:

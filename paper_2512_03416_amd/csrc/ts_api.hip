@@ -44,6 +44,7 @@ struct ts_ctx {
     // device scratch
     char* d_work = nullptr;  size_t work_cap = 0;
     float* d_part_o = nullptr; float* d_part_ml = nullptr; int64_t part_cap = 0;
+    int32_t* d_q_ctr = nullptr;      // queue heads of the persistent kernel (zero between launches)
     // pinned staging ring for the work lists
     HostSlot ring[kRing];
     int ring_pos = 0;
@@ -54,6 +55,11 @@ struct ts_ctx {
     std::chrono::steady_clock::time_point t0;
     hipEvent_t last_pass = nullptr;
     bool have_last = false;
+    // the work-list buffer is reused by every call: a call on another stream than the previous one
+    // first waits for that one's kernels
+    hipEvent_t work_done = nullptr;
+    hipStream_t last_stream = nullptr;
+    bool have_work = false;
     // optional per-kernel timing
     bool timing = false;
     struct Timed { int which; hipEvent_t a, b; };
@@ -142,7 +148,7 @@ int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out)
 }
 
 struct WorkLayout {
-    size_t seqs, dec, cmb, pf, pfmap, rows, total;
+    size_t seqs, dec, cmb, pf, pfmap, rows, queue, q_off, total;
 };
 
 WorkLayout layout_of(const Plan& p)
@@ -155,6 +161,8 @@ WorkLayout layout_of(const Plan& p)
     w.pf = o;   o = align16(o + p.pf.size() * sizeof(PfItem));
     w.pfmap = o; o = align16(o + p.pfmap.size() * sizeof(PfSlot));
     w.rows = o; o = align16(o + p.rows.size() * sizeof(RowItem));
+    w.queue = o; o = align16(o + p.queue.size() * sizeof(QItem));
+    w.q_off = o; o = align16(o + p.q_off.size() * sizeof(int32_t));
     w.total = o;
     return w;
 }
@@ -163,6 +171,7 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
 {
     int rc = ensure_work(c, w.total);
     if (rc != TS_OK) return rc;
+    if (c->have_work && st != c->last_stream) TS_HIP(c, hipStreamWaitEvent(st, c->work_done, 0));
     HostSlot* slot = nullptr;
     rc = acquire_slot(c, w.total, &slot);
     if (rc != TS_OK) return rc;
@@ -174,6 +183,8 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
     if (!p.pf.empty()) memcpy(h + w.pf, p.pf.data(), p.pf.size() * sizeof(PfItem));
     if (!p.pfmap.empty()) memcpy(h + w.pfmap, p.pfmap.data(), p.pfmap.size() * sizeof(PfSlot));
     if (!p.rows.empty()) memcpy(h + w.rows, p.rows.data(), p.rows.size() * sizeof(RowItem));
+    if (!p.queue.empty()) memcpy(h + w.queue, p.queue.data(), p.queue.size() * sizeof(QItem));
+    if (!p.q_off.empty()) memcpy(h + w.q_off, p.q_off.data(), p.q_off.size() * sizeof(int32_t));
     TS_HIP(c, hipMemcpyAsync(c->d_work, h, w.total, hipMemcpyHostToDevice, st));
     TS_HIP(c, hipEventRecord(slot->ev, st));
     slot->pending = true;
@@ -214,6 +225,15 @@ int drain_timed(ts_ctx* c)
         c->ev_pool.push_back(t.b);
     }
     c->timed.clear();
+    return TS_OK;
+}
+
+// Marks the end of a call's device work on its stream (see upload_plan).
+int mark_work_done(ts_ctx* c, hipStream_t st)
+{
+    TS_HIP(c, hipEventRecord(c->work_done, st));
+    c->last_stream = st;
+    c->have_work = true;
     return TS_OK;
 }
 
@@ -270,6 +290,17 @@ extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
     c->device = device;
     rc = ensure_work(c, 1 << 16);
     if (rc == TS_OK) rc = ensure_partials(c, 1024);
+    if (rc == TS_OK) {
+        if (hipMalloc((void**)&c->d_q_ctr, 128 * sizeof(int32_t)) != hipSuccess ||
+            hipMemset(c->d_q_ctr, 0, 128 * sizeof(int32_t)) != hipSuccess) {
+            c->err = "queue counter allocation failed";
+            rc = TS_ERR_NOMEM;
+        }
+    }
+    if (rc == TS_OK && hipEventCreateWithFlags(&c->work_done, hipEventDisableTiming) != hipSuccess) {
+        c->err = "hipEventCreate failed";
+        rc = TS_ERR_HIP;
+    }
     if (rc == TS_OK && hipEventCreateWithFlags(&c->last_pass, hipEventDisableTiming) != hipSuccess) {
         c->err = "hipEventCreate failed";
         rc = TS_ERR_HIP;
@@ -287,11 +318,13 @@ extern "C" int ts_destroy(ts_ctx* c)
     if (c->d_work) (void)hipFree(c->d_work);
     if (c->d_part_o) (void)hipFree(c->d_part_o);
     if (c->d_part_ml) (void)hipFree(c->d_part_ml);
+    if (c->d_q_ctr) (void)hipFree(c->d_q_ctr);
     for (HostSlot& s : c->ring) {
         if (s.ptr) (void)hipHostFree(s.ptr);
         if (s.ev) (void)hipEventDestroy(s.ev);
     }
     if (c->last_pass) (void)hipEventDestroy(c->last_pass);
+    if (c->work_done) (void)hipEventDestroy(c->work_done);
     for (auto& t : c->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     delete c;
@@ -309,7 +342,8 @@ extern "C" int ts_reserve(ts_ctx* c, int64_t max_tokens, int64_t max_seqs, int64
     const size_t items = (size_t)max_ctx_pages / 8 + (size_t)max_seqs + (size_t)max_tokens;
     const size_t bytes = ((size_t)max_seqs + 1) * sizeof(SeqMeta) + items * (sizeof(DecItem) + sizeof(CmbItem)) +
                          (size_t)max_tokens * (sizeof(RowItem) + sizeof(PfItem)) +
-                         (size_t)max_tokens * c->desc.num_kv_heads * 2 * sizeof(PfSlot) + 4096;
+                         (size_t)max_tokens * c->desc.num_kv_heads * 2 * (sizeof(PfSlot) + sizeof(QItem)) +
+                         items * c->desc.num_kv_heads * sizeof(QItem) + 4096;
     int rc = ensure_work(c, bytes);
     if (rc != TS_OK) return rc;
     for (int i = 0; i < kRing; ++i) {
@@ -336,6 +370,10 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
     if (!strcmp(name, "decode_prefetch_tiles")) {
         if (value < 2 || value > 4) return fail(c, TS_ERR_INVALID_ARG, "decode_prefetch_tiles must be 2..4");
         set_decode_nbuf((int)value);
+        return TS_OK;
+    }
+    if (!strcmp(name, "mixed_persistent")) {
+        c->opt.mixed_persistent = value != 0;
         return TS_OK;
     }
     if (!strcmp(name, "xcd_count")) {
@@ -366,6 +404,7 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     if (!k_new || !v_new) return fail(c, TS_ERR_INVALID_ARG, "k_new / v_new is NULL");
     // only the sequence table is needed on the device
     c->plan.dec.clear(); c->plan.cmb.clear(); c->plan.pf.clear(); c->plan.rows.clear(); c->plan.pfmap.clear();
+    c->plan.queue.clear(); c->plan.q_off.clear();
     const WorkLayout w = layout_of(c->plan);
     hipStream_t st = (hipStream_t)stream;
     rc = upload_plan(c, st, w);
@@ -378,7 +417,7 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     a.num_seqs = num_seqs; a.total_tokens = (int32_t)c->plan.info.total_tokens;
     hipError_t e = (hipError_t)timed_launch(c, TS_K_APPEND, true, st, [&] { return launch_append(a, stream); });
     if (e != hipSuccess) return hip_fail(c, e, "append launch");
-    return TS_OK;
+    return mark_work_done(c, st);
 }
 
 extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, const void* k_new,
@@ -432,19 +471,32 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     a.pf = (const PfItem*)(c->d_work + w.pf);      a.n_pf = (int32_t)p.pf.size();
     a.pfmap = (const PfSlot*)(c->d_work + w.pfmap); a.n_pfmap = (int32_t)p.pfmap.size();
     a.rows = (const RowItem*)(c->d_work + w.rows); a.n_rows = (int32_t)p.rows.size();
+    a.queue = (const QItem*)(c->d_work + w.queue); a.q_off = (const int32_t*)(c->d_work + w.q_off);
+    a.n_queue = (int32_t)p.queue.size(); a.n_xcd = p.q_off.empty() ? 0 : (int32_t)p.q_off.size() - 1;
+    a.q_ctr = c->d_q_ctr;
     a.part_o = c->d_part_o; a.part_ml = c->d_part_ml;
 
     hipError_t e;
     // decode first: the serving loop's TPOT depends on these rows (Sec. 4.5.2)
-    e = (hipError_t)timed_launch(c, TS_K_DECODE, a.n_dec > 0, st, [&] { return launch_decode(a, stream); });
-    if (e != hipSuccess) return hip_fail(c, e, "decode launch");
-    e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_cmb > 0, st, [&] { return launch_combine(a, stream); });
-    if (e != hipSuccess) return hip_fail(c, e, "combine launch");
-    e = (hipError_t)timed_launch(c, TS_K_PREFILL, a.n_pf > 0, st, [&] { return launch_prefill(a, stream); });
-    if (e != hipSuccess) return hip_fail(c, e, "prefill launch");
+    if (a.n_queue > 0) {
+        // mixed batch: decode items and prefill tiles share the CUs in one persistent launch
+        e = (hipError_t)timed_launch(c, TS_K_MIXED, true, st, [&] { return launch_mixed(a, stream); });
+        if (e != hipSuccess) return hip_fail(c, e, "mixed launch");
+        e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_cmb > 0, st, [&] { return launch_combine(a, stream); });
+        if (e != hipSuccess) return hip_fail(c, e, "combine launch");
+    } else {
+        e = (hipError_t)timed_launch(c, TS_K_DECODE, a.n_dec > 0, st, [&] { return launch_decode(a, stream); });
+        if (e != hipSuccess) return hip_fail(c, e, "decode launch");
+        e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_cmb > 0, st, [&] { return launch_combine(a, stream); });
+        if (e != hipSuccess) return hip_fail(c, e, "combine launch");
+        e = (hipError_t)timed_launch(c, TS_K_PREFILL, a.n_pf > 0, st, [&] { return launch_prefill(a, stream); });
+        if (e != hipSuccess) return hip_fail(c, e, "prefill launch");
+    }
     e = (hipError_t)timed_launch(c, TS_K_ROWS, a.n_rows > 0, st, [&] { return launch_rows(a, stream); });
     if (e != hipSuccess) return hip_fail(c, e, "rows launch");
 
+    rc = mark_work_done(c, st);
+    if (rc != TS_OK) return rc;
     {
         std::lock_guard<std::mutex> lk(c->mu);
         if (!c->window_open) { c->window_open = true; c->t0 = std::chrono::steady_clock::now(); }

@@ -52,6 +52,13 @@ struct PfSlot {           // workgroup -> (prefill tile, KV head); item < 0 = no
     int32_t head_kv;
 };
 
+struct QItem {            // entry of a per-die work queue of the persistent mixed kernel
+    int32_t kind;         // 0 = decode item, 1 = prefill tile
+    int32_t item;
+    int32_t head_kv;
+    int32_t pad;
+};
+
 struct RowItem {          // one query row for the generic kernel
     int32_t row;
     int32_t seq;
@@ -65,6 +72,8 @@ struct Plan {
     std::vector<CmbItem> cmb;
     std::vector<PfItem> pf;
     std::vector<PfSlot> pfmap;       // launch order of the prefill workgroups (XCD-aware)
+    std::vector<QItem> queue;        // mixed batches: per-die queues, concatenated
+    std::vector<int32_t> q_off;      // xcds + 1 offsets into queue
     std::vector<RowItem> rows;
     ts_plan_info info{};
 };
@@ -73,6 +82,7 @@ struct PlanOptions {
     int32_t split_pages = 0;    // 0 = auto
     int32_t wg_slots = 768;     // decode workgroups resident at once (256 CUs x 3)
     int32_t xcds = 8;           // accelerator dies; workgroup i is dispatched to die i % xcds
+    bool mixed_persistent = true; // decode items and prefill tiles in one persistent launch
     bool generic_only = false;  // every row through the generic kernel
     bool prefill_generic = false;
     int32_t tile_tokens = 0;    // query tokens per prefill tile
@@ -120,6 +130,8 @@ struct AttnArgs {
     const CmbItem* cmb; int32_t n_cmb;
     const PfItem* pf;   int32_t n_pf;
     const PfSlot* pfmap; int32_t n_pfmap;
+    const QItem* queue; const int32_t* q_off; int32_t n_queue; int32_t n_xcd;
+    int32_t* q_ctr;            // n_xcd queue heads + 1 finished-workgroup count, zero between launches
     const RowItem* rows; int32_t n_rows;
     // split-K partials: o [slot][Hq][D] fp32 (unnormalised), ml [slot][Hq][2] = (max, sum) in log2 units
     float* part_o; float* part_ml;
@@ -132,5 +144,6 @@ int launch_decode(const AttnArgs& a, void* stream);
 int launch_combine(const AttnArgs& a, void* stream);
 int decode_resident_workgroups(int kv_dtype);   // on the current device, 0 if unknown
 int launch_prefill(const AttnArgs& a, void* stream);
+int launch_mixed(const AttnArgs& a, void* stream);
 
 }  // namespace ts

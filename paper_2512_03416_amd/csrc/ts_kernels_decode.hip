@@ -1,272 +1,15 @@
-// Step a2 (+a4): split-K decode attention over the paged cache, and the merge of the splits.
-//
-// A decode row reads its whole cached context once and does ~2*G flops per cache element, so
-// the scan is bound by HBM bandwidth (the paper's "memory-intensive decode" whose spare compute
-// lets a decoder absorb prefill work, Sec. 1, Sec. 3.4).  The kernel is therefore built around
-// the loads:
-//   - one workgroup of 4 wavefronts owns one item = (decode row, KV head, page range), the waves
-//     taking every 4th page; they share nothing until the end of the item, so many independent
-//     waves per CU keep loads in flight;
-//   - every (page, KV head) tile is one contiguous 4 KB (bf16) / 2 KB (fp8) block; each load
-//     instruction of the wave reads a contiguous 1 KB (K) or 512 B / 256 B (V) run of it, already
-//     in matrix-operand order, straight into registers;
-//   - NBUF tiles are in flight per wave (register ring, unconditional prefetch so the hardware
-//     load counter is statically known);
-//   - the G query heads of the KV head's group ride along as columns of the same MFMA
-//     (S^T = K Q^T, 16 tokens x 16 columns), so each K/V byte is loaded once for the group;
-//   - the accumulator layout of S^T is the B-operand layout of the next MFMA (O^T += V^T P^T),
-//     so the softmax weights never leave registers; the only cross-lane traffic is a 2-step
-//     reduction of the running maximum when it grows, and of the sum at the end.
-// Online softmax keeps a reference maximum per head in log2 units; it is raised only when a page
-// exceeds it by more than kRaise (any reference gives the same quotient, the bound only guards
-// the fp32 range), which removes the accumulator rescale from almost every page.
-#include "ts_device.h"
+// Step a2 (+a4): launchers of the decode kernel and of the merge of split rows.
+#include "ts_decode_item.h"
 
 namespace ts {
 
-constexpr float kRaise = 16.0f;   // log2 units: weights stay below 2^16 relative to the reference
-
-template <typename KT> struct KVTile;
-template <> struct KVTile<uint16_t> { uint4 k[4]; uint2 v[8]; };
-template <> struct KVTile<uint8_t>  { uint4 k[2]; uint32_t v[8]; };
-
-__device__ __forceinline__ void load_tile(KVTile<uint16_t>& t, const char* kc, const char* vc,
-                                          int64_t tile, int lane)
-{
-    const char* kt = kc + tile * 4096 + lane * 16;
-    const char* vt = vc + tile * 4096 + (lane & 15) * 32 + (lane >> 4) * 8;
-#pragma unroll
-    for (int b = 0; b < 4; ++b) t.k[b] = *(const uint4*)(kt + b * 1024);
-#pragma unroll
-    for (int b = 0; b < 8; ++b) t.v[b] = *(const uint2*)(vt + b * 512);
-}
-
-__device__ __forceinline__ void load_tile(KVTile<uint8_t>& t, const char* kc, const char* vc,
-                                          int64_t tile, int lane)
-{
-    const char* kt = kc + tile * 2048 + lane * 16;
-    const char* vt = vc + tile * 2048 + (lane & 15) * 16 + (lane >> 4) * 4;
-#pragma unroll
-    for (int b = 0; b < 2; ++b) t.k[b] = *(const uint4*)(kt + b * 1024);
-#pragma unroll
-    for (int b = 0; b < 8; ++b) t.v[b] = *(const uint32_t*)(vt + b * 256);
-}
-
-// four e4m3 bytes -> four bf16 (exact: every e4m3 value is a bf16 value)
-__device__ __forceinline__ uint2 fp8x4_to_bf16x4(uint32_t w)
-{
-    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
-    const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
-    uint2 r;
-    r.x = __builtin_amdgcn_perm(__float_as_uint(lo.y), __float_as_uint(lo.x), 0x07060302u);
-    r.y = __builtin_amdgcn_perm(__float_as_uint(hi.y), __float_as_uint(hi.x), 0x07060302u);
-    return r;
-}
-
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
-__device__ __forceinline__ s16x4 as_s16x4(uint2 v) { return __builtin_bit_cast(s16x4, v); }
-
-// S^T (16 tokens x 16 columns) = K tile x Q^T for one page
-__device__ __forceinline__ f32x4 qk_tile(const KVTile<uint16_t>& t, const bf16x8* qb)
-{
-    f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.k[b]), qb[b], s, 0, 0, 0);
-    return s;
-}
-__device__ __forceinline__ f32x4 qk_tile(const KVTile<uint8_t>& t, const bf16x8* qb)
-{
-    f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const uint2 a0 = fp8x4_to_bf16x4(t.k[j].x), a1 = fp8x4_to_bf16x4(t.k[j].y);
-        const uint2 a2 = fp8x4_to_bf16x4(t.k[j].z), a3 = fp8x4_to_bf16x4(t.k[j].w);
-        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(make_uint4(a0.x, a0.y, a1.x, a1.y)),
-                                                    qb[2 * j], s, 0, 0, 0);
-        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(make_uint4(a2.x, a2.y, a3.x, a3.y)),
-                                                    qb[2 * j + 1], s, 0, 0, 0);
-    }
-    return s;
-}
-
-__device__ __forceinline__ uint2 v_operand(const KVTile<uint16_t>& t, int b) { return t.v[b]; }
-__device__ __forceinline__ uint2 v_operand(const KVTile<uint8_t>& t, int b) { return fp8x4_to_bf16x4(t.v[b]); }
-
-// dims held by k-block b of the Q operand for lane group r (must mirror the K tile order)
-template <typename KT> __device__ __forceinline__ int q_dim0(int b, int r)
-{
-    if constexpr (sizeof(KT) == 2) return 8 * (4 * b + r);
-    else return 16 * (4 * (b >> 1) + r) + 8 * (b & 1);
-}
-
-// One workgroup of kDecWaves waves per item = (decode row, KV head, page range).  Wave w streams the
-// pages begin+w, begin+w+kDecWaves, ... so the waves read neighbouring tiles at the same time; at
-// the end their (max, sum, O) states meet in LDS and wave 0 merges them in wave order.  A row that
-// fits one item is finished here (no partial ever goes to HBM: stores into the middle of a saturated
-// read stream were measured to cost ~10x their byte share); only rows longer than one workgroup's
-// fair share are cut into several items whose partials go through combine_kernel.
-constexpr int kDecWaves = 4;
-
-struct DecMerge {                          // LDS image of the non-leading waves' state
-    float o[kDecWaves - 1][8][64][4];      // acc[b] of every lane
-    float m[kDecWaves - 1][16];
-    float l[kDecWaves - 1][16];
-};
-
+// KV heads vary fastest over the grid: the Hkv workgroups of one item start together and read the
+// Hkv adjacent tiles of each page (one contiguous run of the cache) at about the same time.
 template <typename KT, int NBUF>
 __global__ __launch_bounds__(64 * kDecWaves) void decode_kernel(AttnArgs a)
 {
-    constexpr int D = 128, KB = 4, DB = 8;
     __shared__ DecMerge mg;
-    // KV heads vary fastest over the grid: the Hkv workgroups of one item start together and read
-    // the Hkv adjacent tiles of each page (one contiguous run of the cache) at about the same time
-    const int g = blockIdx.x % a.geo.Hkv;
-    const int32_t TS_CONSTANT* itp = as_constant((const int32_t*)(a.dec + blockIdx.x / a.geo.Hkv));
-    const int it_row = itp[0], it_seq = itp[1], it_keys = itp[2], it_pb = itp[3], it_pe = itp[4], it_part = itp[5];
-    // (readfirstlane tells the compiler the wave index is uniform, which keeps everything derived
-    // from it -- the page-id loads above all -- on the scalar unit)
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63, r = lane >> 4, n = lane & 15;
-    const int Hq = a.geo.Hq, Hkv = a.geo.Hkv, G = a.geo.G;
-
-    // this wave's pages: it_pb + wave + kDecWaves * k, k = 0 .. np-1
-    const int np = max(0, (it_pe - it_pb - wave + kDecWaves - 1) / kDecWaves);
-    const int32_t TS_CONSTANT* bt = as_constant(a.block_table) + (int64_t)it_seq * a.geo.max_pages + it_pb + wave;
-
-    f32x4 acc[DB];
-#pragma unroll
-    for (int b = 0; b < DB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_ref = -INFINITY, l = 0.0f;
-
-    if (np > 0) {                                                 // wave-uniform
-        // Q^T operand: column n is query head g*G + n; columns >= G repeat the group's last head
-        // (their results are finite and never stored)
-        bf16x8 qb[KB];
-        {
-            const uint16_t* qrow = (const uint16_t*)a.q + ((int64_t)it_row * Hq + g * G + min(n, G - 1)) * D;
-#pragma unroll
-            for (int b = 0; b < KB; ++b) qb[b] = as_bf16x8(*(const uint4*)(qrow + q_dim0<KT>(b, r)));
-        }
-        const float kscale = (sizeof(KT) == 1) ? a.k_scale[g] : 1.0f;
-        const float c = a.sm_scale * kscale * kLog2e;
-        const char* kc = (const char*)a.k_cache;
-        const char* vc = (const char*)a.v_cache;
-
-        // page ids come through the scalar cache, one fetch ahead of their use
-        int next_k = 0;
-        int next_id = bt[0];
-        auto fetch = [&](KVTile<KT>& t) {
-            load_tile(t, kc, vc, (int64_t)next_id * Hkv + g, lane);
-            next_k = min(next_k + 1, np - 1);                     // past the end: stay on the last page
-            next_id = bt[kDecWaves * next_k];
-        };
-        KVTile<KT> buf[NBUF];
-#pragma unroll
-        for (int j = 0; j < NBUF; ++j) fetch(buf[j]);
-
-        for (int base = 0; base < np; base += NBUF) {
-#pragma unroll
-            for (int j = 0; j < NBUF; ++j) {
-                const int k = base + j;
-                if (k < np) {                                     // wave-uniform
-                    const KVTile<KT>& t = buf[j];
-                    const int page = it_pb + wave + kDecWaves * k;
-                    f32x4 s = qk_tile(t, qb);
-                    float t0 = s[0] * c, t1 = s[1] * c, t2 = s[2] * c, t3 = s[3] * c;
-                    const int nvalid = it_keys - (page * kPage + 4 * r);   // tokens tok0 .. tok0+3 valid if < nvalid
-                    const bool tail = (page + 1) * kPage > it_keys;        // wave-uniform
-                    if (tail) {
-                        t0 = nvalid > 0 ? t0 : -INFINITY; t1 = nvalid > 1 ? t1 : -INFINITY;
-                        t2 = nvalid > 2 ? t2 : -INFINITY; t3 = nvalid > 3 ? t3 : -INFINITY;
-                    }
-                    const float lmax = fmaxf(fmaxf(t0, t1), fmaxf(t2, t3));
-                    if (__any(lmax > m_ref + kRaise)) {           // raise the reference (rare)
-                        float full = fmaxf(lmax, __shfl_xor(lmax, 16, 64));
-                        full = fmaxf(full, __shfl_xor(full, 32, 64));
-                        const float m_new = fmaxf(m_ref, full);
-                        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // 0 on the first page
-#pragma unroll
-                        for (int b = 0; b < DB; ++b) acc[b] *= alpha;
-                        l *= alpha;
-                        m_ref = m_new;
-                    }
-                    const float p0 = __builtin_amdgcn_exp2f(t0 - m_ref), p1 = __builtin_amdgcn_exp2f(t1 - m_ref);
-                    const float p2 = __builtin_amdgcn_exp2f(t2 - m_ref), p3 = __builtin_amdgcn_exp2f(t3 - m_ref);
-                    l += (p0 + p1) + (p2 + p3);
-                    uint2 pw;
-                    pw.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p0, p1}, bf16x2));
-                    pw.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p2, p3}, bf16x2));
-                    const s16x4 pv = as_s16x4(pw);
-                    uint64_t keep = ~0ull;                        // zero V of slots past n_keys (poison)
-                    if (tail) keep = nvalid >= 4 ? ~0ull : (nvalid <= 0 ? 0ull : ((1ull << (16 * nvalid)) - 1ull));
-#pragma unroll
-                    for (int b = 0; b < DB; ++b) {
-                        uint2 vv = v_operand(t, b);
-                        if (tail) { vv.x &= (uint32_t)keep; vv.y &= (uint32_t)(keep >> 32); }
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(as_s16x4(vv), pv, acc[b], 0, 0, 0);
-                    }
-                }
-                fetch(buf[j]);                                    // refill (clamped to the wave's last page)
-            }
-        }
-    }
-
-    float l_tot = l + __shfl_xor(l, 16, 64);
-    l_tot += __shfl_xor(l_tot, 32, 64);
-
-    // ---- merge the waves' states (wave order, so the result is reproducible) ----------------------
-    if (wave > 0) {
-#pragma unroll
-        for (int b = 0; b < DB; ++b) *(f32x4*)mg.o[wave - 1][b][lane] = acc[b];
-        if (r == 0) { mg.m[wave - 1][n] = m_ref; mg.l[wave - 1][n] = l_tot; }
-    }
-    __syncthreads();
-    if (wave != 0) return;
-    float M = m_ref;
-#pragma unroll
-    for (int w = 0; w < kDecWaves - 1; ++w) M = fmaxf(M, mg.m[w][n]);
-    // wave 0 always holds the item's first page, so M is finite
-    {
-        const float w0 = __builtin_amdgcn_exp2f(m_ref - M);
-#pragma unroll
-        for (int b = 0; b < DB; ++b) acc[b] *= w0;
-        l_tot *= w0;
-    }
-#pragma unroll
-    for (int w = 0; w < kDecWaves - 1; ++w) {
-        const float ww = __builtin_amdgcn_exp2f(mg.m[w][n] - M);  // exp2(-inf) = 0 for a wave without pages
-        l_tot += mg.l[w][n] * ww;
-#pragma unroll
-        for (int b = 0; b < DB; ++b) acc[b] += *(const f32x4*)mg.o[w][b][lane] * ww;
-    }
-
-    if (n < G) {
-        const int h = g * G + n;
-        if (it_part < 0) {
-            const float vscale = (sizeof(KT) == 1) ? a.v_scale[g] : 1.0f;
-            const float inv = vscale / l_tot;
-            uint16_t* o = (uint16_t*)a.out + ((int64_t)it_row * Hq + h) * D + 4 * r;
-#pragma unroll
-            for (int b = 0; b < DB; ++b) {
-                const bf16x2 x = __builtin_convertvector(f32x2{acc[b][0] * inv, acc[b][1] * inv}, bf16x2);
-                const bf16x2 y = __builtin_convertvector(f32x2{acc[b][2] * inv, acc[b][3] * inv}, bf16x2);
-                uint2 w;
-                w.x = __builtin_bit_cast(uint32_t, x);
-                w.y = __builtin_bit_cast(uint32_t, y);
-                *(uint2*)(o + 16 * b) = w;
-            }
-        } else {
-            float* o = a.part_o + ((int64_t)it_part * Hq + h) * D + 4 * r;
-#pragma unroll
-            for (int b = 0; b < DB; ++b) *(f32x4*)(o + 16 * b) = acc[b];
-            if (r == 0) {
-                float* ml = a.part_ml + ((int64_t)it_part * Hq + h) * 2;
-                ml[0] = M;
-                ml[1] = l_tot;
-            }
-        }
-    }
+    decode_item<KT, NBUF>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
 }
 
 // Merge of a row's splits, in split order:  M = max m_i, out = sum o_i 2^(m_i-M) / sum l_i 2^(m_i-M).

@@ -1,0 +1,92 @@
+// Step a5: the persistent mixed kernel.
+//
+// A Convertible Decoder's iteration holds HBM-bound decode rows and MFMA-bound prefill tiles at
+// once (paper Sec. 3.4: the decoder's spare compute absorbs the prefill burst).  Launching the
+// two kinds one after the other leaves the matrix cores idle during the decode scan and HBM idle
+// during the prefill tiles.  Here a fixed grid of workgroups (as many as fit on the GPU) stays
+// resident and pulls work from queues until they are empty, so both kinds are in flight on every
+// CU for the whole launch:
+//   - one queue per accelerator die (workgroup i runs on die i % n_xcd and starts on that die's
+//     queue): a prefill stream stays on one die, whose L2 then holds its K/V pages once;
+//   - the host interleaved the two kinds in each queue by their share of their own kind's cost,
+//     decode first on ties, so both kinds drain at the same pace and finish together;
+//   - a workgroup whose queue is empty helps on the next die's queue; it leaves when every queue
+//     has been seen empty (queue heads only grow, so every workgroup ends);
+//   - the last workgroup to leave puts the queue heads back to zero for the next launch.
+// The work itself is the same code as the stand-alone kernels (decode_item, prefill_tile).
+#include "ts_decode_item.h"
+#include "ts_prefill_tile.h"
+
+namespace ts {
+
+union MixedLds {
+    DecMerge mg;
+    StageLds lds;
+};
+
+template <typename KT, int NBUF>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void mixed_kernel(AttnArgs a)
+{
+    __shared__ MixedLds sh;
+    __shared__ int s_idx;
+    const int tid = threadIdx.x;
+    const int n_xcd = a.n_xcd;
+    const int32_t TS_CONSTANT* q_off = as_constant(a.q_off);
+    int x = blockIdx.x % n_xcd;
+    for (int n_empty = 0; n_empty < n_xcd;) {
+        if (tid == 0) s_idx = __hip_atomic_fetch_add(a.q_ctr + x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int idx = __builtin_amdgcn_readfirstlane(s_idx);
+        __syncthreads();                                       // s_idx may be overwritten from here on
+        const int begin = q_off[x], end = q_off[x + 1];
+        if (idx >= end - begin) {                              // this queue is (now and for ever) empty
+            ++n_empty;
+            x = (x + 1) % n_xcd;
+            continue;
+        }
+        const int32_t TS_CONSTANT* q = as_constant((const int32_t*)(a.queue + begin + idx));
+        const int kind = q[0], item = q[1], g = q[2];
+        if (kind == 0) decode_item<KT, NBUF>(a, item, g, sh.mg);
+        else prefill_tile<KT>(a, item, g, sh.lds);
+        __syncthreads();                                       // LDS is reused by the next item
+    }
+    // last workgroup out resets the counters
+    if (tid == 0) {
+        __threadfence();
+        const int done = __hip_atomic_fetch_add(a.q_ctr + n_xcd, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (done == (int)gridDim.x - 1) {
+            for (int i = 0; i <= n_xcd; ++i)
+                __hip_atomic_store(a.q_ctr + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+template <typename KT>
+static int launch_mixed_t(const AttnArgs& a, hipStream_t st)
+{
+    static int wgs[2] = {0, 0};                                // resident workgroups, per element type
+    int& n = wgs[sizeof(KT) == 1 ? 1 : 0];
+    if (n == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mixed_kernel<KT, 4>, 256, 0) != hipSuccess)
+            return (int)hipErrorUnknown;
+        n = cus * (per_cu > 0 ? per_cu : 1);
+    }
+    const int grid = n < a.n_queue ? n : a.n_queue;
+    hipLaunchKernelGGL((mixed_kernel<KT, 4>), dim3((unsigned)grid), dim3(256), 0, st, a);
+    return (int)hipGetLastError();
+}
+
+int launch_mixed(const AttnArgs& a, void* stream)
+{
+    if (a.n_queue <= 0) return (int)hipSuccess;
+    if (a.geo.D != 128 || a.geo.q_dtype != TS_BF16 || a.n_xcd <= 0 || a.n_xcd > 64) return (int)hipErrorInvalidValue;
+    hipStream_t st = (hipStream_t)stream;
+    if (a.geo.kv_dtype == TS_BF16) return launch_mixed_t<uint16_t>(a, st);
+    if (a.geo.kv_dtype == TS_FP8_E4M3) return launch_mixed_t<uint8_t>(a, st);
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace ts

@@ -106,9 +106,11 @@ static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int6
 // are launched next to each other: they walk the stream's pages almost in step, and the pages are
 // fetched from HBM about once instead of once per tile.  Streams are spread over the dies by
 // decreasing work (greedy), longest tiles of a stream first.
-static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds)
+static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds, bool build_queue)
 {
     p.pfmap.clear();
+    p.queue.clear();
+    p.q_off.clear();
     if (p.pf.empty()) return;
     struct Stream { int32_t seq; int32_t g; int64_t work; std::vector<int32_t> items; };
     std::vector<Stream> streams;
@@ -145,6 +147,39 @@ static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds)
     p.pfmap.assign(longest * xcds, PfSlot{-1, 0});
     for (int x = 0; x < xcds; ++x)
         for (size_t k = 0; k < per[x].size(); ++k) p.pfmap[k * xcds + x] = per[x][k];
+    if (!build_queue || p.dec.empty()) return;
+
+    // Mixed batch: one queue per die for the persistent kernel.  Decode items (HBM-bound) and
+    // prefill tiles (MFMA-bound) are interleaved by their share of their own kind's total cost, so
+    // that both kinds are in flight on every CU from the first to the last item and finish together.
+    std::vector<std::vector<PfSlot>> dper(xcds);
+    {
+        int64_t j = 0;
+        for (size_t i = 0; i < p.dec.size(); ++i)
+            for (int g = 0; g < Hkv; ++g, ++j) dper[j % xcds].push_back(PfSlot{(int32_t)i, g});
+    }
+    p.q_off.assign(xcds + 1, 0);
+    for (int x = 0; x < xcds; ++x) {
+        double dtot = 0, ptot = 0;
+        for (const PfSlot& d : dper[x]) dtot += p.dec[d.item].page_end - p.dec[d.item].page_begin;
+        for (const PfSlot& t : per[x]) ptot += p.pf[t.item].prefix + p.pf[t.item].tok_begin + p.pf[t.item].tok_count;
+        size_t di = 0, ti = 0;
+        double dacc = 0, pacc = 0;
+        while (di < dper[x].size() || ti < per[x].size()) {
+            const double dkey = di < dper[x].size() ? dacc / std::max(1.0, dtot) : 2.0;
+            const double pkey = ti < per[x].size() ? pacc / std::max(1.0, ptot) : 2.0;
+            if (dkey <= pkey) {                            // decode first on ties (Sec. 4.5.2)
+                const PfSlot& d = dper[x][di++];
+                dacc += p.dec[d.item].page_end - p.dec[d.item].page_begin;
+                p.queue.push_back(QItem{0, d.item, d.head_kv, 0});
+            } else {
+                const PfSlot& t = per[x][ti++];
+                pacc += p.pf[t.item].prefix + p.pf[t.item].tok_begin + p.pf[t.item].tok_count;
+                p.queue.push_back(QItem{1, t.item, t.head_kv, 0});
+            }
+        }
+        p.q_off[x + 1] = (int32_t)p.queue.size();
+    }
 }
 
 void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx_lens, int num_seqs,
@@ -212,7 +247,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     std::stable_sort(p.pf.begin(), p.pf.end(), [](const PfItem& a, const PfItem& b) {
         return (a.prefix + a.tok_begin + a.tok_count) > (b.prefix + b.tok_begin + b.tok_count);
     });
-    map_prefill_to_xcds(p, Hkv, std::max(1, opt.xcds));
+    map_prefill_to_xcds(p, Hkv, std::max(1, opt.xcds), opt.mixed_persistent);
     std::stable_sort(p.rows.begin(), p.rows.end(),
                      [](const RowItem& a, const RowItem& b) { return a.n_keys > b.n_keys; });
     p.info.n_decode_items = (int32_t)p.dec.size();
@@ -257,25 +292,34 @@ extern "C" int ts_plan_describe(const ts_attn_desc* desc, const int32_t* q_lens,
     return TS_OK;
 }
 
-extern "C" int64_t ts_plan_decode_items(const ts_attn_desc* desc, const int32_t* q_lens,
-                                        const int32_t* ctx_lens, int num_seqs, int32_t split_pages,
-                                        int32_t* items_out, int64_t capacity)
+extern "C" int64_t ts_plan_export(const ts_attn_desc* desc, const int32_t* q_lens, const int32_t* ctx_lens,
+                                  int num_seqs, int32_t split_pages, int32_t wg_slots, int which,
+                                  int32_t* out, int64_t capacity)
 {
     std::string err;
     int rc = ts::check_desc_impl(desc, &err);
     if (rc != TS_OK) return rc;
-    if (split_pages < 0 || capacity < 0 || (capacity > 0 && !items_out)) return TS_ERR_INVALID_ARG;
+    if (split_pages < 0 || wg_slots < 0 || capacity < 0 || (capacity > 0 && !out)) return TS_ERR_INVALID_ARG;
     rc = ts::validate_batch(*desc, q_lens, ctx_lens, num_seqs, &err);
     if (rc != TS_OK) return rc;
     ts::Plan plan;
     ts::PlanOptions opt;
     opt.split_pages = split_pages;
+    if (wg_slots > 0) opt.wg_slots = wg_slots;
     ts::build_plan(*desc, q_lens, ctx_lens, num_seqs, opt, &plan);
-    int64_t n = (int64_t)plan.dec.size();
-    for (int64_t i = 0; i < n && i < capacity; ++i) {
-        const ts::DecItem& it = plan.dec[(size_t)i];
-        int32_t* o = items_out + 5 * i;
-        o[0] = it.row; o[1] = it.seq; o[2] = it.n_keys; o[3] = it.page_begin; o[4] = it.page_end;
+    const void* src = nullptr;
+    int64_t n = 0, words = 0;
+    switch (which) {
+    case TS_LIST_DECODE:  src = plan.dec.data();   n = (int64_t)plan.dec.size();   words = sizeof(ts::DecItem) / 4; break;
+    case TS_LIST_COMBINE: src = plan.cmb.data();   n = (int64_t)plan.cmb.size();   words = sizeof(ts::CmbItem) / 4; break;
+    case TS_LIST_PREFILL: src = plan.pf.data();    n = (int64_t)plan.pf.size();    words = sizeof(ts::PfItem) / 4; break;
+    case TS_LIST_PFMAP:   src = plan.pfmap.data(); n = (int64_t)plan.pfmap.size(); words = sizeof(ts::PfSlot) / 4; break;
+    case TS_LIST_ROWS:    src = plan.rows.data();  n = (int64_t)plan.rows.size();  words = sizeof(ts::RowItem) / 4; break;
+    case TS_LIST_QUEUE:   src = plan.queue.data(); n = (int64_t)plan.queue.size(); words = sizeof(ts::QItem) / 4; break;
+    case TS_LIST_QOFF:    src = plan.q_off.data(); n = (int64_t)plan.q_off.size(); words = 1; break;
+    default: return TS_ERR_INVALID_ARG;
     }
+    const int64_t fit = words ? std::min<int64_t>(n, capacity / words) : 0;
+    if (fit > 0) memcpy(out, src, (size_t)(fit * words) * 4);
     return n;
 }

@@ -119,6 +119,28 @@ def test_mixed_batch_one_pass(kv):
     assert e1 == e2
 
 
+@pytest.mark.parametrize("persistent", [1, 0])
+def test_mixed_batch_persistent_and_separate_launches(persistent):
+    shape = AttnShape(32, 8, 128, "bf16", "bf16")
+    q = [1] * 40 + [300, 129, 1000] + [1] * 17
+    rng = np.random.default_rng(5)
+    c = list(rng.integers(1, 3000, size=40)) + [300 + 77, 129, 1000 + 640] + list(rng.integers(1, 600, size=17))
+    b = make_batch(shape, q, c, seed=44, pool_rule=1.25, value_mult=0.5)
+    check(b, options={"mixed_persistent": persistent})
+    # a second pass on the same context must find the queue counters reset
+    import paper_2512_03416_amd as ts
+    g = gpu()
+    b = g.to_dev(make_batch(shape, q, c, seed=44, pool_rule=1.25, value_mult=0.5))
+    ctx = ts.Context(g.make_desc(b))
+    ctx.set_option("mixed_persistent", persistent)
+    outs = []
+    for _ in range(3):
+        o, _, _ = g.run_batch(b, ctx=ctx)
+        outs.append(o)
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    ctx.close()
+
+
 def test_prefill_generic_path_agrees():
     shape = AttnShape(8, 2, 128, "bf16", "bf16")
     b = make_batch(shape, [150, 1], [190, 50], seed=43, value_mult=0.5)
@@ -256,6 +278,32 @@ def test_run_to_run_identical_and_default_scale():
     b.sm_scale = 0.0                       # <= 0 selects 1/sqrt(D)
     o3, _, _ = g.run_batch(b, options={"decode_split_pages": 8})
     assert np.array_equal(o1, o3)
+
+
+def test_context_follows_stream_switch():
+    """Calls of one context may move to another stream without a host synchronisation in between:
+    the library orders the new stream behind its previous call (its work lists share one buffer)."""
+    import paper_2512_03416_amd as ts
+    g = gpu()
+    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+    b = make_batch(shape, [1, 300, 1, 64], [900, 700, 33, 64], seed=64, value_mult=0.5)
+    print("[case] stream switch", flush=True)
+    ref, rk, rv = oracle.run_batch(b)
+    b = g.to_dev(b)
+    ctx = ts.Context(g.make_desc(b))
+    kc, vc = g.new_caches(b)
+    bt = torch.from_numpy(b.block_table).cuda()
+    out = torch.zeros_like(b.q)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    pre = b.prefix_lens
+    ctx.kv_append(b.k_prefix, b.v_prefix, kc, vc, None, None, bt, pre, pre, stream=s1)
+    ctx.mixed_paged_attention(b.q, b.k_new, b.v_new, kc, vc, None, None, bt, b.q_lens, b.ctx_lens, b.sm_scale, out,
+                              stream=s2)
+    torch.cuda.synchronize()
+    assert same_bytes(g.cache_raw(kc, "bf16"), rk) and same_bytes(g.cache_raw(vc, "bf16"), rv)
+    assert float(np.max(np.abs(out.double().cpu().numpy() - ref))) <= 2e-2
+    ctx.close()
 
 
 def test_token_velocity_counters():
