@@ -102,6 +102,27 @@ def cpu_baseline(batch, out_gpu, max_seqs: int, row_stride: int):
                 max_abs_err_vs_gpu=err)
 
 
+def recorded_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None when there is none
+    for this kernel and workload or the kernel sources changed since it was taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload.split('_')[0]}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    kv = dict(l.strip().split("=", 1) for l in open(path) if "=" in l and not l.startswith("#"))
+    if kv.get("workload") != workload:
+        return None
+    h = hashlib.sha256()
+    for f in kv.get("sources", "").split(","):
+        fp = os.path.join(ROOT, "paper_2512_03416_amd", "csrc", f)
+        if not os.path.exists(fp):
+            return None
+        h.update(open(fp, "rb").read())
+    if h.hexdigest() != kv.get("digest"):
+        return None
+    return int(kv["fetch_bytes"]) + int(kv["write_bytes"])
+
+
 def calibrate(nbytes: int = 2 << 30):
     import torch
     import paper_2512_03416_amd as ts
@@ -136,6 +157,8 @@ def main():
     ap.add_argument("--split-pages", type=int, default=0)
     ap.add_argument("--prefetch-tiles", type=int, default=0)
     ap.add_argument("--xcd-count", type=int, default=0)
+    ap.add_argument("--time-every", type=int, default=4,
+                    help="record HIP events around the kernels of every N-th step of the timed region")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -193,7 +216,7 @@ def main():
     ms_plain = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # timed region: HIP events on the launch stream around every kernel launch
-    ctx.set_option("kernel_timing", 1)
+    ctx.set_option("kernel_timing", args.time_every)
     ctx.kernel_times(reset=True)
     ctx.token_velocity(reset=True)
     torch.cuda.synchronize()
@@ -208,7 +231,8 @@ def main():
     ms_step = elapsed * 1e3 / args.steps
     T = batch.total_q
     value = T * args.steps / elapsed
-    log(f"[bench] {ms_step:.4f} ms/step with kernel events, {ms_plain:.4f} ms/step without; kernels: " +
+    log(f"[bench] {ms_step:.4f} ms/step with kernel events on every {args.time_every}. step, {ms_plain:.4f} "
+        f"ms/step without; kernels: " +
         ", ".join(f"{k} {v[1] * 1e3:.1f} us x{v[0]}" for k, v in ktimes.items() if v[0]))
     log(f"[bench] token velocity counters: prefill {vel.prefill_tok_per_s:.0f} tok/s, decode "
         f"{vel.decode_tok_per_s:.0f} tok/s over {vel.window_s:.3f} s ({vel.passes} passes)")
@@ -220,7 +244,8 @@ def main():
     if dominant == "decode":
         ach = work["decode_bytes"] / (dom_ms * 1e-3) / 1e9
         roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
-                    traffic=None, kernel="decode_kernel", kernel_ms=dom_ms,
+                    traffic=recorded_traffic("decode_kernel", batch.name), kernel="decode_kernel",
+                    kernel_ms=dom_ms, kernel_launches_timed=ktimes[dominant][0],
                     algorithmic_bytes=work["decode_bytes"])
     elif dominant == "prefill":
         ach = work["prefill_flops"] / (dom_ms * 1e-3) / 1e12
@@ -267,8 +292,8 @@ def main():
         log(f"[bench] calibration: {result['calibration']}")
     if not args.no_cpu_baseline:
         out_host = out.double().cpu().numpy()
-        n = args.cpu_seqs or {"cfg2": 128, "cfg4": 40, "cfg5": 24, "cfg3": 4, "cfg1": 8}[args.workload]
-        stride = {"cfg4": 8, "cfg5": 64, "cfg3": 8}.get(args.workload, 1)
+        n = args.cpu_seqs or {"cfg2": 256, "cfg4": 132, "cfg5": 64, "cfg3": 8, "cfg1": 8}[args.workload]
+        stride = {"cfg4": 16, "cfg5": 256, "cfg3": 8}.get(args.workload, 1)
         result["cpu_baseline"] = cpu_baseline(batch, out_host, n, stride)
         log(f"[bench] oracle: {result['cpu_baseline']}")
     print(json.dumps(result), flush=True)

@@ -157,12 +157,14 @@ const char *ts_last_error(const ts_ctx *ctx);
  *   "mixed_persistent"    1 (default) = decode items and prefill tiles of a mixed batch share one
  *                         persistent launch; 0 = decode kernel, then prefill kernel
  *   "xcd_count"           accelerator dies the prefill launch order is laid out for (default 8)
- *   "kernel_timing"       1 = record HIP events around every launch (see ts_kernel_times)
+ *   "kernel_timing"       N > 0 = record HIP events around the launches of every N-th call
+ *                         (see ts_kernel_times), 0 = off
  * Unknown names give TS_ERR_INVALID_ARG. */
 int ts_set_option(ts_ctx *ctx, const char *name, int64_t value);
 
 /* Optional per-kernel timing with HIP events recorded on the caller's stream around each launch
- * (enable with ts_set_option(ctx, "kernel_timing", 1); costs two event records per launch).
+ * (enable with ts_set_option(ctx, "kernel_timing", N): every N-th call is timed; two event records
+ * per timed launch).
  * ts_kernel_times waits for the recorded events, then reports, per kernel, the number of timed
  * launches and their mean duration in milliseconds since the last reset. */
 enum { TS_K_APPEND = 0, TS_K_DECODE = 1, TS_K_COMBINE = 2, TS_K_PREFILL = 3, TS_K_ROWS = 4, TS_K_MIXED = 5,

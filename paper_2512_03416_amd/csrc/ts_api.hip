@@ -61,7 +61,9 @@ struct ts_ctx {
     hipStream_t last_stream = nullptr;
     bool have_work = false;
     // optional per-kernel timing
-    bool timing = false;
+    int timing = 0;                    // 0 = off, N = time the launches of every N-th pass
+    uint64_t timing_pass = 0;
+    bool timing_now = false;
     struct Timed { int which; hipEvent_t a, b; };
     std::vector<Timed> timed;          // recorded, not yet read
     std::vector<hipEvent_t> ev_pool;   // spare events
@@ -203,7 +205,7 @@ hipEvent_t take_event(ts_ctx* c)
 template <typename F>
 int timed_launch(ts_ctx* c, int which, bool has_work, hipStream_t st, F&& launch)
 {
-    if (!c->timing || !has_work || c->timed.size() >= 65536) return launch();
+    if (!c->timing_now || !has_work || c->timed.size() >= 65536) return launch();
     hipEvent_t ea = take_event(c), eb = take_event(c);
     if (!ea || !eb) return launch();
     (void)hipEventRecord(ea, st);
@@ -382,7 +384,9 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         return TS_OK;
     }
     if (!strcmp(name, "kernel_timing")) {
-        c->timing = value != 0;
+        if (value < 0 || value > 1024) return fail(c, TS_ERR_INVALID_ARG, "kernel_timing must be 0..1024");
+        c->timing = (int)value;
+        c->timing_pass = 0;
         return TS_OK;
     }
     return fail(c, TS_ERR_INVALID_ARG, std::string("unknown option: ") + name);
@@ -398,6 +402,7 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     int rc = check_common(c, k_cache, v_cache, k_scale, v_scale, block_table, q_lens, ctx_lens, num_seqs);
     if (rc != TS_OK) return rc;
     DeviceGuard guard(c->device);
+    c->timing_now = c->timing > 0 && (c->timing_pass++ % (uint64_t)c->timing) == 0;
     PlanOptions opt = c->opt;
     build_plan(c->desc, q_lens, ctx_lens, num_seqs, opt, &c->plan);
     if (c->plan.info.total_tokens == 0) return TS_OK;
@@ -434,6 +439,7 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
         return fail(c, TS_ERR_INVALID_ARG, "k_new and v_new must both be given or both be NULL");
     if (!(sm_scale == sm_scale)) return fail(c, TS_ERR_INVALID_ARG, "sm_scale is NaN");
     DeviceGuard guard(c->device);
+    c->timing_now = c->timing > 0 && (c->timing_pass++ % (uint64_t)c->timing) == 0;
     if (desc_uses_mfma(c->desc)) {
         const int slots = decode_resident_workgroups(c->desc.kv_dtype);
         if (slots > 0) c->opt.wg_slots = slots;
