@@ -157,6 +157,8 @@ def main():
     ap.add_argument("--split-pages", type=int, default=0)
     ap.add_argument("--prefetch-tiles", type=int, default=0)
     ap.add_argument("--xcd-count", type=int, default=0)
+    ap.add_argument("--no-persistent", action="store_true",
+                    help="mixed batches: decode kernel then prefill kernel instead of the persistent launch")
     ap.add_argument("--time-every", type=int, default=4,
                     help="record HIP events around the kernels of every N-th step of the timed region")
     args = ap.parse_args()
@@ -184,6 +186,8 @@ def main():
         ctx.set_option("decode_prefetch_tiles", args.prefetch_tiles)
     if args.xcd_count:
         ctx.set_option("xcd_count", args.xcd_count)
+    if args.no_persistent:
+        ctx.set_option("mixed_persistent", 0)
     nbytes = ts.cache_bytes(desc)
     kc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
     vc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")

@@ -21,14 +21,14 @@ namespace ts {
 
 union MixedLds {
     DecMerge mg;
-    StageLds lds;
+    StageLds lds[2];
 };
 
 template <typename KT, int NBUF>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void mixed_kernel(AttnArgs a)
 {
     __shared__ MixedLds sh;
-    __shared__ int s_idx;
+    int& s_idx = *reinterpret_cast<int*>(&sh);             // LDS is idle between two items
     const int tid = threadIdx.x;
     const int n_xcd = a.n_xcd;
     const int32_t TS_CONSTANT* q_off = as_constant(a.q_off);

@@ -6,7 +6,7 @@ namespace ts {
 template <typename KT>
 __global__ __launch_bounds__(256) void prefill_kernel(AttnArgs a)
 {
-    __shared__ StageLds lds;
+    __shared__ StageLds lds[2];
     const int32_t TS_CONSTANT* slot = as_constant((const int32_t*)(a.pfmap + blockIdx.x));
     const int item_idx = slot[0], g = slot[1];
     if (item_idx < 0) return;                               // padding of the die-aware launch order

@@ -36,6 +36,8 @@ __device__ __forceinline__ uint2 fp8x4_bf16x4(uint32_t w)
     return r;
 }
 
+__device__ __forceinline__ float fmax3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
+
 // keep the first n (0..8) 16-bit elements of a 16-byte vector (plain register arithmetic: local
 // arrays here end up in scratch memory and serialise the prefetch)
 __device__ __forceinline__ uint32_t mask16(int left) { return left >= 2 ? 0xffffffffu : (left == 1 ? 0xffffu : 0u); }
@@ -71,15 +73,16 @@ __device__ __forceinline__ int v_lds_offset(int page_in_stage, int dim, int r)
 }
 
 // ---- bf16 cache: each thread copies 16 bytes of every page's K tile and V tile ------------------
-__device__ __forceinline__ void fetch_page_bf16(uint4& k, uint4& v, const AttnArgs& a, const int32_t* bt,
-                                                int page_idx, int last_page, int g, int tid)
+__device__ __forceinline__ void fetch_page_bf16(uint4& k, uint4& v, const AttnArgs& a,
+                                                const int32_t TS_CONSTANT* bt, int page_idx, int last_page,
+                                                int g, int tid)
 {
     const int64_t tile = (int64_t)bt[min(page_idx, last_page)] * a.geo.Hkv + g;
     k = *(const uint4*)((const char*)a.k_cache + tile * 4096 + tid * 16);
     v = *(const uint4*)((const char*)a.v_cache + tile * 4096 + tid * 16);
 }
-__device__ __forceinline__ void stage_fetch(Stage<uint16_t>& st, const AttnArgs& a, const int32_t* bt, int kv0,
-                                            int last_page, int g, int tid)
+__device__ __forceinline__ void stage_fetch(Stage<uint16_t>& st, const AttnArgs& a,
+                                            const int32_t TS_CONSTANT* bt, int kv0, int last_page, int g, int tid)
 {
     const int p0 = kv0 / kPage;
     fetch_page_bf16(st.k0, st.v0, a, bt, p0 + 0, last_page, g, tid);
@@ -106,15 +109,16 @@ __device__ __forceinline__ void stage_store(const Stage<uint16_t>& st, StageLds&
 }
 
 // ---- fp8 cache: 4 pages x 2048 bytes = 512 chunks of 16 bytes, two per thread, widened to bf16 ----
-__device__ __forceinline__ void fetch_chunk_fp8(uint4& k, uint4& v, const AttnArgs& a, const int32_t* bt,
-                                                int kv0, int ci, int last_page, int g)
+__device__ __forceinline__ void fetch_chunk_fp8(uint4& k, uint4& v, const AttnArgs& a,
+                                                const int32_t TS_CONSTANT* bt, int kv0, int ci, int last_page, int g)
 {
-    const int64_t tile = (int64_t)bt[min(kv0 / kPage + (ci >> 7), last_page)] * a.geo.Hkv + g;
+    const int pg = __builtin_amdgcn_readfirstlane(ci >> 7);       // uniform within a wave
+    const int64_t tile = (int64_t)bt[min(kv0 / kPage + pg, last_page)] * a.geo.Hkv + g;
     k = *(const uint4*)((const char*)a.k_cache + tile * 2048 + (ci & 127) * 16);
     v = *(const uint4*)((const char*)a.v_cache + tile * 2048 + (ci & 127) * 16);
 }
-__device__ __forceinline__ void stage_fetch(Stage<uint8_t>& st, const AttnArgs& a, const int32_t* bt, int kv0,
-                                            int last_page, int g, int tid)
+__device__ __forceinline__ void stage_fetch(Stage<uint8_t>& st, const AttnArgs& a,
+                                            const int32_t TS_CONSTANT* bt, int kv0, int last_page, int g, int tid)
 {
     fetch_chunk_fp8(st.k0, st.v0, a, bt, kv0, tid, last_page, g);
     fetch_chunk_fp8(st.k1, st.v1, a, bt, kv0, 256 + tid, last_page, g);
@@ -142,9 +146,10 @@ __device__ __forceinline__ void stage_store(const Stage<uint8_t>& st, StageLds& 
 }
 
 // One causal tile for KV head g, executed by a workgroup of 256 threads.  All threads must call
-// it; every stage ends with a workgroup barrier, so lds may be reused right after it returns.
+// it; every stage ends with a workgroup barrier, so the two stage buffers lds2[0..1] may be reused
+// right after it returns.
 template <typename KT>
-__device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, int g, StageLds& lds)
+__device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, int g, StageLds* lds2)
 {
     constexpr int D = 128, KB = 4, DB = 8, NT = 2;
     const PfItem it = a.pf[item_idx];
@@ -176,23 +181,33 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     const int wave_max_q = it.prefix + it.tok_begin + min((32 * wave + 31) / G, it.tok_count - 1);
     const int kv_hi = it.prefix + it.tok_begin + it.tok_count;     // keys [0, kv_hi) matter to this tile
     const int last_page = (it.ctx_len - 1) / kPage;
-    const int32_t* bt = a.block_table + (int64_t)it.seq * a.geo.max_pages;
+    const int32_t TS_CONSTANT* bt = as_constant(a.block_table) + (int64_t)it.seq * a.geo.max_pages;
 
     f32x4 acc[DB][NT];
 #pragma unroll
     for (int b = 0; b < DB; ++b)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[b][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_ref[NT] = {-INFINITY, -INFINITY}, l[NT] = {0.f, 0.f};
+    // running sums of the weights come out of the matrix cores too: an all-ones A operand makes
+    // every row of the product the column sum of P^T, i.e. the softmax denominator of the lane's row
+    f32x4 accl[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) accl[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const bf16x8 ones = u4_bf16x8(make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u));
+    float m_ref[NT] = {-INFINITY, -INFINITY};
 
+    // Two LDS stage buffers: while stage i is multiplied out of one, stage i+1 (fetched into
+    // registers during stage i-1 and i) is written into the other, so a stage costs one barrier.
     Stage<KT> st;
     stage_fetch(st, a, bt, 0, last_page, g, tid);
-    for (int kv0 = 0; kv0 < kv_hi; kv0 += kStageTok) {
-        stage_store(st, lds, kv0, it.ctx_len, tid);
-        __syncthreads();
-        if (kv0 + kStageTok < kv_hi) stage_fetch(st, a, bt, kv0 + kStageTok, last_page, g, tid);
+    stage_store(st, lds2[0], 0, it.ctx_len, tid);
+    if (kStageTok < kv_hi) stage_fetch(st, a, bt, kStageTok, last_page, g, tid);
+    __syncthreads();
+    int buf = 0;
+    for (int kv0 = 0; kv0 < kv_hi; kv0 += kStageTok, buf ^= 1) {
+        const StageLds& lds = lds2[buf];
         if (kv0 <= wave_max_q) {                            // wave-uniform: some row sees this stage
-            // ---- S^T = K Q^T -------------------------------------------------------------
+            // ---- S^T = K Q^T (raw scores; the softmax scale is folded into the exponent) ----
             f32x4 s[4][NT];
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt) {
@@ -206,7 +221,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
 #pragma unroll
                     for (int b = 0; b < KB; ++b)
                         x = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak[b], qb[nt][b], x, 0, 0, 0);
-                    s[tt][nt] = x * c;
+                    s[tt][nt] = x;
                 }
             }
             // ---- causal mask (only stages that reach the diagonal) ------------------------
@@ -219,15 +234,18 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
                         for (int i = 0; i < 4; ++i)
                             if (kv0 + tt * 16 + 4 * r + i > qpos[nt]) s[tt][nt][i] = -INFINITY;
             }
-            // ---- online softmax, reference maximum raised lazily ---------------------------
+            // ---- online softmax, reference maximum (in scaled log2 units) raised lazily -----
             float lmax[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                float x = -INFINITY;
+                float x = __builtin_fmaxf(s[0][nt][0], s[0][nt][1]);
+                x = fmax3(x, s[0][nt][2], s[0][nt][3]);
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt)
-                    x = fmaxf(x, fmaxf(fmaxf(s[tt][nt][0], s[tt][nt][1]), fmaxf(s[tt][nt][2], s[tt][nt][3])));
-                lmax[nt] = x;
+                for (int tt = 1; tt < 4; ++tt) {
+                    x = fmax3(x, s[tt][nt][0], s[tt][nt][1]);
+                    x = fmax3(x, s[tt][nt][2], s[tt][nt][3]);
+                }
+                lmax[nt] = x * c;                          // c > 0: the maximum commutes with the scale
             }
             if (__any(lmax[0] > m_ref[0] + kRaisePf || lmax[1] > m_ref[1] + kRaisePf)) {
 #pragma unroll
@@ -238,31 +256,36 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
                     const float alpha = __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
 #pragma unroll
                     for (int b = 0; b < DB; ++b) acc[b][nt] *= alpha;
-                    l[nt] *= alpha;
+                    accl[nt] *= alpha;
                     m_ref[nt] = m_new;
                 }
             }
             bf16x8 pop[2][NT];                             // P^T operands: [page pair][row tile]
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
+                const float nm = -m_ref[nt];
 #pragma unroll
                 for (int pp = 0; pp < 2; ++pp) {
                     uint32_t w[4];
 #pragma unroll
                     for (int ab = 0; ab < 2; ++ab) {
                         const f32x4 x = s[2 * pp + ab][nt];
-                        const float p0 = __builtin_amdgcn_exp2f(x[0] - m_ref[nt]);
-                        const float p1 = __builtin_amdgcn_exp2f(x[1] - m_ref[nt]);
-                        const float p2 = __builtin_amdgcn_exp2f(x[2] - m_ref[nt]);
-                        const float p3 = __builtin_amdgcn_exp2f(x[3] - m_ref[nt]);
-                        l[nt] += (p0 + p1) + (p2 + p3);
+                        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[0], c, nm));
+                        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[1], c, nm));
+                        const float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[2], c, nm));
+                        const float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[3], c, nm));
                         w[2 * ab] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p0, p1}, bf16x2));
                         w[2 * ab + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p2, p3}, bf16x2));
                     }
                     pop[pp][nt] = u4_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
                 }
             }
-            // ---- O^T += V^T P^T ---------------------------------------------------------------
+            // ---- O^T += V^T P^T (and the row sums) -----------------------------------------------
+#pragma unroll
+            for (int pp = 0; pp < 2; ++pp)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    accl[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pop[pp][nt], accl[nt], 0, 0, 0);
 #pragma unroll
             for (int pp = 0; pp < 2; ++pp)
 #pragma unroll
@@ -273,14 +296,19 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
                         acc[b][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pop[pp][nt], acc[b][nt], 0, 0, 0);
                 }
         }
+        if (kv0 + kStageTok < kv_hi) {
+            // the other buffer was last read during the previous stage, which every wave left
+            // through the barrier below
+            stage_store(st, lds2[buf ^ 1], kv0 + kStageTok, it.ctx_len, tid);
+            if (kv0 + 2 * kStageTok < kv_hi) stage_fetch(st, a, bt, kv0 + 2 * kStageTok, last_page, g, tid);
+        }
         __syncthreads();
     }
 
     const float vscale = (sizeof(KT) == 1) ? a.v_scale[g] : 1.0f;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        float lt = l[nt] + __shfl_xor(l[nt], 16, 64);
-        lt += __shfl_xor(lt, 32, 64);
+        const float lt = accl[nt][0];
         if (!row_ok[nt]) continue;
         const float inv = vscale / lt;
         uint16_t* o = (uint16_t*)a.out +
