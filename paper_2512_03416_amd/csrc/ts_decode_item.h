@@ -108,19 +108,20 @@ template <typename KT> __device__ __forceinline__ int q_dim0(int b, int r)
 // fits one item is finished here (no partial ever goes to HBM: stores into the middle of a saturated
 // read stream were measured to cost ~10x their byte share); only rows longer than one workgroup's
 // fair share are cut into several items whose partials go through combine_kernel.
-constexpr int kDecWaves = 4;
+constexpr int kDecWaves = 4;               // stand-alone decode kernel; the mixed kernel uses 8
 
+template <int WAVES>
 struct DecMerge {                          // LDS image of the non-leading waves' state
-    float o[kDecWaves - 1][8][64][4];      // acc[b] of every lane
-    float m[kDecWaves - 1][16];
-    float l[kDecWaves - 1][16];
+    float o[WAVES - 1][8][64][4];          // acc[b] of every lane
+    float m[WAVES - 1][16];
+    float l[WAVES - 1][16];
 };
 
-// One decode item for KV head g, executed by a workgroup of kDecWaves waves.  All waves must call
+// One decode item for KV head g, executed by a workgroup of WAVES waves.  All waves must call
 // it; it contains one workgroup barrier, and the caller must place another barrier before mg is
 // reused.
-template <typename KT, int NBUF>
-__device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int g, DecMerge& mg)
+template <typename KT, int NBUF, int WAVES>
+__device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int g, DecMerge<WAVES>& mg)
 {
     constexpr int D = 128, KB = 4, DB = 8;
     const int32_t TS_CONSTANT* itp = as_constant((const int32_t*)(a.dec + item_idx));
@@ -131,8 +132,8 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
     const int lane = threadIdx.x & 63, r = lane >> 4, n = lane & 15;
     const int Hq = a.geo.Hq, Hkv = a.geo.Hkv, G = a.geo.G;
 
-    // this wave's pages: it_pb + wave + kDecWaves * k, k = 0 .. np-1
-    const int np = max(0, (it_pe - it_pb - wave + kDecWaves - 1) / kDecWaves);
+    // this wave's pages: it_pb + wave + WAVES * k, k = 0 .. np-1
+    const int np = max(0, (it_pe - it_pb - wave + WAVES - 1) / WAVES);
     const int32_t TS_CONSTANT* bt = as_constant(a.block_table) + (int64_t)it_seq * a.geo.max_pages + it_pb + wave;
 
     f32x4 acc[DB];
@@ -160,7 +161,7 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
         auto fetch = [&](KVTile<KT>& t) {
             load_tile(t, kc, vc, (int64_t)next_id * Hkv + g, lane);
             next_k = min(next_k + 1, np - 1);                     // past the end: stay on the last page
-            next_id = bt[kDecWaves * next_k];
+            next_id = bt[WAVES * next_k];
         };
         KVTile<KT> buf[NBUF];
 #pragma unroll
@@ -172,7 +173,7 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
                 const int k = base + j;
                 if (k < np) {                                     // wave-uniform
                     const KVTile<KT>& t = buf[j];
-                    const int page = it_pb + wave + kDecWaves * k;
+                    const int page = it_pb + wave + WAVES * k;
                     f32x4 s = qk_tile(t, qb);
                     float t0 = s[0] * c, t1 = s[1] * c, t2 = s[2] * c, t3 = s[3] * c;
                     const int nvalid = it_keys - (page * kPage + 4 * r);   // tokens tok0 .. tok0+3 valid if < nvalid
@@ -226,7 +227,7 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
     if (wave != 0) return;                                        // (leaves this function only)
     float M = m_ref;
 #pragma unroll
-    for (int w = 0; w < kDecWaves - 1; ++w) M = fmaxf(M, mg.m[w][n]);
+    for (int w = 0; w < WAVES - 1; ++w) M = fmaxf(M, mg.m[w][n]);
     // wave 0 always holds the item's first page, so M is finite
     {
         const float w0 = __builtin_amdgcn_exp2f(m_ref - M);
@@ -235,7 +236,7 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
         l_tot *= w0;
     }
 #pragma unroll
-    for (int w = 0; w < kDecWaves - 1; ++w) {
+    for (int w = 0; w < WAVES - 1; ++w) {
         const float ww = __builtin_amdgcn_exp2f(mg.m[w][n] - M);  // exp2(-inf) = 0 for a wave without pages
         l_tot += mg.l[w][n] * ww;
 #pragma unroll

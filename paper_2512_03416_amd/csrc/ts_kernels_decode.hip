@@ -8,8 +8,8 @@ namespace ts {
 template <typename KT, int NBUF>
 __global__ __launch_bounds__(64 * kDecWaves) void decode_kernel(AttnArgs a)
 {
-    __shared__ DecMerge mg;
-    decode_item<KT, NBUF>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
+    __shared__ DecMerge<kDecWaves> mg;
+    decode_item<KT, NBUF, kDecWaves>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
 }
 
 // Merge of a row's splits, in split order:  M = max m_i, out = sum o_i 2^(m_i-M) / sum l_i 2^(m_i-M).

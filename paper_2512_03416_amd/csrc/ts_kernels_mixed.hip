@@ -20,12 +20,12 @@
 namespace ts {
 
 union MixedLds {
-    DecMerge mg;
-    StageLds lds[2];
+    DecMerge<kPfWaves> mg;
+    PfLds lds;
 };
 
 template <typename KT, int NBUF>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void mixed_kernel(AttnArgs a)
+__global__ __launch_bounds__(kPfThreads) void mixed_kernel(AttnArgs a)
 {
     __shared__ MixedLds sh;
     int& s_idx = *reinterpret_cast<int*>(&sh);             // LDS is idle between two items
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void m
         }
         const int32_t TS_CONSTANT* q = as_constant((const int32_t*)(a.queue + begin + idx));
         const int kind = q[0], item = q[1], g = q[2];
-        if (kind == 0) decode_item<KT, NBUF>(a, item, g, sh.mg);
+        if (kind == 0) decode_item<KT, NBUF, kPfWaves>(a, item, g, sh.mg);
         else prefill_tile<KT>(a, item, g, sh.lds);
         __syncthreads();                                       // LDS is reused by the next item
     }
@@ -70,12 +70,12 @@ static int launch_mixed_t(const AttnArgs& a, hipStream_t st)
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mixed_kernel<KT, 4>, 256, 0) != hipSuccess)
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mixed_kernel<KT, 4>, kPfThreads, 0) != hipSuccess)
             return (int)hipErrorUnknown;
         n = cus * (per_cu > 0 ? per_cu : 1);
     }
     const int grid = n < a.n_queue ? n : a.n_queue;
-    hipLaunchKernelGGL((mixed_kernel<KT, 4>), dim3((unsigned)grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((mixed_kernel<KT, 4>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
     return (int)hipGetLastError();
 }
 

@@ -23,7 +23,7 @@ bool desc_uses_mfma(const ts_attn_desc& d)
 int32_t prefill_tile_tokens(const ts_attn_desc& d)
 {
     int G = d.num_q_heads / d.num_kv_heads;
-    return 128 / G;     // 128 query rows (token, head-in-group) per tile
+    return 256 / G;     // 256 query rows (token, head-in-group) per tile
 }
 
 static int check_desc_impl(const ts_attn_desc* d, std::string* err)

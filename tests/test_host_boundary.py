@@ -71,8 +71,8 @@ def test_plan_counts_and_decode_items_cover_every_page_once():
         assert info.total_tokens == ql.sum() and info.decode_tokens == n_dec
         assert info.prefill_tokens == 337
         assert info.n_generic_rows == 0
-        assert info.tile_tokens == 32
-        assert info.n_prefill_tiles == -(-37 // 32) + -(-300 // 32)
+        assert info.tile_tokens == 64
+        assert info.n_prefill_tiles == -(-37 // 64) + -(-300 // 64)
         items = ts.plan_decode_items(D(), ql, ctx, split)
         assert len(items) == info.n_decode_items
         cover = {}
