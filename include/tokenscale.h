@@ -210,9 +210,12 @@ int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int3
  *   TS_LIST_ROWS    (row, seq, n_keys, 0)
  *   TS_LIST_QUEUE   (kind 0 decode / 1 prefill, item, kv_head, 0)   per-die queues, concatenated
  *   TS_LIST_QOFF    (offset)                                        n_dies + 1 offsets into the queue
+ *   TS_LIST_APPEND  (seq, page_index, slot_lo, slot_hi, row_of_slot_0, 0, 0, 0)   page-wise append work
+ *   TS_LIST_APPEND_ROWS (row, seq)                                  tokens appended one by one
  * wg_slots = 0 uses the default number of resident decode workgroups. */
 enum { TS_LIST_DECODE = 0, TS_LIST_COMBINE = 1, TS_LIST_PREFILL = 2, TS_LIST_PFMAP = 3, TS_LIST_ROWS = 4,
-       TS_LIST_QUEUE = 5, TS_LIST_QOFF = 6 };
+       TS_LIST_QUEUE = 5, TS_LIST_QOFF = 6, TS_LIST_APPEND = 7,
+       TS_LIST_APPEND_ROWS = 8 };
 int64_t ts_plan_export(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
                        int num_seqs, int32_t split_pages, int32_t wg_slots, int which,
                        int32_t *out, int64_t capacity);

@@ -150,7 +150,7 @@ int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out)
 }
 
 struct WorkLayout {
-    size_t seqs, dec, cmb, pf, pfmap, rows, queue, q_off, total;
+    size_t seqs, dec, cmb, pf, pfmap, rows, queue, q_off, apt, apr, total;
 };
 
 WorkLayout layout_of(const Plan& p)
@@ -165,6 +165,8 @@ WorkLayout layout_of(const Plan& p)
     w.rows = o; o = align16(o + p.rows.size() * sizeof(RowItem));
     w.queue = o; o = align16(o + p.queue.size() * sizeof(QItem));
     w.q_off = o; o = align16(o + p.q_off.size() * sizeof(int32_t));
+    w.apt = o; o = align16(o + p.apt.size() * sizeof(AppTile));
+    w.apr = o; o = align16(o + p.apr.size() * sizeof(AppRow));
     w.total = o;
     return w;
 }
@@ -187,6 +189,8 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
     if (!p.rows.empty()) memcpy(h + w.rows, p.rows.data(), p.rows.size() * sizeof(RowItem));
     if (!p.queue.empty()) memcpy(h + w.queue, p.queue.data(), p.queue.size() * sizeof(QItem));
     if (!p.q_off.empty()) memcpy(h + w.q_off, p.q_off.data(), p.q_off.size() * sizeof(int32_t));
+    if (!p.apt.empty()) memcpy(h + w.apt, p.apt.data(), p.apt.size() * sizeof(AppTile));
+    if (!p.apr.empty()) memcpy(h + w.apr, p.apr.data(), p.apr.size() * sizeof(AppRow));
     TS_HIP(c, hipMemcpyAsync(c->d_work, h, w.total, hipMemcpyHostToDevice, st));
     TS_HIP(c, hipEventRecord(slot->ev, st));
     slot->pending = true;
@@ -345,7 +349,9 @@ extern "C" int ts_reserve(ts_ctx* c, int64_t max_tokens, int64_t max_seqs, int64
     const size_t bytes = ((size_t)max_seqs + 1) * sizeof(SeqMeta) + items * (sizeof(DecItem) + sizeof(CmbItem)) +
                          (size_t)max_tokens * (sizeof(RowItem) + sizeof(PfItem)) +
                          (size_t)max_tokens * c->desc.num_kv_heads * 2 * (sizeof(PfSlot) + sizeof(QItem)) +
-                         items * c->desc.num_kv_heads * sizeof(QItem) + 4096;
+                         items * c->desc.num_kv_heads * sizeof(QItem) +
+                         ((size_t)max_tokens / 8 + 2 * (size_t)max_seqs) * sizeof(AppTile) +
+                         (size_t)max_tokens * sizeof(AppRow) + 4096;
     int rc = ensure_work(c, bytes);
     if (rc != TS_OK) return rc;
     for (int i = 0; i < kRing; ++i) {
@@ -425,6 +431,8 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     a.k_scale = k_scale; a.v_scale = v_scale; a.block_table = block_table;
     a.seqs = (const SeqMeta*)(c->d_work + w.seqs);
     a.num_seqs = num_seqs; a.total_tokens = (int32_t)c->plan.info.total_tokens;
+    a.apt = (const AppTile*)(c->d_work + w.apt); a.n_apt = (int32_t)c->plan.apt.size();
+    a.apr = (const AppRow*)(c->d_work + w.apr); a.n_apr = (int32_t)c->plan.apr.size();
     hipError_t e = (hipError_t)timed_launch(c, TS_K_APPEND, true, st, [&] { return launch_append(a, stream); });
     if (e != hipSuccess) return hip_fail(c, e, "append launch");
     return mark_work_done(c, st);
@@ -468,6 +476,8 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
         ap.k_scale = k_scale; ap.v_scale = v_scale; ap.block_table = block_table;
         ap.seqs = (const SeqMeta*)(c->d_work + w.seqs);
         ap.num_seqs = num_seqs; ap.total_tokens = (int32_t)p.info.total_tokens;
+        ap.apt = (const AppTile*)(c->d_work + w.apt); ap.n_apt = (int32_t)p.apt.size();
+        ap.apr = (const AppRow*)(c->d_work + w.apr); ap.n_apr = (int32_t)p.apr.size();
         hipError_t e = (hipError_t)timed_launch(c, TS_K_APPEND, true, st, [&] { return launch_append(ap, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "append launch");
     }

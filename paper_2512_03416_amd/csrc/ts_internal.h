@@ -59,6 +59,20 @@ struct QItem {            // entry of a per-die work queue of the persistent mix
     int32_t pad;
 };
 
+struct AppTile {          // one cache page of a chunk's new tokens; launched once per KV head
+    int32_t seq;
+    int32_t page_idx;     // index into the sequence's page list
+    int32_t slot_lo;      // new tokens occupy slots [slot_lo, slot_hi) of the page
+    int32_t slot_hi;
+    int32_t row_slot0;    // row (in k_new / v_new) that slot 0 of the page would hold
+    int32_t pad0, pad1, pad2;
+};
+constexpr int kAppendTileMin = 8;   // sequences with at least this many new tokens are appended page-wise
+struct AppRow {           // one new token that is appended on its own
+    int32_t row;
+    int32_t seq;
+};
+
 struct RowItem {          // one query row for the generic kernel
     int32_t row;
     int32_t seq;
@@ -72,6 +86,8 @@ struct Plan {
     std::vector<CmbItem> cmb;
     std::vector<PfItem> pf;
     std::vector<PfSlot> pfmap;       // launch order of the prefill workgroups (XCD-aware)
+    std::vector<AppTile> apt;        // page-wise append work of the chunks
+    std::vector<AppRow> apr;         // token-wise append work: short sequences, and everything the page-wise kernel does not cover
     std::vector<QItem> queue;        // mixed batches: per-die queues, concatenated
     std::vector<int32_t> q_off;      // xcds + 1 offsets into queue
     std::vector<RowItem> rows;
@@ -116,6 +132,8 @@ struct AppendArgs {
     const float* k_scale; const float* v_scale;
     const int32_t* block_table;
     const SeqMeta* seqs; int32_t num_seqs; int32_t total_tokens;
+    const AppTile* apt; int32_t n_apt;
+    const AppRow* apr; int32_t n_apr;
 };
 
 struct AttnArgs {

@@ -2,9 +2,15 @@
 //
 // Prefill builds cache entries for all input tokens, a decode iteration adds the entry of the
 // last token (paper Sec. 2.1); in a Convertible Decoder both kinds of rows arrive in one batch
-// (Sec. 3.4).  One workgroup per new token: it finds the token's sequence, position, page and
-// slot, then scatters the token's Hkv x D values of K (as 16-byte dim-chunks) and of V
-// (token-fastest tile) into place, converting to the cache element type on the way.
+// (Sec. 3.4).  Two kernels:
+//   - append_token_kernel: one workgroup per new token of a short sequence (decode rows): looks up the
+//     token's page and slot and scatters its Hkv x D values of K (16-byte dim-chunks) and V
+//     (token-fastest tile) into place;
+//   - append_tile_kernel: one workgroup per (cache page, KV head) of a chunk: loads the page's up
+//     to 16 new rows with full 256-byte reads, turns them into the K tile and -- through LDS --
+//     into the token-fastest V tile, and writes whole 16-byte vectors.  (Scattering a chunk token
+//     by token wrote 5.5x the new bytes: every 2-byte V element dirtied its own cache sector.)
+// Both convert to the cache element type with the same functions, so the bytes are identical.
 #include "ts_device.h"
 
 namespace ts {
@@ -21,17 +27,11 @@ template <> struct Elem<uint16_t> {
 // SRC: element type of k_new/v_new (float or uint16_t holding bf16 bits).
 // DST: cache element type (float, uint16_t bf16 bits, uint8_t e4m3).
 template <typename SRC, typename DST>
-__global__ __launch_bounds__(256) void append_kernel(AppendArgs a)
+__global__ __launch_bounds__(256) void append_token_kernel(AppendArgs a)
 {
-    const int row = blockIdx.x;
+    const AppRow r = a.apr[blockIdx.x];
+    const int row = r.row, lo = r.seq;
     const int Hkv = a.geo.Hkv, D = a.geo.D;
-    // sequence of this row: last s with q_off[s] <= row  (empty sequences share the offset of the
-    // next one and are skipped by taking the last match)
-    int lo = 0, hi = a.num_seqs;                   // invariant: q_off[lo] <= row < q_off[hi]
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (a.seqs[mid].q_off <= row) lo = mid; else hi = mid;
-    }
     const SeqMeta m = a.seqs[lo];
     const int pos = m.prefix + (row - m.q_off);
     const int64_t page = a.block_table[(int64_t)lo * a.geo.max_pages + (pos >> 4)];
@@ -59,19 +59,112 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a)
     }
 }
 
+// bf16 source rows, head_dim 128; DST = uint16_t (bf16 cache) or uint8_t (e4m3 cache).
+// Thread (t = tid / 16, c = tid % 16) loads the 16 bytes (dims 8c .. 8c+7) of slot t's K and V row.
+constexpr int kRowPad = 136;                       // LDS row stride in elements: 272 bytes, avoids bank conflicts
+template <typename DST>
+__global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
+{
+    constexpr int D = 128;
+    __shared__ __align__(16) uint16_t ks[16 * kRowPad];
+    __shared__ __align__(16) uint16_t vs[16 * kRowPad];
+    const int Hkv = a.geo.Hkv;
+    const int g = blockIdx.x % Hkv;
+    const AppTile it = a.apt[blockIdx.x / Hkv];
+    const int tid = threadIdx.x, t = tid >> 4, c = tid & 15;
+    const int64_t page = a.block_table[(int64_t)it.seq * a.geo.max_pages + it.page_idx];
+    const bool mine = t >= it.slot_lo && t < it.slot_hi;
+    uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
+    if (mine) {
+        const int64_t src = ((int64_t)(it.row_slot0 + t) * Hkv + g) * D + 8 * c;
+        kv = *(const uint4*)((const uint16_t*)a.k_new + src);
+        vv = *(const uint4*)((const uint16_t*)a.v_new + src);
+    }
+    *(uint4*)(vs + t * kRowPad + 8 * c) = vv;
+    if constexpr (sizeof(DST) == 1) *(uint4*)(ks + t * kRowPad + 8 * c) = kv;
+    __syncthreads();
+    const bool full = it.slot_lo == 0 && it.slot_hi == kPage;
+
+    if constexpr (sizeof(DST) == 2) {
+        uint16_t* kt = (uint16_t*)a.k_cache + tile_elem_base(page, Hkv, g, D);
+        uint16_t* vt = (uint16_t*)a.v_cache + tile_elem_base(page, Hkv, g, D);
+        // K tile [16 chunks][16 slots][8]: this thread's own 16 bytes
+        if (mine) *(uint4*)(kt + (c * 16 + t) * 8) = kv;
+        // V tile [128 dims][16 slots]: thread (dim = tid / 2, half = tid % 2) gathers 8 slots of one dim
+        const int dim = tid >> 1, hf = tid & 1;
+        uint16_t e[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) e[i] = vs[(8 * hf + i) * kRowPad + dim];
+        uint16_t* dst = vt + dim * kPage + 8 * hf;
+        if (full) {
+            *(uint4*)dst = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
+                                      e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (8 * hf + i >= it.slot_lo && 8 * hf + i < it.slot_hi) dst[i] = e[i];
+        }
+    } else {
+        uint8_t* kt = (uint8_t*)a.k_cache + tile_elem_base(page, Hkv, g, D);
+        uint8_t* vt = (uint8_t*)a.v_cache + tile_elem_base(page, Hkv, g, D);
+        const float kscale = a.k_scale[g], vscale = a.v_scale[g];
+        if (tid < 128) {
+            // K tile [8 chunks of 16 dims][16 slots][16]: thread (chunk = tid / 16, slot = tid % 16)
+            const int c16 = tid >> 4, slot = tid & 15;
+            if (slot >= it.slot_lo && slot < it.slot_hi) {
+                uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float x = bf16_bits_to_float(ks[slot * kRowPad + 16 * c16 + i]) / kscale;
+                    w[i >> 2] |= float_to_e4m3_bits(x) << (8 * (i & 3));
+                }
+                *(uint4*)(kt + (c16 * 16 + slot) * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        } else {
+            // V tile [128 dims][16 slots]: thread dim = tid - 128 gathers the 16 slots of one dim
+            const int dim = tid - 128;
+            uint32_t w[4] = {0, 0, 0, 0};
+            uint8_t b[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float x = bf16_bits_to_float(vs[i * kRowPad + dim]) / vscale;
+                b[i] = (uint8_t)float_to_e4m3_bits(x);
+                w[i >> 2] |= (uint32_t)b[i] << (8 * (i & 3));
+            }
+            uint8_t* dst = vt + dim * kPage;
+            if (full) {
+                *(uint4*)dst = make_uint4(w[0], w[1], w[2], w[3]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (i >= it.slot_lo && i < it.slot_hi) dst[i] = b[i];
+            }
+        }
+    }
+}
+
 int launch_append(const AppendArgs& a, void* stream)
 {
     if (a.total_tokens <= 0) return (int)hipSuccess;
-    dim3 grid((unsigned)a.total_tokens), block(256);
     hipStream_t st = (hipStream_t)stream;
-    if (a.geo.q_dtype == TS_F32 && a.geo.kv_dtype == TS_F32)
-        hipLaunchKernelGGL((append_kernel<float, float>), grid, block, 0, st, a);
-    else if (a.geo.q_dtype == TS_BF16 && a.geo.kv_dtype == TS_BF16)
-        hipLaunchKernelGGL((append_kernel<uint16_t, uint16_t>), grid, block, 0, st, a);
-    else if (a.geo.q_dtype == TS_BF16 && a.geo.kv_dtype == TS_FP8_E4M3)
-        hipLaunchKernelGGL((append_kernel<uint16_t, uint8_t>), grid, block, 0, st, a);
-    else
-        return (int)hipErrorInvalidValue;
+    dim3 block(256);
+    if (a.n_apr > 0) {
+        dim3 grid((unsigned)a.n_apr);
+        if (a.geo.q_dtype == TS_F32 && a.geo.kv_dtype == TS_F32)
+            hipLaunchKernelGGL((append_token_kernel<float, float>), grid, block, 0, st, a);
+        else if (a.geo.q_dtype == TS_BF16 && a.geo.kv_dtype == TS_BF16)
+            hipLaunchKernelGGL((append_token_kernel<uint16_t, uint16_t>), grid, block, 0, st, a);
+        else if (a.geo.q_dtype == TS_BF16 && a.geo.kv_dtype == TS_FP8_E4M3)
+            hipLaunchKernelGGL((append_token_kernel<uint16_t, uint8_t>), grid, block, 0, st, a);
+        else
+            return (int)hipErrorInvalidValue;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.n_apt == 0) return (int)e;
+    if (a.geo.q_dtype != TS_BF16 || a.geo.D != 128) return (int)hipErrorInvalidValue;
+    dim3 tgrid((unsigned)a.n_apt * (unsigned)a.geo.Hkv);
+    if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((append_tile_kernel<uint16_t>), tgrid, block, 0, st, a);
+    else hipLaunchKernelGGL((append_tile_kernel<uint8_t>), tgrid, block, 0, st, a);
     return (int)hipGetLastError();
 }
 

@@ -207,6 +207,21 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     p.seqs[num_seqs] = SeqMeta{off, 0, 0, 0};
     p.info.total_tokens = off;
 
+    // append work: chunks page by page where the page-wise kernel applies, the rest token by token
+    const bool page_wise = d.q_dtype == TS_BF16 && d.head_dim == 128;
+    for (int s = 0; s < num_seqs; ++s) {
+        const SeqMeta& m = p.seqs[s];
+        if (!page_wise || m.q_len < kAppendTileMin) {
+            for (int32_t i = 0; i < m.q_len; ++i) p.apr.push_back(AppRow{m.q_off + i, s});
+            continue;
+        }
+        for (int32_t pg = m.prefix / kPage; pg <= (m.ctx_len - 1) / kPage; ++pg) {
+            const int32_t lo = std::max(m.prefix, pg * kPage) - pg * kPage;
+            const int32_t hi = std::min(m.ctx_len, (pg + 1) * kPage) - pg * kPage;
+            p.apt.push_back(AppTile{s, pg, lo, hi, m.q_off + pg * kPage - m.prefix, 0, 0, 0});
+        }
+    }
+
     const int32_t L = opt.split_pages > 0
                           ? opt.split_pages
                           : auto_split_pages(decode_tiles, decode_pages, p.info.decode_tokens, Hkv, opt.wg_slots);
@@ -317,6 +332,8 @@ extern "C" int64_t ts_plan_export(const ts_attn_desc* desc, const int32_t* q_len
     case TS_LIST_ROWS:    src = plan.rows.data();  n = (int64_t)plan.rows.size();  words = sizeof(ts::RowItem) / 4; break;
     case TS_LIST_QUEUE:   src = plan.queue.data(); n = (int64_t)plan.queue.size(); words = sizeof(ts::QItem) / 4; break;
     case TS_LIST_QOFF:    src = plan.q_off.data(); n = (int64_t)plan.q_off.size(); words = 1; break;
+    case TS_LIST_APPEND:  src = plan.apt.data();   n = (int64_t)plan.apt.size();   words = sizeof(ts::AppTile) / 4; break;
+    case TS_LIST_APPEND_ROWS: src = plan.apr.data(); n = (int64_t)plan.apr.size(); words = sizeof(ts::AppRow) / 4; break;
     default: return TS_ERR_INVALID_ARG;
     }
     const int64_t fit = words ? std::min<int64_t>(n, capacity / words) : 0;

@@ -234,6 +234,22 @@ def test_append_only_entry_point_bit_exact():
         ctx.close()
 
 
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+def test_append_page_alignments_bit_exact(kv):
+    """Chunks that start and end anywhere inside a page, next to short sequences that take the
+    per-token kernel: every byte of both caches equals the oracle's, untouched bytes included."""
+    g = gpu()
+    q_lens = [7, 8, 9, 16, 17, 33, 100, 1, 8, 15, 16, 48, 2]
+    prefix = [3, 0, 15, 16, 5, 31, 77, 40, 9, 1, 8, 32, 14]
+    shape = AttnShape(8, 4, 128, "bf16", kv)
+    b = make_batch(shape, q_lens, [q + p for q, p in zip(q_lens, prefix)], seed=59, pool_rule=1.3)
+    print(f"[case] append_alignments {shape}", flush=True)
+    _, rk, rv = oracle.run_batch(b)
+    _, gk, gv = g.run_batch(b)
+    assert same_bytes(gk, rk)
+    assert same_bytes(gv, rv)
+
+
 # ---------------------------------------------------------------------------------------------
 # boundary behaviour on the GPU
 # ---------------------------------------------------------------------------------------------

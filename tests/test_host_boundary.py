@@ -92,6 +92,37 @@ def test_plan_counts_and_decode_items_cover_every_page_once():
                                          if len([1 for it in items if it[1] == s]) > 1)
 
 
+def test_plan_append_pages_cover_every_new_token_of_the_chunks_once():
+    """Page-wise append work: each new token of a sequence with >= 8 new tokens lies in exactly one
+    (page, slot range) record, and the record's row arithmetic points at that token's input row."""
+    from paper_2512_03416_amd import binding
+    rng = np.random.default_rng(5)
+    q_lens = rng.integers(0, 70, size=60).astype(np.int32)
+    q_lens[:6] = [0, 1, 7, 8, 16, 17]
+    prefix = rng.integers(0, 50, size=60).astype(np.int32)
+    ctx = q_lens + prefix
+    desc = binding.Desc.make(8, 2, 128, "bf16", "bf16", 4096, 16)
+    rec = binding.plan_export(desc, q_lens, ctx, "append")
+    q_off = np.concatenate([[0], np.cumsum(q_lens)])
+    seen = {}
+    for seq, pg, lo, hi, row0, *_ in rec:
+        assert q_lens[seq] >= 8 and 0 <= lo < hi <= 16
+        for slot in range(lo, hi):
+            pos = pg * 16 + slot
+            assert prefix[seq] <= pos < ctx[seq]
+            assert row0 + slot == q_off[seq] + pos - prefix[seq]
+            assert (seq, pos) not in seen
+            seen[(seq, pos)] = True
+    assert len(seen) == int(q_lens[q_lens >= 8].sum())
+    # the other tokens, and all tokens of shapes the page-wise kernel does not take, go one by one
+    rows = binding.plan_export(desc, q_lens, ctx, "append_rows")
+    want = [(q_off[s] + i, s) for s in range(len(q_lens)) if q_lens[s] < 8 for i in range(q_lens[s])]
+    assert [tuple(r) for r in rows] == want
+    d64 = binding.Desc.make(4, 1, 64, "f32", "f32", 4096, 16)
+    assert len(binding.plan_export(d64, q_lens, ctx, "append")) == 0
+    assert len(binding.plan_export(d64, q_lens, ctx, "append_rows")) == int(q_lens.sum())
+
+
 def test_plan_routes_fp32_and_head_dim_64_to_generic_rows():
     d = D(q_dtype="f32", kv_dtype="f32", D=64, Hq=4, Hkv=1)
     info = ts.plan_describe(d, [1, 37, 64], [5, 37, 112])
