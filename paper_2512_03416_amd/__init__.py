@@ -6,5 +6,7 @@ kernels.  PyTorch is used by callers only for device memory and streams.
 from .binding import (Context, Desc, PlanInfo, Velocity, TokenScaleError, cache_bytes, check_desc,
                       library_path, load_library, plan_decode_items, plan_describe, plan_export, DTYPES, calib_copy, calib_read)
 
-__all__ = ["Context", "Desc", "PlanInfo", "Velocity", "TokenScaleError", "cache_bytes", "check_desc",
+from . import policy
+
+__all__ = ["policy", "Context", "Desc", "PlanInfo", "Velocity", "TokenScaleError", "cache_bytes", "check_desc",
            "library_path", "load_library", "plan_decode_items", "plan_describe", "plan_export", "DTYPES", "calib_copy", "calib_read"]

@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtokenscale.so")
 
-SOURCES = ["ts_planner.cpp", "ts_api.hip", "ts_kernels_append.hip", "ts_kernels_rows.hip",
+SOURCES = ["ts_planner.cpp", "ts_policy.cpp", "ts_api.hip", "ts_kernels_append.hip", "ts_kernels_rows.hip",
            "ts_kernels_decode.hip", "ts_kernels_prefill.hip", "ts_kernels_mixed.hip", "ts_calib.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -23,6 +23,19 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(binding.EXPORTS)
 
 
+def test_library_exports_every_policy_symbol():
+    from paper_2512_03416_amd import policy
+    hdr = open(os.path.join(ROOT, "include", "tokenscale_policy.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ts_[a-z_0-9]+)\s*\(", hdr))
+    lib = ctypes.CDLL(ts.library_path())
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(policy.EXPORTS)
+    headers = sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
+    assert headers == ["tokenscale.h", "tokenscale_policy.h"]      # every header is covered by a symbol test
+
+
 def D(**kw):
     base = dict(Hq=32, Hkv=8, D=128, q_dtype="bf16", kv_dtype="bf16", num_pages=1000, max_pages_per_seq=64)
     base.update(kw)
