@@ -6,22 +6,32 @@
 // chunk rows up to itself.  This part of the pass is a dense contraction (QK^T and PV), so it
 // is tiled for MFMA:
 //   - one workgroup (8 waves) owns a tile of 256 query rows = (256/G tokens) x (G query heads of
-//     one KV head), so each K/V byte staged into LDS serves the whole head group;
-//   - KV is consumed in stages of 64 tokens (4 pages).  Cache tiles are already in matrix-operand
-//     order: K tiles are copied to LDS verbatim, V tiles are interleaved pairwise so that every
-//     operand fetch is one conflict-free 16-byte LDS read at a lane-linear address;
-//   - S^T = K Q^T (tokens x rows) so that the accumulator layout of S^T is the B-operand layout
-//     of O^T += V^T P^T: the weights go from the first product to the second without leaving
-//     registers, and softmax statistics are per lane (row) with a 2-step cross-lane reduction;
-//   - the tiles of the next two stages are on their way from global memory into registers while
-//     the current stage is multiplied.
-// fp8 caches are widened to bf16 while being staged, so the multiply loop is the same.
+//     one KV head), so each K/V byte staged into LDS serves the whole head group; a wave owns 32
+//     rows, one per lane pair (lane n and lane n + 32);
+//   - KV is consumed in stages of 64 tokens (4 pages) that sit in a ring of four LDS slots; a
+//     wave works through a stage in two half-stages of 32 tokens (2 pages);
+//   - both products use the 32x32x16 MFMA: it occupies the matrix pipe for 32 cycles but the
+//     vector issue port for 8, so 24 of every 32 cycles are free for the softmax arithmetic (the
+//     16x16x32 form leaves 8 of 16, which is less than one exponential per MFMA needs);
+//   - S^T = K Q^T (tokens x rows).  The 16-byte pieces of the K tiles are placed in LDS such that
+//     row rho of S^T is the token for which the accumulator registers of a lane come out as
+//     "8 consecutive tokens of the first page, then the same 8 of the second page": packed to
+//     bf16 they are the B operands of O^T += V^T P^T as they stand, and the matching A operand is
+//     one natural 16-byte piece (dim, 8 tokens) of the V tile;
+//   - three half-stages are in flight per wave: while the matrix cores multiply K Q^T of
+//     half-stage h+2 and V^T P^T of half-stage h, the vector ALU turns the scores of h+1 into
+//     weights.  The instruction order of that steady state is written out slot by slot and pinned
+//     with scheduling barriers (left to itself the compiler puts the phases one after the other);
+//   - bf16 caches: the memory system copies the tiles straight into LDS (no registers, no vector
+//     instructions); fp8 caches are widened to bf16 by the threads while being staged, so the
+//     multiply loop is the same.
 #pragma once
 #include "ts_device.h"
 
 namespace ts {
 
 constexpr float kRaisePf = 16.0f;
+constexpr float kBigWeight = 65536.0f;                   // 2^kRaisePf
 constexpr int kStageTok = 64;
 
 __device__ __forceinline__ bf16x8 u4_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -59,19 +69,23 @@ constexpr int kPfWaves = 8;                                // 512 threads, 256 q
 constexpr int kPfThreads = 64 * kPfWaves;
 constexpr int kPfRing = 4;                                 // stages resident in LDS
 
-// LDS image of a stage (bf16 in both cases), both in the order of the cache tiles:
-//   K: 4 pages x [16 dim-chunks][16 tokens][8]  = 4 x 4096 bytes
-//   V: 4 pages x [8 dim blocks][2 token halves][16 dims][8 tokens] = 4 x 4096 bytes: the 16-byte
-//      pieces (dim, 8 tokens) of the cache tile [128 dims][16 tokens], reordered so that the 16
-//      dims of an MFMA operand lie side by side (conflict-free 8-byte operand reads)
+// LDS image of a stage (bf16 in both cases): per page the 256 16-byte pieces of the cache tile,
+// reordered.
+//   K page: piece (dim chunk c, token slot s) at [c][swap23(s)]: the slot index with its bits 2 and
+//           3 exchanged.  Row rho of the A operand of S^T = K Q^T reads [c][rho % 16] of page
+//           rho / 16, so row rho is token 16 (rho / 16) + swap23(rho % 16) of the half-stage, and
+//           the 16 accumulator registers of lane (n, h) are tokens 8h..8h+7 of the first page
+//           followed by tokens 8h..8h+7 of the second.
+//   V page: piece (dim d, token half t) at [d / 32][t][d % 32]: the A operand (32 dims x 16
+//           tokens) of dim block b is 1 KB at lane * 16.
 // Stage i lives in slot i % kPfRing of both rings.
 struct __align__(16) PfLds {
     unsigned char k[kPfRing][4 * 4096];
     unsigned char v[kPfRing][4 * 4096];
 };
-
-// byte offset inside a page's V image of the piece (dim, token half)
-__device__ __forceinline__ int v_piece_offset(int dim, int half) { return (((dim >> 4) * 2 + half) * 16 + (dim & 15)) * 16; }
+__device__ __forceinline__ int swap23(int s) { return (s & 3) | ((s & 4) << 1) | ((s & 8) >> 1); }
+__device__ __forceinline__ int k_piece_offset(int chunk, int slot) { return (chunk * 16 + swap23(slot)) * 16; }
+__device__ __forceinline__ int v_piece_offset(int dim, int half) { return (((dim >> 5) * 2 + half) * 32 + (dim & 31)) * 16; }
 
 __device__ __forceinline__ uint32_t lds_address(const void* p)
 {
@@ -79,7 +93,7 @@ __device__ __forceinline__ uint32_t lds_address(const void* p)
 }
 
 // ---- bf16 cache: the memory system copies a stage straight into LDS -------------------------------
-// One instruction moves 64 x 16 bytes: lane l's chunk lands at lds_addr + 16 l (the instruction offset
+// One instruction moves 64 x 16 bytes: lane l's piece lands at lds_addr + 16 l (the instruction offset
 // advances both the global and the LDS address).  A wave moves 2 KB of K and 2 KB of V per stage:
 // half of page `wave / 2`.  The copies are counted by vmcnt like any load; nothing here tells the
 // compiler that LDS changes, so the caller waits (pf_wait_copies) and publishes with a barrier.
@@ -96,10 +110,11 @@ __device__ __forceinline__ void stage_copy_bf16(const AttnArgs& a, const int32_t
     const int page = min(stage * 4 + (wave >> 1), last_page);          // wave-uniform
     const int64_t off = ((int64_t)bt[page] * a.geo.Hkv + g) * 4096 + (wave & 1) * 2048;
     const int slot = stage % kPfRing;
-    copy_2k_to_lds(lds_address(lds.k[slot]) + wave * 2048, (const char*)a.k_cache + off, lane * 16);
-    // V: LDS piece p = 64 k + lane of this wave's 2 KB takes cache piece (dim 32 k + 16 (lane / 32) + lane % 16,
-    // half (lane / 16) % 2); the second instruction (k = 1) is 1 KB further in both
-    const int v_src = ((16 * (lane >> 5) + (lane & 15)) * 2 + ((lane >> 4) & 1)) * 16;
+    // K: LDS piece [c0 + lane / 16][lane % 16] takes cache piece (c0 + lane / 16, swap23(lane % 16))
+    const int k_src = (lane >> 4) * 256 + swap23(lane & 15) * 16;
+    // V: LDS piece [b0][lane / 32][lane % 32] takes cache piece (dim 32 b0 + lane % 32, half lane / 32)
+    const int v_src = (lane & 31) * 32 + (lane >> 5) * 16;
+    copy_2k_to_lds(lds_address(lds.k[slot]) + wave * 2048, (const char*)a.k_cache + off, k_src);
     copy_2k_to_lds(lds_address(lds.v[slot]) + wave * 2048, (const char*)a.v_cache + off, v_src);
 }
 constexpr int kCopiesPerStage = 4;                         // vmcnt units one stage_copy_bf16 adds per wave
@@ -136,13 +151,13 @@ __device__ __forceinline__ void stage_store(const StageFp8& st, unsigned char* l
                                             int ctx_len, int tid)
 {
     const int pg = tid >> 7, c = tid & 127;
-    // K chunk: 16 dims (chunk c/16) of token c%16 -> two bf16 chunks of 8 dims
+    // K chunk: 16 dims (chunk c/16) of token c%16 -> two bf16 pieces of 8 dims
     const int c16 = c >> 4, tok = c & 15;
     const uint4 k = st.k0;
     uint4 v = st.v0;
     const uint2 a0 = fp8x4_bf16x4(k.x), a1 = fp8x4_bf16x4(k.y), a2 = fp8x4_bf16x4(k.z), a3 = fp8x4_bf16x4(k.w);
-    *(uint4*)(lk + pg * 4096 + ((2 * c16) * 16 + tok) * 16) = make_uint4(a0.x, a0.y, a1.x, a1.y);
-    *(uint4*)(lk + pg * 4096 + ((2 * c16 + 1) * 16 + tok) * 16) = make_uint4(a2.x, a2.y, a3.x, a3.y);
+    *(uint4*)(lk + pg * 4096 + k_piece_offset(2 * c16, tok)) = make_uint4(a0.x, a0.y, a1.x, a1.y);
+    *(uint4*)(lk + pg * 4096 + k_piece_offset(2 * c16 + 1, tok)) = make_uint4(a2.x, a2.y, a3.x, a3.y);
     // V chunk: dim c, 16 tokens of page pg -> two pieces of 8 tokens
     const int nvalid = ctx_len - (kv0 + pg * kPage);
     if (nvalid < 16) v = keep_first8(v, max(nvalid, 0));             // poison past ctx_len -> 0
@@ -153,226 +168,198 @@ __device__ __forceinline__ void stage_store(const StageFp8& st, unsigned char* l
 
 // One causal tile for KV head g, executed by a workgroup of kPfThreads threads.  All threads must call
 // it; it ends with a workgroup barrier, so lds may be reused right after it returns.
-//
-// A wave works through its keys in half-stages of 32 tokens and keeps two of them in flight: while
-// the matrix cores multiply K Q^T of half-stage h+1, the vector ALU turns the scores of half-stage
-// h into weights (one fused multiply-add, one exp2 and half a pack per MFMA slot); while they
-// multiply V^T P^T of half-stage h, it reduces the row maxima of h+1.  The instruction order of
-// that steady state is written out slot by slot and pinned with scheduling barriers: an MFMA
-// occupies its pipe for 16 cycles but the issue port for 4, and left to itself the compiler puts
-// the two phases one after the other, where their times add up.
 template <typename KT>
 __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, int g, PfLds& lds)
 {
-    constexpr int D = 128, KB = 4, DB = 8, NT = 2, kHalf = 32;
+    constexpr int D = 128, KS = 8, DB = 4, kHalf = 32;     // KS: 16-dim steps of K Q^T, DB: 32-dim blocks of O^T
     const PfItem it = a.pf[item_idx];
-    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r = lane >> 4,
-              n = lane & 15;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, h = lane >> 5,
+              n = lane & 31;
     const int Hq = a.geo.Hq, G = a.geo.G;
 
-    // rows of this lane: rho = 32*wave + 16*nt + n  ->  (token rho / G, head rho % G)
-    int tok[NT], hd[NT];
-    bool row_ok[NT];
-    bf16x8 qb[NT][KB];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int rho = 32 * wave + 16 * nt + n;
-        const int t = rho / G;
-        row_ok[nt] = t < it.tok_count;
-        tok[nt] = min(t, it.tok_count - 1);                 // padding rows repeat the last token
-        hd[nt] = rho - t * G;
+    // row of this lane pair: rho = 32*wave + n  ->  (token rho / G, head rho % G)
+    const int rho = 32 * wave + n;
+    const int t_raw = rho / G;
+    const bool row_ok = t_raw < it.tok_count;
+    const int tok = min(t_raw, it.tok_count - 1);          // padding rows repeat the last token
+    const int hd = rho - t_raw * G;
+    bf16x8 qb[KS];                                          // Q^T operands: dims 16 s + 8 h .. + 7 of the row
+    {
         const uint16_t* qrow = (const uint16_t*)a.q +
-            ((int64_t)(it.row0 + it.tok_begin + tok[nt]) * Hq + g * G + hd[nt]) * D + 8 * r;
+            ((int64_t)(it.row0 + it.tok_begin + tok) * Hq + g * G + hd) * D + 8 * h;
 #pragma unroll
-        for (int b = 0; b < KB; ++b) qb[nt][b] = u4_bf16x8(*(const uint4*)(qrow + 32 * b));
+        for (int s = 0; s < KS; ++s) qb[s] = u4_bf16x8(*(const uint4*)(qrow + 16 * s));
     }
     const float kscale = (sizeof(KT) == 1) ? a.k_scale[g] : 1.0f;
     const float c = a.sm_scale * kscale * kLog2e;
-    int qpos[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) qpos[nt] = it.prefix + it.tok_begin + tok[nt];
+    const int qpos = it.prefix + it.tok_begin + tok;
     const int wave_min_q = it.prefix + it.tok_begin + min((32 * wave) / G, it.tok_count - 1);
-    const int wave_max_q = it.prefix + it.tok_begin + min((32 * wave + 31) / G, it.tok_count - 1);
     const int kv_hi = it.prefix + it.tok_begin + it.tok_count;     // keys [0, kv_hi) matter to this tile
     const int last_page = (it.ctx_len - 1) / kPage;
     const int32_t TS_CONSTANT* bt = as_constant(a.block_table) + (int64_t)it.seq * a.geo.max_pages;
-    // half-stages [0, hend) hold keys that some row of this wave sees; [0, hfull) need no causal mask
-    const int hend = wave_max_q / kHalf + 1;
+    // Half-stages [0, hend) hold keys that some row of the tile sees; every wave works through all of
+    // them (a wave whose rows all come earlier multiplies one or two fully masked half-stages: that
+    // keeps the eight waves in the same loop).  Half-stages [0, hfull) need no causal mask in this wave.
+    const int hend = (kv_hi - 1) / kHalf + 1;
     const int hfull = (wave_min_q + 1) / kHalf;
 
-    f32x4 acc[DB][NT];
+    // O^T: register v of acc[b] is dim 32 b + 8 (v / 4) + 4 h + v % 4 of the lane's row
+    f32x16 acc[DB];
 #pragma unroll
     for (int b = 0; b < DB; ++b)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[b][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // running sums of the weights come out of the matrix cores too: an all-ones A operand makes
-    // every row of the product the column sum of P^T, i.e. the softmax denominator of the lane's row
-    f32x4 accl[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) accl[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const bf16x8 ones = u4_bf16x8(make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u));
-    float m_ref[NT] = {-INFINITY, -INFINITY};
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+    float l_part = 0.f;                                    // this lane's half of the row's weight sum
+    float m_ref = -INFINITY;                               // reference maximum of the row (scaled log2 units)
 
-    // lane's operand addresses of half-stage h inside the LDS rings.  K operand of dim block b of the
-    // first / second 16 tokens: 16 bytes at kptr + b * 1024 (+ 4096).  V operand of dim block b: tokens
-    // 4r..4r+3 of both pages of the half-stage, 8 bytes each at vptr + b * 512 (+ 4096): half of the
-    // piece (dim 16 b + n, token half r / 2).
-    auto kptr = [&](int h) { return lds.k[(h >> 1) % kPfRing] + (h & 1) * 8192 + lane * 16; };
-    auto vptr = [&](int h) { return lds.v[(h >> 1) % kPfRing] + (h & 1) * 8192 + v_piece_offset(n, r >> 1) + (r & 1) * 8; };
-    auto lds16 = [](const unsigned char* p) { return u4_bf16x8(*(const uint4*)p); };
-    auto ldsv = [](const unsigned char* p) {
-        const uint2 x = *(const uint2*)p, y = *(const uint2*)(p + 4096);
-        return u4_bf16x8(make_uint4(x.x, x.y, y.x, y.y));
+    // lane's operand addresses of half-stage hs inside the LDS rings.  K operand of dim step s:
+    // 16 bytes at kptr + 512 s.  V operand of page t, dim block b: 16 bytes at vptr + 4096 t + 1024 b.
+    auto kptr = [&](int hs) {
+        return lds.k[(hs >> 1) % kPfRing] + (hs & 1) * 8192 + (n >> 4) * 4096 + h * 256 + (n & 15) * 16;
     };
-    auto mfma = [](bf16x8 x, bf16x8 y, f32x4 z) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, z, 0, 0, 0); };
+    auto vptr = [&](int hs) { return lds.v[(hs >> 1) % kPfRing] + (hs & 1) * 8192 + lane * 16; };
+    auto lds16 = [](const unsigned char* p) { return u4_bf16x8(*(const uint4*)p); };
+    auto mfma = [](bf16x8 x, bf16x8 y, f32x16 z) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, z, 0, 0, 0); };
     auto pack2 = [](float x, float y) {
         return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{x, y}, bf16x2));
     };
+    // register v of a score accumulator is token 16 (v / 8) + 8 h + v % 8 of the half-stage
 
     // ---- plain building blocks (first and last half-stages of a wave) -------------------------------
     // S^T = K Q^T of one half-stage (raw scores; the softmax scale is folded into the exponent)
-    auto qk_plain = [&](const unsigned char* lk, f32x4 (&s)[2][NT]) {
+    auto qk_plain = [&](const unsigned char* lk, f32x16& s) {
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            bf16x8 ak[KB];
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
-            for (int b = 0; b < KB; ++b) ak[b] = lds16(lk + tt * 4096 + b * 1024);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                f32x4 x = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int b = 0; b < KB; ++b) x = mfma(ak[b], qb[nt][b], x);
-                s[tt][nt] = x;
-            }
-        }
+        for (int ks = 0; ks < KS; ++ks) s = mfma(lds16(lk + ks * 512), qb[ks], s);
     };
-    auto causal_mask = [&](f32x4 (&s)[2][NT], int k0) {
+    auto causal_mask = [&](f32x16& s, int k0) {
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (k0 + tt * 16 + 4 * r + i > qpos[nt]) s[tt][nt][i] = -INFINITY;
+        for (int v = 0; v < 16; ++v)
+            if (k0 + 16 * (v >> 3) + 8 * h + (v & 7) > qpos) s[v] = -INFINITY;
     };
-    // raise the reference maximum (scaled log2 units) when a row's scores outgrow it by kRaisePf
-    auto raise = [&](float lmax0, float lmax1) {
-        const float lm[NT] = {lmax0, lmax1};
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            float full = fmaxf(lm[nt], __shfl_xor(lm[nt], 16, 64));
-            full = fmaxf(full, __shfl_xor(full, 32, 64));
-            const float m_new = fmaxf(m_ref[nt], full);
-            const float alpha = __builtin_amdgcn_exp2f(m_ref[nt] - m_new);
-#pragma unroll
-            for (int b = 0; b < DB; ++b) acc[b][nt] *= alpha;
-            accl[nt] *= alpha;
-            m_ref[nt] = m_new;
-        }
+    auto lane_max = [&](const f32x16& s) {
+        float x = fmax3(s[0], s[1], s[2]);
+        x = fmax3(x, s[3], s[4]);
+        x = fmax3(x, s[5], s[6]);
+        x = fmax3(x, s[7], s[8]);
+        x = fmax3(x, s[9], s[10]);
+        x = fmax3(x, s[11], s[12]);
+        x = fmax3(x, s[13], s[14]);
+        return __builtin_fmaxf(x, s[15]) * c;              // c > 0: the maximum commutes with the scale
     };
-    auto raise_if_needed = [&](float lmax0, float lmax1) {
-        if (__any(lmax0 > m_ref[0] + kRaisePf || lmax1 > m_ref[1] + kRaisePf)) raise(lmax0, lmax1);
+    // New reference maximum of the row; returns the factor that rescales everything accumulated so
+    // far.  The weight sum is rescaled here, the caller rescales acc.
+    auto raise = [&](float lmax) {
+        const float full = fmaxf(lmax, __shfl_xor(lmax, 32, 64));
+        const float m_new = fmaxf(m_ref, full);
+        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+        l_part *= alpha;
+        m_ref = m_new;
+        return alpha;
     };
-    auto lane_max = [&](const f32x4 (&s)[2][NT], int nt) {
-        float x = fmax3(s[0][nt][0], s[0][nt][1], s[0][nt][2]);
-        x = fmax3(x, s[0][nt][3], s[1][nt][0]);
-        x = fmax3(x, s[1][nt][1], s[1][nt][2]);
-        return __builtin_fmaxf(x, s[1][nt][3]) * c;         // c > 0: the maximum commutes with the scale
-    };
-    auto weights_plain = [&](const f32x4 (&s)[2][NT], bf16x8 (&pop)[NT]) {
+    auto rescale = [&](float alpha) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const float nm = -m_ref[nt];
+        for (int b = 0; b < DB; ++b) acc[b] *= alpha;
+    };
+    // weights of one half-stage: P^T operands of its two pages, and their sum
+    auto weights_plain = [&](const f32x16& s, bf16x8 (&pop)[2]) {
+        const float nm = -m_ref;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
             uint32_t w[4];
 #pragma unroll
-            for (int ab = 0; ab < 2; ++ab) {
-                const f32x4 x = s[ab][nt];
-                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[0], c, nm));
-                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[1], c, nm));
-                const float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[2], c, nm));
-                const float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(x[3], c, nm));
-                w[2 * ab] = pack2(p0, p1);
-                w[2 * ab + 1] = pack2(p2, p3);
+            for (int i = 0; i < 4; ++i) {
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * i], c, nm));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * i + 1], c, nm));
+                l_part += p0 + p1;
+                w[i] = pack2(p0, p1);
             }
-            pop[nt] = u4_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+            pop[t] = u4_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
         }
     };
-    // O^T += V^T P^T (and the row sums) of one half-stage
-    auto pv_plain = [&](const unsigned char* lv, const bf16x8 (&pop)[NT]) {
+    // O^T += V^T P^T of one half-stage
+    auto pv_plain = [&](const unsigned char* lv, const bf16x8 (&pop)[2]) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) accl[nt] = mfma(ones, pop[nt], accl[nt]);
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int b = 0; b < DB; ++b) {
-            const bf16x8 av = ldsv(lv + b * 512);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) acc[b][nt] = mfma(av, pop[nt], acc[b][nt]);
-        }
+            for (int b = 0; b < DB; ++b) acc[b] = mfma(lds16(lv + t * 4096 + b * 1024), pop[t], acc[b]);
     };
 
-    // ---- steady state: half-stage h with h+1 unmasked --------------------------------------------------
-    // in: scores of h (maximum already accounted for in m_ref), kpre: K operands of the first 16 tokens
-    // of h+1.  out: scores of h+1; kpre: the same for h+2.
-    auto fast_half = [&](int h, const f32x4 (&in)[2][NT], f32x4 (&out)[2][NT], bf16x8 (&kpre)[KB]) {
-        const unsigned char* lk = kptr(h + 1);
-        const unsigned char* lv = vptr(h);
-        const unsigned char* lkn = kptr(h + 2);
-        const float nm[NT] = {-m_ref[0], -m_ref[1]};
-        bf16x8 k1[KB], av[DB], pop[NT];
-        uint32_t w[NT][4];
+    // ---- steady state: one iteration = V^T P^T of half-stage hs and K Q^T of hs+2 on the matrix
+    // cores, weights of hs+1 on the vector ALU.  s1: scores of hs+1 (in), s2: scores of hs+2 (out),
+    // pop0: weights of hs (in), pop1: weights of hs+1 (out).  16 slots of one MFMA each; a slot also
+    // carries one weight (fused multiply-add, exp2, add to the sum, running maximum; every other slot
+    // a pack) and the LDS read of an operand needed four slots later.
+    auto fast_iter = [&](int hs, bool masked, const f32x16& s1, f32x16& s2, const bf16x8 (&pop0)[2], bf16x8 (&pop1)[2]) {
+        const unsigned char* lk = kptr(hs + 2);
+        const unsigned char* lv = vptr(hs);
+        // The weights of hs+1 are formed against the current reference maximum without looking at the
+        // scores first; a weight above 2^kRaisePf shows afterwards that the maximum has to be raised,
+        // and only then are the weights of this half-stage formed again (the scores are still there).
+        const float nm = -m_ref;
+        const float l_before = l_part;
+        float p_max = 0.f;
+        bf16x8 kop[KS], vop[2 * DB];
+        uint32_t w[8];
         float p_even = 0.f;
         __builtin_amdgcn_sched_barrier(0);
-        // 16 slots: MFMA j of K Q^T(h+1)  |  weight j of half-stage h
+        // operands of the first slots
+        vop[0] = lds16(lv);
+        kop[0] = lds16(lk);
+        vop[1] = lds16(lv + 1024);
+        kop[1] = lds16(lk + 512);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int tt = j >> 3, b = (j >> 1) & 3, nt = j & 1;
-            const f32x4 cin = b == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : out[tt][nt];
-            out[tt][nt] = mfma(tt == 0 ? kpre[b] : k1[b], qb[nt][b], cin);
-            if (j < 4) k1[j] = lds16(lk + 4096 + j * 1024);              // second 16 tokens of h+1
-            if (j >= 8 && j < 12) av[j - 8] = ldsv(lv + (j - 8) * 512);
-            const int ent = j >> 3, ab = (j >> 2) & 1, i = j & 3;
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(in[ab][ent][i], c, nm[ent]));
-            if (i & 1) w[ent][2 * ab + (i >> 1)] = pack2(p_even, p); else p_even = p;
+            const int u = j >> 1;
+            if ((j & 1) == 0) {
+                acc[u & 3] = mfma(vop[u], pop0[u >> 2], acc[u & 3]);
+                if (u + 2 < 2 * DB) vop[u + 2] = lds16(lv + ((u + 2) >> 2) * 4096 + ((u + 2) & 3) * 1024);
+            } else {
+                if (u == 0) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s2[v] = 0.f;
+                }
+                s2 = mfma(kop[u], qb[u], s2);
+                if (u + 2 < KS) kop[u + 2] = lds16(lk + (u + 2) * 512);
+            }
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[j], c, nm));
+            l_part += p;
+            p_max = __builtin_fmaxf(p_max, p);
+            if (j & 1) w[j >> 1] = pack2(p_even, p); else p_even = p;
             __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) pop[nt] = u4_bf16x8(make_uint4(w[nt][0], w[nt][1], w[nt][2], w[nt][3]));
-        // 18 slots: row sums and V^T P^T(h)  |  lane maxima of h+1, operand reads
-        float lmax[NT] = {0.f, 0.f};
-        unsigned long long vote = 0;                       // taken early: the branch at the end finds it in a scalar register
-#pragma unroll
-        for (int j = 0; j < 18; ++j) {
-            if (j < 2) accl[j] = mfma(ones, pop[j], accl[j]);
-            else acc[(j - 2) >> 1][j & 1] = mfma(av[(j - 2) >> 1], pop[j & 1], acc[(j - 2) >> 1][j & 1]);
-            if (j < 4) av[4 + j] = ldsv(lv + (4 + j) * 512);
-            if (j >= 8 && j < 12) kpre[j - 8] = lds16(lkn + (j - 8) * 1024);   // first 16 tokens of h+2
-            if (j == 6) lmax[0] = lane_max(out, 0);
-            if (j == 7) lmax[1] = lane_max(out, 1);
-            if (j == 9) vote = __builtin_amdgcn_ballot_w64(lmax[0] > m_ref[0] + kRaisePf || lmax[1] > m_ref[1] + kRaisePf);
-            __builtin_amdgcn_sched_barrier(0);
+        pop1[0] = u4_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+        pop1[1] = u4_bf16x8(make_uint4(w[4], w[5], w[6], w[7]));
+        if (__any(!(p_max <= kBigWeight))) {               // rare; also catches infinities
+            l_part = l_before;
+            const float alpha = raise(lane_max(s1));
+            weights_plain(s1, pop1);
+            rescale(alpha);                                // everything up to half-stage hs was relative to the old maximum
         }
-        if (vote != 0) raise(lmax[0], lmax[1]);
+        if (masked) causal_mask(s2, (hs + 2) * kHalf);     // wave-uniform
     };
-    // ---- any other half-stage -----------------------------------------------------------------------------
-    auto slow_half = [&](int h, const f32x4 (&in)[2][NT], f32x4 (&out)[2][NT]) {
-        const bool next = h + 1 < hend;                    // wave-uniform
-        if (next) {
-            qk_plain(kptr(h + 1), out);
-            if (h + 1 >= hfull) causal_mask(out, (h + 1) * kHalf);
+    // ---- any other iteration --------------------------------------------------------------------------
+    auto slow_iter = [&](int hs, const f32x16& s1, f32x16& s2, const bf16x8 (&pop0)[2], bf16x8 (&pop1)[2]) {
+        pv_plain(vptr(hs), pop0);
+        if (hs + 1 < hend) {                               // wave-uniform
+            const float lmax = lane_max(s1);
+            if (__any(lmax > m_ref + kRaisePf)) rescale(raise(lmax));
+            weights_plain(s1, pop1);
         }
-        bf16x8 pop[NT];
-        weights_plain(in, pop);
-        pv_plain(vptr(h), pop);
-        if (next) raise_if_needed(lane_max(out, 0), lane_max(out, 1));
+        if (hs + 2 < hend) {
+            qk_plain(kptr(hs + 2), s2);
+            if (hs + 2 >= hfull) causal_mask(s2, (hs + 2) * kHalf);
+        }
     };
-    f32x4 sA[2][NT], sB[2][NT];
-    bf16x8 kpre[KB];
 
     const int n_stage = (kv_hi + kStageTok - 1) / kStageTok;
-    // Body i multiplies stages i and i+1 (the scores run one half-stage ahead); the barrier that ends
-    // it publishes stage i+2.  bf16: the copy of stage i+3 is started at the top of body i, over stage
-    // i-1 whose last reader finished before the barrier that ended body i-1, and is awaited at the end
-    // of body i+1.  fp8: stage i+2 goes from registers into LDS at the top of body i, stage i+3 is
-    // fetched into the registers.
+    // Body i runs iterations 2i and 2i+1: it reads V of stage i and K of stage i+1.  The barrier that
+    // ends it publishes stage i+2.  bf16: the copy of stage i+3 is started at the top of body i, over
+    // stage i-1 whose last reader finished before the barrier that ended body i-1, and is awaited at
+    // the end of body i+1.  fp8: stage i+2 goes from registers into LDS at the top of body i, stage
+    // i+3 is fetched into the registers.
     constexpr bool kCopy = sizeof(KT) == 2;
     // bf16: the stage that holds tokens >= ctx_len (if this tile reads it) needs its V tail cleared
     const int clear_stage = (kCopy && it.ctx_len % kStageTok != 0 && it.ctx_len / kStageTok < n_stage)
@@ -417,49 +404,61 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         clear_v_tail(lds.v[clear_stage], clear_stage, it.ctx_len, tid);
         __syncthreads();
     }
-    // scores of half-stage 0 (every wave has at least one half-stage: key 0 is visible to every row)
-    qk_plain(kptr(0), sA);
-    if (hfull == 0) causal_mask(sA, 0);
-    raise_if_needed(lane_max(sA, 0), lane_max(sA, 1));
-#pragma unroll
-    for (int b = 0; b < KB; ++b) kpre[b] = lds16(kptr(1) + b * 1024);
 
-    // Bodies in which every wave of the tile is in its steady state: half-stages up to 2i+2 lie
-    // below the first query position of the tile (wave 0 has the smallest).
+    // Fill the pipeline: weights of half-stage 0 and scores of half-stage 1 (every wave has at least
+    // one half-stage: key 0 is visible to every row).
+    f32x16 sA, sB;
+    bf16x8 popA[2], popB[2];
+    qk_plain(kptr(0), sB);
+    if (hfull == 0) causal_mask(sB, 0);
+    raise(lane_max(sB));                                   // acc is still zero: nothing to rescale
+    weights_plain(sB, popA);
+    if (hend > 1) {
+        qk_plain(kptr(1), sA);
+        if (hfull <= 1) causal_mask(sA, kHalf);
+    }
+
+    // Bodies whose iterations all have a half-stage hs+2 to multiply run the steady state: first those
+    // that lie below the first query position of the tile (no wave needs a mask), then those that
+    // reach into the diagonal; the last one or two bodies drain the pipeline.
     const int hfull_tile = (it.prefix + it.tok_begin + 1) / kHalf;
-    const int n_fast = max(0, (hfull_tile - 1) / 2);
+    const int n_plain = max(0, (hfull_tile - 2) / 2);      // 2i+3 < hfull_tile
+    const int n_steady = max(0, (hend - 2) / 2);           // 2i+3 < hend
     int i = 0;
-    for (; i < n_fast; ++i) {
+    for (; i < n_plain; ++i) {
         top(i);
-        fast_half(2 * i, sA, sB, kpre);
-        fast_half(2 * i + 1, sB, sA, kpre);
+        fast_iter(2 * i, false, sA, sB, popA, popB);
+        fast_iter(2 * i + 1, false, sB, sA, popB, popA);
         bottom(i);
     }
-    // the last bodies: waves run out of visible keys one after the other
+    for (; i < n_steady; ++i) {
+        top(i);
+        fast_iter(2 * i, 2 * i + 2 >= hfull, sA, sB, popA, popB);
+        fast_iter(2 * i + 1, 2 * i + 3 >= hfull, sB, sA, popB, popA);
+        bottom(i);
+    }
     for (; i < n_stage; ++i) {
         top(i);
-        if (2 * i < hend) slow_half(2 * i, sA, sB);
-        if (2 * i + 1 < hend) slow_half(2 * i + 1, sB, sA);
+        if (2 * i < hend) slow_iter(2 * i, sA, sB, popA, popB);
+        if (2 * i + 1 < hend) slow_iter(2 * i + 1, sB, sA, popB, popA);
         bottom(i);
     }
     // (the last body ended with a barrier: lds may be reused by the caller)
 
     const float vscale = (sizeof(KT) == 1) ? a.v_scale[g] : 1.0f;
+    const float l_row = l_part + __shfl_xor(l_part, 32, 64);
+    if (row_ok) {
+        const float inv = vscale / l_row;
+        uint16_t* o = (uint16_t*)a.out + ((int64_t)(it.row0 + it.tok_begin + tok) * Hq + g * G + hd) * D + 4 * h;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const float lt = accl[nt][0];
-        if (!row_ok[nt]) continue;
-        const float inv = vscale / lt;
-        uint16_t* o = (uint16_t*)a.out +
-            ((int64_t)(it.row0 + it.tok_begin + tok[nt]) * Hq + g * G + hd[nt]) * D + 4 * r;
+        for (int b = 0; b < DB; ++b)
 #pragma unroll
-        for (int b = 0; b < DB; ++b) {
-            const f32x4 x = acc[b][nt] * inv;
-            uint2 w;
-            w.x = pack2(x[0], x[1]);
-            w.y = pack2(x[2], x[3]);
-            *(uint2*)(o + 16 * b) = w;
-        }
+            for (int j = 0; j < 4; ++j) {
+                uint2 w;
+                w.x = pack2(acc[b][4 * j] * inv, acc[b][4 * j + 1] * inv);
+                w.y = pack2(acc[b][4 * j + 2] * inv, acc[b][4 * j + 3] * inv);
+                *(uint2*)(o + 32 * b + 8 * j) = w;
+            }
     }
 }
 
