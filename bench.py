@@ -157,7 +157,6 @@ def main():
     ap.add_argument("--split-pages", type=int, default=0)
     ap.add_argument("--prefetch-tiles", type=int, default=0)
     ap.add_argument("--xcd-count", type=int, default=0)
-    ap.add_argument("--prefill-skew", type=int, default=-1)
     ap.add_argument("--no-persistent", action="store_true",
                     help="mixed batches: decode kernel then prefill kernel instead of the persistent launch")
     ap.add_argument("--time-every", type=int, default=4,
@@ -187,8 +186,6 @@ def main():
         ctx.set_option("decode_prefetch_tiles", args.prefetch_tiles)
     if args.xcd_count:
         ctx.set_option("xcd_count", args.xcd_count)
-    if args.prefill_skew >= 0:
-        ctx.set_option("prefill_skew", args.prefill_skew)
     if args.no_persistent:
         ctx.set_option("mixed_persistent", 0)
     nbytes = ts.cache_bytes(desc)

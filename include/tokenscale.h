@@ -156,8 +156,6 @@ const char *ts_last_error(const ts_ctx *ctx);
  *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave (process-wide)
  *   "mixed_persistent"    1 (default) = decode items and prefill tiles of a mixed batch share one
  *                         persistent launch; 0 = decode kernel, then prefill kernel
- *   "prefill_skew"        0 = the eight waves of a prefill tile run in lockstep, 1 (default) = waves 4..7
- *                         run half a stage behind waves 0..3, 2 = odd waves behind even waves
  *   "xcd_count"           accelerator dies the prefill launch order is laid out for (default 8)
  *   "kernel_timing"       N > 0 = record HIP events around the launches of every N-th call
  *                         (see ts_kernel_times), 0 = off

@@ -384,11 +384,6 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         c->opt.mixed_persistent = value != 0;
         return TS_OK;
     }
-    if (!strcmp(name, "prefill_skew")) {
-        if (value < 0 || value > 2) return fail(c, TS_ERR_INVALID_ARG, "prefill_skew must be 0..2");
-        c->opt.pf_skew = (int32_t)value;
-        return TS_OK;
-    }
     if (!strcmp(name, "xcd_count")) {
         if (value < 1 || value > 64) return fail(c, TS_ERR_INVALID_ARG, "xcd_count must be 1..64");
         c->opt.xcds = (int32_t)value;
@@ -491,7 +486,6 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     a.cmb = (const CmbItem*)(c->d_work + w.cmb);   a.n_cmb = (int32_t)p.cmb.size();
     a.pf = (const PfItem*)(c->d_work + w.pf);      a.n_pf = (int32_t)p.pf.size();
     a.pfmap = (const PfSlot*)(c->d_work + w.pfmap); a.n_pfmap = (int32_t)p.pfmap.size();
-    a.pf_skew = c->opt.pf_skew;
     a.rows = (const RowItem*)(c->d_work + w.rows); a.n_rows = (int32_t)p.rows.size();
     a.queue = (const QItem*)(c->d_work + w.queue); a.q_off = (const int32_t*)(c->d_work + w.q_off);
     a.n_queue = (int32_t)p.queue.size(); a.n_xcd = p.q_off.empty() ? 0 : (int32_t)p.q_off.size() - 1;

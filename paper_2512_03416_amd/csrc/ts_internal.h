@@ -99,7 +99,6 @@ struct PlanOptions {
     int32_t wg_slots = 768;     // decode workgroups resident at once (256 CUs x 3)
     int32_t xcds = 8;           // accelerator dies; workgroup i is dispatched to die i % xcds
     bool mixed_persistent = true; // decode items and prefill tiles in one persistent launch
-    int32_t pf_skew = 1;
     bool generic_only = false;  // every row through the generic kernel
     bool prefill_generic = false;
     int32_t tile_tokens = 0;    // query tokens per prefill tile
@@ -149,7 +148,6 @@ struct AttnArgs {
     const CmbItem* cmb; int32_t n_cmb;
     const PfItem* pf;   int32_t n_pf;
     const PfSlot* pfmap; int32_t n_pfmap;
-    int32_t pf_skew;           // 0 = lockstep, 1 = waves 4..7 lag half a stage, 2 = odd waves lag
     const QItem* queue; const int32_t* q_off; int32_t n_queue; int32_t n_xcd;
     int32_t* q_ctr;            // n_xcd queue heads + 1 finished-workgroup count, zero between launches
     const RowItem* rows; int32_t n_rows;

@@ -107,6 +107,34 @@ def test_prefill_chunks(kv, heads):
 
 
 @pytest.mark.parametrize("kv", ["bf16", "fp8"])
+@pytest.mark.parametrize("heads", [(8, 2), (16, 2)], ids=lambda h: f"{h[0]}q{h[1]}kv")
+def test_prefill_pipeline_boundaries(kv, heads):
+    """Chunks whose first and last tiles start at every kind of position relative to the 32-token
+    half-stages, the 64-token stages and the tile size: tiles with one, two, three ... half-stages,
+    with and without an unmasked steady state, prefixes that end inside a stage (cache tail beyond
+    ctx_len holds the poison pattern)."""
+    shape = AttnShape(heads[0], heads[1], 128, "bf16", kv)
+    pre = [0, 1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 159, 160, 191, 192, 193, 255, 257]
+    q = [2 + (7 * i) % 70 for i in range(len(pre))]
+    b = make_batch(shape, q, [a + c for a, c in zip(q, pre)], seed=43, pool_rule=1.2, value_mult=0.5)
+    check(b, options={"mixed_persistent": 0})
+
+
+def test_prefill_maximum_rises_late():
+    """Scores that keep growing along the context: the running maximum has to be raised again and
+    again after the weights were formed (large jumps included), in the steady state and in the
+    drain."""
+    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+    b = make_batch(shape, [300, 70], [1500, 400], seed=44, pool_rule=1.2, value_mult=0.5)
+    # scale the keys with their position: later keys score higher by construction for positive q . k
+    pos_pre = torch.cat([torch.arange(1200), torch.arange(330)]).float()
+    pos_new = torch.cat([1200 + torch.arange(300), 330 + torch.arange(70)]).float()
+    b.k_prefix = (b.k_prefix.float() * (1.0 + pos_pre / 60.0)[:, None, None]).to(b.k_prefix.dtype)
+    b.k_new = (b.k_new.float() * (1.0 + pos_new / 60.0)[:, None, None]).to(b.k_new.dtype)
+    check(b, options={"mixed_persistent": 0})
+
+
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
 def test_mixed_batch_one_pass(kv):
     shape = AttnShape(32, 8, 128, "bf16", kv)
     q = [1, 1, 200, 1, 0, 77, 1, 1, 512, 1]
