@@ -94,6 +94,21 @@ def instances_to_provision(requirement: float) -> int:
     return int(math.ceil(requirement))
 
 
+def largest_admissible_chunk(iteration_time_s: Sequence[float], tpot_slo_s: float) -> int:
+    """Chunk-size profiling of a Convertible Decoder (Sec. 4.4): the chunk size is raised step by
+    step and the iteration time measured until the TPOT SLO is violated; the largest size that
+    still met it is chosen.  iteration_time_s[i] is the time measured at the i-th (ascending) chunk
+    size.  Returns the index chosen, -1 when even the first size violates the SLO.  Reading: the
+    sweep stops at the first violation, so a larger size that happens to pass again is not looked
+    at."""
+    chosen = -1
+    for i, t in enumerate(iteration_time_s):
+        if not t <= tpot_slo_s:
+            break
+        chosen = i
+    return chosen
+
+
 PREFILLER, CONVERTIBLE, QUEUE = 0, 1, 2
 
 

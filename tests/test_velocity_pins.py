@@ -131,3 +131,22 @@ def test_decode_routing_hand_cases():
     assert ov.route_decode(inflight, 0, [False, False, False, False], util, 0.9) == 3  # regular decoders are never left out
     assert ov.route_decode([[1]], 0, [True], [0.99], 0.9) == -1
     assert ov.route_decode([], 0, [], [], 0.9) == -1
+
+
+def test_chunk_profiling_stops_at_the_first_violation():
+    """Sec. 4.4 on hand-made sweeps (TPOT SLO 100 ms, Sec. 5)."""
+    slo = 0.100
+    assert ov.largest_admissible_chunk([0.020, 0.040, 0.080, 0.100, 0.130, 0.300], slo) == 3   # meeting it exactly counts
+    assert ov.largest_admissible_chunk([0.020, 0.040, 0.101, 0.090, 0.095], slo) == 1           # later passes are not looked at
+    assert ov.largest_admissible_chunk([0.150, 0.050], slo) == -1
+    assert ov.largest_admissible_chunk([], slo) == -1
+    assert ov.largest_admissible_chunk([0.01, 0.02, 0.03], slo) == 2
+    assert ov.largest_admissible_chunk([0.01, math.nan, 0.02], slo) == 0
+    # growing the sweep never makes the choice smaller; tightening the SLO never makes it larger
+    rng = np.random.default_rng(9)
+    for _ in range(200):
+        t = np.cumsum(rng.uniform(0.001, 0.02, 12))
+        full = ov.largest_admissible_chunk(list(t), slo)
+        assert ov.largest_admissible_chunk(list(t[:6]), slo) <= full
+        assert ov.largest_admissible_chunk(list(t), slo * 0.5) <= full
+        assert full == int(np.searchsorted(t, slo, side="right")) - 1      # monotone sweep: a plain count
