@@ -19,6 +19,9 @@
 extern "C" {
 #endif
 
+#define TS_POLICY_NONE    (-1)   /* no eligible instance: queue the prefill task / reject the decode request */
+#define TS_POLICY_INVALID (-2)   /* NULL array with a positive count, negative count, type out of range */
+
 /* Decode velocity V_D (Sec. 3.2, first equation): sum of the tokens L_r held by the n requests
  * that completed during one decode iteration, over the measured TPOT.  Domain: tpot_s > 0,
  * L_r >= 0; n = 0 gives 0. */
@@ -49,6 +52,13 @@ double ts_tv_convertible_prefill_velocity(double chunk_size, double batch_size, 
  * Domain: all >= 0. */
 double ts_tv_reserved_memory(double v_d_p, double mem_t_bytes, double ttft_slo_s);
 
+/* Chunk-size profiling of a Convertible Decoder (Sec. 4.4): iteration_time_s[i] is the iteration
+ * time measured at the i-th chunk size of an ascending sweep.  Returns the index of the largest
+ * chunk size met before the first one that exceeds tpot_slo_s (a time equal to the SLO meets it; NaN
+ * does not), TS_POLICY_NONE when the first size already exceeds it or n = 0, TS_POLICY_INVALID for
+ * n < 0 or a NULL array with n > 0. */
+int ts_tv_largest_chunk(const double *iteration_time_s, int n, double tpot_slo_s);
+
 /* Mem_T of a cache geometry: bytes of K and V one token occupies in num_layers layers
  * (2 * num_kv_heads * head_dim * element size * num_layers).  0 for an invalid descriptor or
  * num_layers < 1. */
@@ -57,10 +67,6 @@ int64_t ts_tv_token_bytes(const ts_attn_desc *desc, int num_layers);
 /* The minimum number of instances that provides the required velocity (Sec. 4.3): the smallest
  * integer >= requirement.  TS_POLICY_INVALID for NaN, infinity or a negative requirement. */
 int64_t ts_tv_instances(double requirement);
-
-#define TS_POLICY_NONE    (-1)   /* no eligible instance: queue the prefill task / reject the decode request */
-#define TS_POLICY_INVALID (-2)   /* NULL array with a positive count, negative count, type out of range */
-
 #define TS_ROUTE_PREFILLER   0
 #define TS_ROUTE_CONVERTIBLE 1
 #define TS_ROUTE_QUEUE       2

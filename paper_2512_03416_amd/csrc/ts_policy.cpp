@@ -80,6 +80,14 @@ extern "C" double ts_tv_reserved_memory(double v_d_p, double mem_t_bytes, double
     return v_d_p * mem_t_bytes * ttft_slo_s;
 }
 
+extern "C" int ts_tv_largest_chunk(const double* iteration_time_s, int n, double tpot_slo_s)
+{
+    if (n < 0 || (n > 0 && !iteration_time_s)) return TS_POLICY_INVALID;
+    int chosen = TS_POLICY_NONE;
+    for (int i = 0; i < n && iteration_time_s[i] <= tpot_slo_s; ++i) chosen = i;   // stops at the first violation (or NaN)
+    return chosen;
+}
+
 extern "C" int64_t ts_tv_token_bytes(const ts_attn_desc* desc, int num_layers)
 {
     if (num_layers < 1 || ts_check_desc(desc) != TS_OK) return 0;

@@ -14,7 +14,7 @@ from .binding import Desc, load_library
 
 EXPORTS = ["ts_tv_decode_velocity", "ts_tv_prefillers", "ts_tv_decoders", "ts_tv_regular_decoders",
            "ts_tv_decode_batch", "ts_tv_convertible_prefill_velocity", "ts_tv_reserved_memory",
-           "ts_tv_token_bytes", "ts_tv_instances", "ts_route_prefill", "ts_route_decode"]
+           "ts_tv_token_bytes", "ts_tv_instances", "ts_tv_largest_chunk", "ts_route_prefill", "ts_route_decode"]
 
 NONE, INVALID = -1, -2
 PREFILLER, CONVERTIBLE, QUEUE = 0, 1, 2
@@ -40,6 +40,8 @@ def _lib():
         lib.ts_tv_token_bytes.restype = ctypes.c_int64
         lib.ts_tv_instances.argtypes = [d]
         lib.ts_tv_instances.restype = ctypes.c_int64
+        lib.ts_tv_largest_chunk.argtypes = [vp, ci, d]
+        lib.ts_tv_largest_chunk.restype = ci
         lib.ts_route_prefill.argtypes = [vp, vp, ci, vp, vp, ci, d, ctypes.POINTER(ci)]
         lib.ts_route_prefill.restype = ci
         lib.ts_route_decode.argtypes = [vp, ci, ci, ci, vp, vp, d]
@@ -95,6 +97,11 @@ def tv_token_bytes(desc: Desc, num_layers: int) -> int:
 
 def tv_instances(requirement: float) -> int:
     return _lib().ts_tv_instances(requirement)
+
+
+def tv_largest_chunk(iteration_time_s, tpot_slo_s: float) -> int:
+    t = _arr(iteration_time_s, np.float64)
+    return _lib().ts_tv_largest_chunk(_ptr(t), len(t), tpot_slo_s)
 
 
 def route_prefill(prefiller_inflight, prefiller_velocity, conv_inflight, conv_velocity,

@@ -371,3 +371,20 @@ def test_token_velocity_counters():
     assert abs(v.prefill_tok_per_s - 141 / v.window_s) < 1e-6 * v.prefill_tok_per_s + 1e-9
     assert ctx.token_velocity().passes == 0
     ctx.close()
+
+
+def test_chunk_size_profiler_sweep():
+    """Sec. 4.4 sweep on a small decoder: times grow with the chunk, the choice is the oracle's choice
+    on the measured times, velocity and reservation follow from it."""
+    from oracle import velocity as ov
+    from paper_2512_03416_amd import profiler
+    res = profiler.main(["--heads", "8,2", "--decode-batch", "16", "--ctx-min", "200", "--ctx-max", "600",
+                         "--chunks", "64,256,1024", "--layers", "4", "--tpot-slo-ms", "100", "--steps", "5"])
+    times = [p["iteration_attention_ms"] * 1e-3 for p in res["sweep"]]
+    assert all(t > 0 for t in times) and times[-1] > times[0]
+    assert res["chosen_index"] == ov.largest_admissible_chunk(times, res["attention_budget_ms"] * 1e-3)
+    if res["chosen_index"] >= 0:
+        c = res["sweep"][res["chosen_index"]]["chunk_size"]
+        v = ov.convertible_prefill_velocity(c, 16, 0.1)
+        assert res["prefill_velocity_tok_per_s"] == v
+        assert res["reserved_bytes"] == ov.reserved_memory(v, 2 * 2 * 128 * 2 * 4, 0.4)

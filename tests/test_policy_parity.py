@@ -104,3 +104,17 @@ def test_decode_routing_matches_oracle():
         none += got == policy.NONE
     assert none > 0
     assert policy.route_decode(np.zeros((2, 3), np.int32), 3, [0, 0], [0.1, 0.1], 0.9) == policy.INVALID
+
+
+def test_chunk_sweep_choice_matches_oracle():
+    rng = np.random.default_rng(15)
+    for _ in range(1000):
+        n = int(rng.integers(0, 14))
+        t = np.cumsum(rng.uniform(0.0, 0.03, n)) * rng.choice([1.0, 1.0, 1.0, -1.0]) ** 0
+        if n and rng.random() < 0.3:
+            t[rng.integers(0, n)] *= rng.choice([0.2, 3.0])           # a non-monotone sample
+        if n and rng.random() < 0.1:
+            t[rng.integers(0, n)] = math.nan
+        slo = float(rng.choice([0.05, 0.1, 0.2]))
+        assert policy.tv_largest_chunk(t, slo) == ov.largest_admissible_chunk(list(t), slo)
+    assert policy.tv_largest_chunk([], 0.1) == policy.NONE
