@@ -388,3 +388,18 @@ def test_chunk_size_profiler_sweep():
         v = ov.convertible_prefill_velocity(c, 16, 0.1)
         assert res["prefill_velocity_tok_per_s"] == v
         assert res["reserved_bytes"] == ov.reserved_memory(v, 2 * 2 * 128 * 2 * 4, 0.4)
+
+
+def test_burst_replay_accounts_for_every_token():
+    """A short 2 -> 12 requests/s step through one small Convertible Decoder: batches change shape
+    every iteration (new prefill task, rows finishing), the library's velocity counters see exactly
+    the rows that were submitted, every admitted request gets its first token."""
+    from paper_2512_03416_amd import replay
+    res = replay.main(["--heads", "8,2", "--seconds", "3", "--step-at", "1", "--rps", "2,12", "--drain", "2",
+                       "--in-median", "120", "--in-max", "600", "--out-median", "12", "--out-max", "40",
+                       "--chunk-size", "256", "--layers", "2", "--other-ms", "4", "--max-resident", "64"])
+    assert res["iterations"] > 50 and res["passes_counted"] == res["iterations"]
+    assert res["prefill_tokens_counted"] == res["prefill_tokens_submitted"]
+    assert res["decode_tokens_counted"] == res["decode_tokens_submitted"]
+    assert res["requests"] > 10 and res["first_tokens"] >= res["requests"] - 2
+    assert res["completed"] >= res["first_tokens"] - 40 and res["completed"] > 0
