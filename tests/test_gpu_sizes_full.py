@@ -59,3 +59,17 @@ def test_config4_burst_full_size_sampled():
     b = W.config4(device="cuda")
     dec = np.random.default_rng(8).choice(128, size=6, replace=False).tolist()
     _sampled_check(b, sorted(dec) + [128, 131], 7, 2e-2)      # every 7th row of the sample, two chunks included
+
+
+def test_config5_fp8_full_size_sampled():
+    b = W.config5(device="cuda")
+    assert b.shape.kv_dtype == "fp8" and b.num_seqs == 528
+    dec = np.random.default_rng(9).choice(512, size=5, replace=False).tolist()
+    longest = int(np.argmax(b.ctx_lens[:512]))
+    _sampled_check(b, sorted(set(dec + [longest])) + [512, 527], 61, 6e-2)   # two chunks, every 61st row of the sample
+
+
+@pytest.mark.parametrize("step", [0, 3])
+def test_config3_chunked_prefill_full_size_sampled(step):
+    b = W.config3_step(step, device="cuda")
+    _sampled_check(b, list(range(b.num_seqs)), 11, 2e-2)                     # every sequence, every 11th row
