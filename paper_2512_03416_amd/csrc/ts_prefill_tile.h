@@ -26,6 +26,7 @@
 //     instructions); fp8 caches are widened to bf16 by the threads while being staged, so the
 //     multiply loop is the same.
 #pragma once
+#include <type_traits>
 #include "ts_device.h"
 
 namespace ts {
@@ -290,10 +291,23 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // cores, weights of hs+1 on the vector ALU.  s1: scores of hs+1 (in), s2: scores of hs+2 (out),
     // pop0: weights of hs (in), pop1: weights of hs+1 (out).  16 slots of one MFMA each; a slot also
     // carries one weight (fused multiply-add, exp2, add to the sum, running maximum; every other slot
-    // a pack) and the LDS read of an operand needed four slots later.
-    auto fast_iter = [&](int hs, bool masked, const f32x16& s1, f32x16& s2, const bf16x8 (&pop0)[2], bf16x8 (&pop1)[2]) {
+    // a pack) and the LDS read of the operand needed four slots later.  The operands of the first
+    // slots arrive in vpre / kpre, read during the previous iteration; those of the next iteration
+    // are read during the last slots.  K operands cannot be read ahead across the barrier that
+    // publishes their stage: the first iteration of a body (KIN false) reads them at its top and
+    // starts with three V^T P^T slots.
+    bf16x8 vpre[2], kpre[2];
+    auto fast_iter = [&](auto kin_tag, auto kout_tag, int hs, bool masked, const f32x16& s1, f32x16& s2,
+                         const bf16x8 (&pop0)[2], bf16x8 (&pop1)[2]) {
+        constexpr bool KIN = decltype(kin_tag)::value, KOUT = decltype(kout_tag)::value;
+        // slot -> MFMA: values 0..7 = V^T P^T step u (page u / 4, dim block u % 4), 8..15 = K Q^T step u - 8
+        constexpr int kWarm[16] = {0, 8, 1, 9, 2, 10, 3, 11, 4, 12, 5, 13, 6, 14, 7, 15};
+        constexpr int kCold[16] = {0, 1, 2, 8, 3, 9, 4, 10, 5, 11, 6, 12, 7, 13, 14, 15};
         const unsigned char* lk = kptr(hs + 2);
         const unsigned char* lv = vptr(hs);
+        const unsigned char* lvn = vptr(hs + 1);
+        const unsigned char* lkn = kptr(hs + 3);
+        auto v_at = [&](const unsigned char* base, int u) { return lds16(base + (u >> 2) * 4096 + (u & 3) * 1024); };
         // The weights of hs+1 are formed against the current reference maximum without looking at the
         // scores first; a weight above 2^kRaisePf shows afterwards that the maximum has to be raised,
         // and only then are the weights of this half-stage formed again (the scores are still there).
@@ -303,26 +317,43 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         bf16x8 kop[KS], vop[2 * DB];
         uint32_t w[8];
         float p_even = 0.f;
+        vop[0] = vpre[0];
+        vop[1] = vpre[1];
         __builtin_amdgcn_sched_barrier(0);
-        // operands of the first slots
-        vop[0] = lds16(lv);
-        kop[0] = lds16(lk);
-        vop[1] = lds16(lv + 1024);
-        kop[1] = lds16(lk + 512);
+        if constexpr (KIN) {
+            kop[0] = kpre[0];
+            kop[1] = kpre[1];
+        } else {
+            vop[2] = v_at(lv, 2);
+            kop[0] = lds16(lk);
+            kop[1] = lds16(lk + 512);
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int u = j >> 1;
-            if ((j & 1) == 0) {
-                acc[u & 3] = mfma(vop[u], pop0[u >> 2], acc[u & 3]);
-                if (u + 2 < 2 * DB) vop[u + 2] = lds16(lv + ((u + 2) >> 2) * 4096 + ((u + 2) & 3) * 1024);
+            const int op = KIN ? kWarm[j] : kCold[j];
+            if (op < 8) {
+                acc[op & 3] = mfma(vop[op], pop0[op >> 2], acc[op & 3]);
             } else {
-                if (u == 0) {
+                if (op == 8) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) s2[v] = 0.f;
                 }
-                s2 = mfma(kop[u], qb[u], s2);
-                if (u + 2 < KS) kop[u + 2] = lds16(lk + (u + 2) * 512);
+                s2 = mfma(kop[op - 8], qb[op - 8], s2);
+            }
+            // read the operand of the MFMA four slots on (the first ones came with the iteration)
+            if (j + 4 < 16) {
+                const int nx = KIN ? kWarm[j + 4] : kCold[j + 4];
+                if (nx < 8) { if (nx >= (KIN ? 2 : 3)) vop[nx] = v_at(lv, nx); }
+                else if (nx - 8 >= 2) kop[nx - 8] = lds16(lk + (nx - 8) * 512);
+            } else {
+                // the last four slots read the first operands of the next iteration
+                if (j == 12) vpre[0] = v_at(lvn, 0);
+                if (j == 13) vpre[1] = v_at(lvn, 1);
+                if constexpr (KOUT) {
+                    if (j == 14) kpre[0] = lds16(lkn);
+                    if (j == 15) kpre[1] = lds16(lkn + 512);
+                }
             }
             const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[j], c, nm));
             l_part += p;
@@ -425,16 +456,20 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     const int n_plain = max(0, (hfull_tile - 2) / 2);      // 2i+3 < hfull_tile
     const int n_steady = max(0, (hend - 2) / 2);           // 2i+3 < hend
     int i = 0;
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+    vpre[0] = lds16(vptr(0));                              // V operands of the first iteration
+    vpre[1] = lds16(vptr(0) + 1024);
     for (; i < n_plain; ++i) {
         top(i);
-        fast_iter(2 * i, false, sA, sB, popA, popB);
-        fast_iter(2 * i + 1, false, sB, sA, popB, popA);
+        fast_iter(no, yes, 2 * i, false, sA, sB, popA, popB);
+        fast_iter(yes, no, 2 * i + 1, false, sB, sA, popB, popA);
         bottom(i);
     }
     for (; i < n_steady; ++i) {
         top(i);
-        fast_iter(2 * i, 2 * i + 2 >= hfull, sA, sB, popA, popB);
-        fast_iter(2 * i + 1, 2 * i + 3 >= hfull, sB, sA, popB, popA);
+        fast_iter(no, yes, 2 * i, 2 * i + 2 >= hfull, sA, sB, popA, popB);
+        fast_iter(yes, no, 2 * i + 1, 2 * i + 3 >= hfull, sB, sA, popB, popA);
         bottom(i);
     }
     for (; i < n_stage; ++i) {
