@@ -14,6 +14,8 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -77,5 +79,14 @@ __device__ __forceinline__ int64_t tile_elem_base(int64_t page, int Hkv, int g, 
 {
     return (page * Hkv + g) * (int64_t)(kPage * D);
 }
+
+// Stores of data this pass does not read again (new cache entries, outputs): the non-temporal hint
+// sends them on to memory instead of leaving partially written lines in the L2, whose write-back in
+// the middle of the decode scan was measured to cost ten times its byte share.
+__device__ __forceinline__ void store_nt(void* p, uint4 v)
+{
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, (u32x4*)p);
+}
+__device__ __forceinline__ void store_nt(void* p, uint2 v) { __builtin_nontemporal_store(u32x2{v.x, v.y}, (u32x2*)p); }
 
 }  // namespace ts

@@ -50,11 +50,11 @@ __global__ __launch_bounds__(256) void append_token_kernel(AppendArgs a)
         if constexpr (sizeof(DST) == 1) {
             const float kf = Elem<SRC>::load(ks, e) / a.k_scale[g];
             const float vf = Elem<SRC>::load(vs, e) / a.v_scale[g];
-            kc[kidx] = (uint8_t)float_to_e4m3_bits(kf);
-            vc[vidx] = (uint8_t)float_to_e4m3_bits(vf);
+            __builtin_nontemporal_store((uint8_t)float_to_e4m3_bits(kf), &kc[kidx]);
+            __builtin_nontemporal_store((uint8_t)float_to_e4m3_bits(vf), &vc[vidx]);
         } else {
-            kc[kidx] = (DST)ks[e];                 // same element type: plain copy of the bits
-            vc[vidx] = (DST)vs[e];
+            __builtin_nontemporal_store((DST)ks[e], &kc[kidx]);   // same element type: plain copy of the bits
+            __builtin_nontemporal_store((DST)vs[e], &vc[vidx]);
         }
     }
 }
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
         uint16_t* kt = (uint16_t*)a.k_cache + tile_elem_base(page, Hkv, g, D);
         uint16_t* vt = (uint16_t*)a.v_cache + tile_elem_base(page, Hkv, g, D);
         // K tile [16 chunks][16 slots][8]: this thread's own 16 bytes
-        if (mine) *(uint4*)(kt + (c * 16 + t) * 8) = kv;
+        if (mine) store_nt(kt + (c * 16 + t) * 8, kv);
         // V tile [128 dims][16 slots]: thread (dim = tid / 2, half = tid % 2) gathers 8 slots of one dim
         const int dim = tid >> 1, hf = tid & 1;
         uint16_t e[8];
@@ -97,12 +97,12 @@ __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
         for (int i = 0; i < 8; ++i) e[i] = vs[(8 * hf + i) * kRowPad + dim];
         uint16_t* dst = vt + dim * kPage + 8 * hf;
         if (full) {
-            *(uint4*)dst = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
-                                      e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+            store_nt(dst, make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
+                                     e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16)));
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                if (8 * hf + i >= it.slot_lo && 8 * hf + i < it.slot_hi) dst[i] = e[i];
+                if (8 * hf + i >= it.slot_lo && 8 * hf + i < it.slot_hi) __builtin_nontemporal_store(e[i], &dst[i]);
         }
     } else {
         uint8_t* kt = (uint8_t*)a.k_cache + tile_elem_base(page, Hkv, g, D);
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
                     const float x = bf16_bits_to_float(ks[slot * kRowPad + 16 * c16 + i]) / kscale;
                     w[i >> 2] |= float_to_e4m3_bits(x) << (8 * (i & 3));
                 }
-                *(uint4*)(kt + (c16 * 16 + slot) * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+                store_nt(kt + (c16 * 16 + slot) * 16, make_uint4(w[0], w[1], w[2], w[3]));
             }
         } else {
             // V tile [128 dims][16 slots]: thread dim = tid - 128 gathers the 16 slots of one dim
@@ -133,11 +133,11 @@ __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
             }
             uint8_t* dst = vt + dim * kPage;
             if (full) {
-                *(uint4*)dst = make_uint4(w[0], w[1], w[2], w[3]);
+                store_nt(dst, make_uint4(w[0], w[1], w[2], w[3]));
             } else {
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    if (i >= it.slot_lo && i < it.slot_hi) dst[i] = b[i];
+                    if (i >= it.slot_lo && i < it.slot_hi) __builtin_nontemporal_store(b[i], &dst[i]);
             }
         }
     }
