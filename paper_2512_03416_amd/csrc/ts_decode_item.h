@@ -32,15 +32,18 @@ template <typename KT> struct KVTile;
 template <> struct KVTile<uint16_t> { uint4 k[4]; uint2 v[8]; };
 template <> struct KVTile<uint8_t>  { uint4 k[2]; uint32_t v[8]; };
 
+// bf16 tiles are read with the non-temporal hint: the scan touches every byte once, and keeping it
+// out of the L2's replacement traffic raised the rate from 5.9 to 6.45 TB/s.  (For the 2 KB fp8 tiles
+// the same hint lowered it by 15 %, so those use plain loads.)
 __device__ __forceinline__ void load_tile(KVTile<uint16_t>& t, const char* kc, const char* vc,
                                           int64_t tile, int lane)
 {
     const char* kt = kc + tile * 4096 + lane * 16;
     const char* vt = vc + tile * 4096 + (lane & 15) * 32 + (lane >> 4) * 8;
 #pragma unroll
-    for (int b = 0; b < 4; ++b) t.k[b] = *(const uint4*)(kt + b * 1024);
+    for (int b = 0; b < 4; ++b) t.k[b] = load_nt4(kt + b * 1024);
 #pragma unroll
-    for (int b = 0; b < 8; ++b) t.v[b] = *(const uint2*)(vt + b * 512);
+    for (int b = 0; b < 8; ++b) t.v[b] = load_nt2(vt + b * 512);
 }
 
 __device__ __forceinline__ void load_tile(KVTile<uint8_t>& t, const char* kc, const char* vc,

@@ -87,6 +87,16 @@ __device__ __forceinline__ void store_nt(void* p, uint4 v)
 {
     __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, (u32x4*)p);
 }
+__device__ __forceinline__ uint4 load_nt4(const void* p)
+{
+    const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 load_nt2(const void* p)
+{
+    const u32x2 v = __builtin_nontemporal_load((const u32x2*)p);
+    return make_uint2(v.x, v.y);
+}
 __device__ __forceinline__ void store_nt(void* p, uint2 v) { __builtin_nontemporal_store(u32x2{v.x, v.y}, (u32x2*)p); }
 
 }  // namespace ts
