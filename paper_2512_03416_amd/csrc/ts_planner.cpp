@@ -88,14 +88,17 @@ int validate_batch(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* 
 // Pages per decode item.  A row that fits one item is finished by its workgroup without any
 // partial result in HBM, so rows are cut only (a) when they exceed one workgroup slot's fair share
 // of the batch (they would otherwise finish last), or (b) when the batch has too few rows to
-// occupy every slot.
+// occupy every slot.  In a mixed batch whose prefill tiles fill the chip on their own (persistent
+// launch: one resident workgroup per CU, a third of the stand-alone decode slots), (b) does not apply
+// and the fair share in (a) is that of a resident workgroup: measured on the burst configuration,
+// 706 -> 692 us and no combine launch.
 static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int64_t n_rows, int Hkv,
-                                int32_t wg_slots)
+                                int32_t wg_slots, bool filled_by_prefill)
 {
-    const int64_t slots = std::max<int32_t>(1, wg_slots);
+    const int64_t slots = std::max<int32_t>(1, filled_by_prefill ? wg_slots / 3 : wg_slots);
     int64_t L = std::max<int64_t>(32, (decode_tiles + slots - 1) / slots);
     const int64_t want_items = (3 * slots / 2 + Hkv - 1) / Hkv;        // per KV head
-    if (n_rows < want_items && decode_pages > 0)
+    if (!filled_by_prefill && n_rows < want_items && decode_pages > 0)
         L = std::min<int64_t>(L, std::max<int64_t>(8, (decode_pages + want_items - 1) / want_items));
     return (int32_t)std::min<int64_t>(L, 1 << 20);
 }
@@ -222,10 +225,16 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
         }
     }
 
+    const int32_t TT = opt.tile_tokens > 0 ? opt.tile_tokens : prefill_tile_tokens(d);
+    int64_t tile_heads = 0;                                // prefill workgroups of the batch
+    if (mfma && !opt.prefill_generic)
+        for (int s = 0; s < num_seqs; ++s)
+            if (p.seqs[s].q_len > 1) tile_heads += (int64_t)((p.seqs[s].q_len + TT - 1) / TT) * Hkv;
+    const bool filled_by_prefill = opt.mixed_persistent && tile_heads >= opt.wg_slots / 3;
     const int32_t L = opt.split_pages > 0
                           ? opt.split_pages
-                          : auto_split_pages(decode_tiles, decode_pages, p.info.decode_tokens, Hkv, opt.wg_slots);
-    const int32_t TT = opt.tile_tokens > 0 ? opt.tile_tokens : prefill_tile_tokens(d);
+                          : auto_split_pages(decode_tiles, decode_pages, p.info.decode_tokens, Hkv, opt.wg_slots,
+                                             filled_by_prefill);
     p.info.split_pages = L;
     p.info.tile_tokens = TT;
 
