@@ -70,12 +70,12 @@ static int launch_mixed_t(const AttnArgs& a, hipStream_t st)
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mixed_kernel<KT, 4>, kPfThreads, 0) != hipSuccess)
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mixed_kernel<KT, 2>, kPfThreads, 0) != hipSuccess)
             return (int)hipErrorUnknown;
         n = cus * (per_cu > 0 ? per_cu : 1);
     }
     const int grid = n < a.n_queue ? n : a.n_queue;
-    hipLaunchKernelGGL((mixed_kernel<KT, 4>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
+    hipLaunchKernelGGL((mixed_kernel<KT, 2>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
     return (int)hipGetLastError();
 }
 
