@@ -73,3 +73,24 @@ def test_config5_fp8_full_size_sampled():
 def test_config3_chunked_prefill_full_size_sampled(step):
     b = W.config3_step(step, device="cuda")
     _sampled_check(b, list(range(b.num_seqs)), 11, 2e-2)                     # every sequence, every 11th row
+
+
+def test_many_short_sequences():
+    """4096 decode rows with contexts of 1..64 tokens (first tokens, half-filled pages, page-opening
+    tokens): work lists far longer than the number of resident workgroups."""
+    rng = np.random.default_rng(21)
+    ctx = rng.integers(1, 65, 4096).tolist()
+    b = W.make_batch(W.AttnShape(32, 8, 128, "bf16", "bf16"), [1] * 4096, ctx, seed=21, pool_rule=1.1,
+                     value_mult=0.5, device="cuda")
+    _sampled_check(b, sorted(rng.choice(4096, size=64, replace=False).tolist()), 1, 2e-2)
+
+
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+def test_one_very_long_row_and_one_long_chunk(kv):
+    """A decode row over 131072 cached tokens (cut into many items whose partial results are merged)
+    next to a prefill chunk of 4096 tokens over a prefix of 12288, at the page-table limit of both."""
+    shape = W.AttnShape(32, 8, 128, "bf16", kv)
+    b = W.make_batch(shape, [1, 4096], [131072, 16384], seed=22, num_pages=8192 + 1024 + 8, value_mult=0.5,
+                     device="cuda")
+    assert b.max_pages_per_seq == 8192
+    _sampled_check(b, [0, 1], 257, 2e-2 if kv == "bf16" else 6e-2)
