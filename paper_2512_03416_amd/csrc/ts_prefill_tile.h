@@ -32,7 +32,7 @@
 namespace ts {
 
 constexpr float kRaisePf = 16.0f;
-constexpr float kBigWeight = 65536.0f;                   // 2^kRaisePf
+constexpr float kBigSum = 16.0f * 65536.0f;               // 16 weights of 2^kRaisePf
 constexpr int kStageTok = 64;
 
 __device__ __forceinline__ bf16x8 u4_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -48,6 +48,13 @@ __device__ __forceinline__ uint2 fp8x4_bf16x4(uint32_t w)
 }
 
 __device__ __forceinline__ float fmax3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
+
+// acc + lo + hi for a pair of packed bf16 values (one dot-product instruction against the pair (1, 1))
+__device__ __forceinline__ float add_bf16_pair(uint32_t w, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
+                                           false);
+}
 
 // keep the first n (0..8) 16-bit elements of a 16-byte vector (plain register arithmetic: local
 // arrays here end up in scratch memory and serialise the prefetch)
@@ -273,8 +280,8 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             for (int i = 0; i < 4; ++i) {
                 const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * i], c, nm));
                 const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * i + 1], c, nm));
-                l_part += p0 + p1;
                 w[i] = pack2(p0, p1);
+                l_part = add_bf16_pair(w[i], l_part);      // the sum runs over the rounded weights the product uses
             }
             pop[t] = u4_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
         }
@@ -309,14 +316,14 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         const unsigned char* lkn = kptr(hs + 3);
         auto v_at = [&](const unsigned char* base, int u) { return lds16(base + (u >> 2) * 4096 + (u & 3) * 1024); };
         // The weights of hs+1 are formed against the current reference maximum without looking at the
-        // scores first; a weight above 2^kRaisePf shows afterwards that the maximum has to be raised,
-        // and only then are the weights of this half-stage formed again (the scores are still there).
+        // scores first; their sum shows afterwards whether one of them was above 2^kRaisePf, i.e. that
+        // the maximum has to be raised (a sum above 16 x 2^kRaisePf needs such a weight; larger weights
+        // that stay below it are harmless: the bound only keeps the sums far from overflow), and only
+        // then are the weights of this half-stage formed again (the scores are still there).
         const float nm = -m_ref;
         const float l_before = l_part;
-        float p_max = 0.f;
         bf16x8 kop[KS], vop[2 * DB];
         uint32_t w[8];
-        float p_even = 0.f;
         vop[0] = vpre[0];
         vop[1] = vpre[1];
         __builtin_amdgcn_sched_barrier(0);
@@ -328,6 +335,11 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             kop[0] = lds16(lk);
             kop[1] = lds16(lk + 512);
         }
+        // The weight arithmetic is spread over the slots such that no instruction uses a result of its
+        // own slot: slot j scales score j+1, takes the exponential of score j, and packs / sums the
+        // weights j-2 and j-1 (odd j).
+        float t_next = __builtin_fmaf(s1[0], c, nm);
+        float p_a = 0.f, p_b = 0.f;                        // the two most recent weights
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
@@ -355,15 +367,22 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
                     if (j == 15) kpre[1] = lds16(lkn + 512);
                 }
             }
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[j], c, nm));
-            l_part += p;
-            p_max = __builtin_fmaxf(p_max, p);
-            if (j & 1) w[j >> 1] = pack2(p_even, p); else p_even = p;
+            if (j >= 2 && !(j & 1)) {                      // weights j-2 and j-1 are complete
+                w[(j - 2) >> 1] = pack2(p_a, p_b);
+                l_part = add_bf16_pair(w[(j - 2) >> 1], l_part);
+                asm volatile("" : "+v"(l_part));           // (keeps the two instructions in this slot)
+            }
+            const float t_cur = t_next;
+            if (j + 1 < 16) t_next = __builtin_fmaf(s1[j + 1], c, nm);
+            const float p = __builtin_amdgcn_exp2f(t_cur);
+            if (j & 1) p_b = p; else p_a = p;
             __builtin_amdgcn_sched_barrier(0);
         }
+        w[7] = pack2(p_a, p_b);
+        l_part = add_bf16_pair(w[7], l_part);
         pop1[0] = u4_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
         pop1[1] = u4_bf16x8(make_uint4(w[4], w[5], w[6], w[7]));
-        if (__any(!(p_max <= kBigWeight))) {               // rare; also catches infinities
+        if (__any(!(l_part - l_before <= kBigSum))) {      // rare; also catches infinities and NaN
             l_part = l_before;
             const float alpha = raise(lane_max(s1));
             weights_plain(s1, pop1);
@@ -412,9 +431,11 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             if (i + 3 < n_stage) pf_wait_copies<kCopiesPerStage>(); else pf_wait_copies<0>();
         }
         __syncthreads();
-        if (i + 2 == clear_stage) {                        // tile-uniform, at most once per tile
-            clear_v_tail(lds.v[clear_stage % kPfRing], clear_stage, it.ctx_len, tid);
-            __syncthreads();
+        if constexpr (kCopy) {
+            if (i + 2 == clear_stage) {                    // tile-uniform, at most once per tile
+                clear_v_tail(lds.v[clear_stage % kPfRing], clear_stage, it.ctx_len, tid);
+                __syncthreads();
+            }
         }
     };
     if constexpr (kCopy) {
@@ -431,9 +452,11 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         if (n_stage > 1) stage_store(st1, lds.k[1], lds.v[1], kStageTok, it.ctx_len, tid);
     }
     __syncthreads();
-    if (clear_stage == 0 || clear_stage == 1) {
-        clear_v_tail(lds.v[clear_stage], clear_stage, it.ctx_len, tid);
-        __syncthreads();
+    if constexpr (kCopy) {
+        if (clear_stage == 0 || clear_stage == 1) {
+            clear_v_tail(lds.v[clear_stage], clear_stage, it.ctx_len, tid);
+            __syncthreads();
+        }
     }
 
     // Fill the pipeline: weights of half-stage 0 and scores of half-stage 1 (every wave has at least
