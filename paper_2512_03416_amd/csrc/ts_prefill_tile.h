@@ -49,13 +49,6 @@ __device__ __forceinline__ uint2 fp8x4_bf16x4(uint32_t w)
 
 __device__ __forceinline__ float fmax3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
-// acc + lo + hi for a pair of packed bf16 values (one dot-product instruction against the pair (1, 1))
-__device__ __forceinline__ float add_bf16_pair(uint32_t w, float acc)
-{
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
-                                           false);
-}
-
 // keep the first n (0..8) 16-bit elements of a 16-byte vector (plain register arithmetic: local
 // arrays here end up in scratch memory and serialise the prefetch)
 __device__ __forceinline__ uint32_t mask16(int left) { return left >= 2 ? 0xffffffffu : (left == 1 ? 0xffffu : 0u); }
@@ -280,8 +273,8 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             for (int i = 0; i < 4; ++i) {
                 const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * i], c, nm));
                 const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * t + 2 * i + 1], c, nm));
+                l_part += p0 + p1;
                 w[i] = pack2(p0, p1);
-                l_part = add_bf16_pair(w[i], l_part);      // the sum runs over the rounded weights the product uses
             }
             pop[t] = u4_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
         }
@@ -336,8 +329,11 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             kop[1] = lds16(lk + 512);
         }
         // The weight arithmetic is spread over the slots such that no instruction uses a result of its
-        // own slot: slot j scales score j+1, takes the exponential of score j, and packs / sums the
-        // weights j-2 and j-1 (odd j).
+        // own slot: slot j scales score j+1, takes the exponential of score j, adds weight j-1 to the
+        // row sum and (even j) packs the weights j-2 and j-1.  Only instructions that measurably run in
+        // the shadow of an MFMA for free are used here (fma, exp, add, pack; the bf16 dot-product
+        // instruction, which would sum two packed weights at once, is not one of them: it delays the
+        // MFMAs of the SIMD).
         float t_next = __builtin_fmaf(s1[0], c, nm);
         float p_a = 0.f, p_b = 0.f;                        // the two most recent weights
         __builtin_amdgcn_sched_barrier(0);
@@ -367,10 +363,13 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
                     if (j == 15) kpre[1] = lds16(lkn + 512);
                 }
             }
-            if (j >= 2 && !(j & 1)) {                      // weights j-2 and j-1 are complete
-                w[(j - 2) >> 1] = pack2(p_a, p_b);
-                l_part = add_bf16_pair(w[(j - 2) >> 1], l_part);
-                asm volatile("" : "+v"(l_part));           // (keeps the two instructions in this slot)
+            if (j >= 1) {
+                l_part += (j & 1) ? p_a : p_b;             // weight j-1
+                asm volatile("" : "+v"(l_part));           // (keeps the instruction in this slot)
+                if (!(j & 1)) {
+                    w[(j - 2) >> 1] = pack2(p_a, p_b);
+                    asm volatile("" : "+v"(w[(j - 2) >> 1]));
+                }
             }
             const float t_cur = t_next;
             if (j + 1 < 16) t_next = __builtin_fmaf(s1[j + 1], c, nm);
@@ -378,8 +377,8 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             if (j & 1) p_b = p; else p_a = p;
             __builtin_amdgcn_sched_barrier(0);
         }
+        l_part += p_b;
         w[7] = pack2(p_a, p_b);
-        l_part = add_bf16_pair(w[7], l_part);
         pop1[0] = u4_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
         pop1[1] = u4_bf16x8(make_uint4(w[4], w[5], w[6], w[7]));
         if (__any(!(l_part - l_before <= kBigSum))) {      // rare; also catches infinities and NaN
