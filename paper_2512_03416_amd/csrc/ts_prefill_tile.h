@@ -96,7 +96,7 @@ __device__ __forceinline__ uint32_t lds_address(const void* p)
 // ---- bf16 cache: the memory system copies a stage straight into LDS -------------------------------
 // One instruction moves 64 x 16 bytes: lane l's piece lands at lds_addr + 16 l (the instruction offset
 // advances both the global and the LDS address).  A wave moves 2 KB of K and 2 KB of V per stage:
-// half of page `wave / 2`.  The copies are counted by vmcnt like any load; nothing here tells the
+// half of page `wave / 2` of the stage.  The copies are counted by vmcnt like any load; nothing here tells the
 // compiler that LDS changes, so the caller waits (pf_wait_copies) and publishes with a barrier.
 __device__ __forceinline__ void copy_2k_to_lds(uint32_t lds_addr, const void* base, uint32_t lane_off)
 {
@@ -105,18 +105,24 @@ __device__ __forceinline__ void copy_2k_to_lds(uint32_t lds_addr, const void* ba
                  "global_load_lds_dwordx4 %1, %2 offset:1024\n"
                  :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }
-__device__ __forceinline__ void stage_copy_bf16(const AttnArgs& a, const int32_t TS_CONSTANT* bt, int stage,
-                                                int last_page, int g, int wave, int lane, PfLds& lds)
+template <int OFF>
+__device__ __forceinline__ void copy_1k_to_lds(uint32_t lds_addr, const void* base, uint32_t lane_off)
 {
-    const int page = min(stage * 4 + (wave >> 1), last_page);          // wave-uniform
-    const int64_t off = ((int64_t)bt[page] * a.geo.Hkv + g) * 4096 + (wave & 1) * 2048;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %1, %2 offset:%3\n"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base), "n"(OFF) : "memory");
+}
+__device__ __forceinline__ int copy_k_lane_offset(int lane) { return (lane >> 4) * 256 + swap23(lane & 15) * 16; }
+__device__ __forceinline__ int copy_v_lane_offset(int lane) { return (lane & 31) * 32 + (lane >> 5) * 16; }
+__device__ __forceinline__ void stage_copy_bf16(const AttnArgs& a, int stage, int page_id, int g, int wave, int lane,
+                                                PfLds& lds)
+{
+    const int64_t off = ((int64_t)page_id * a.geo.Hkv + g) * 4096 + (wave & 1) * 2048;   // (page_id: of page 4 stage + wave / 2)
     const int slot = stage % kPfRing;
     // K: LDS piece [c0 + lane / 16][lane % 16] takes cache piece (c0 + lane / 16, swap23(lane % 16))
-    const int k_src = (lane >> 4) * 256 + swap23(lane & 15) * 16;
     // V: LDS piece [b0][lane / 32][lane % 32] takes cache piece (dim 32 b0 + lane % 32, half lane / 32)
-    const int v_src = (lane & 31) * 32 + (lane >> 5) * 16;
-    copy_2k_to_lds(lds_address(lds.k[slot]) + wave * 2048, (const char*)a.k_cache + off, k_src);
-    copy_2k_to_lds(lds_address(lds.v[slot]) + wave * 2048, (const char*)a.v_cache + off, v_src);
+    copy_2k_to_lds(lds_address(lds.k[slot]) + wave * 2048, (const char*)a.k_cache + off, copy_k_lane_offset(lane));
+    copy_2k_to_lds(lds_address(lds.v[slot]) + wave * 2048, (const char*)a.v_cache + off, copy_v_lane_offset(lane));
 }
 constexpr int kCopiesPerStage = 4;                         // vmcnt units one stage_copy_bf16 adds per wave
 template <int N> __device__ __forceinline__ void pf_wait_copies()
@@ -140,11 +146,9 @@ __device__ __forceinline__ void clear_v_tail(unsigned char* lv, int stage, int c
 // ---- fp8 cache: 4 pages x 2048 bytes = 512 chunks of 16 bytes of K and of V, one each per thread,
 // widened to bf16 on the way into LDS -------------------------------------------------------------
 struct StageFp8 { uint4 k0, v0; };                          // (named members: arrays end up in scratch memory)
-__device__ __forceinline__ void stage_fetch(StageFp8& st, const AttnArgs& a, const int32_t TS_CONSTANT* bt, int kv0,
-                                            int last_page, int g, int tid)
+__device__ __forceinline__ void stage_fetch(StageFp8& st, const AttnArgs& a, int page_id, int g, int tid)
 {
-    const int pg = __builtin_amdgcn_readfirstlane(tid >> 7);      // uniform within a wave
-    const int64_t tile = (int64_t)bt[min(kv0 / kPage + pg, last_page)] * a.geo.Hkv + g;
+    const int64_t tile = (int64_t)page_id * a.geo.Hkv + g;        // (page_id: of page 4 stage + wave / 2)
     st.k0 = *(const uint4*)((const char*)a.k_cache + tile * 2048 + (tid & 127) * 16);
     st.v0 = *(const uint4*)((const char*)a.v_cache + tile * 2048 + (tid & 127) * 16);
 }
@@ -296,10 +300,25 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // are read during the last slots.  K operands cannot be read ahead across the barrier that
     // publishes their stage: the first iteration of a body (KIN false) reads them at its top and
     // starts with three V^T P^T slots.
+    //
+    // bf16 caches: the four copy instructions with which a wave brings in its part of the next stage are
+    // issued from four slots of the first iteration of a body (DMA true).  Issued together at the top of
+    // the body, right after the barrier, the 32 copies of the workgroup fill the queue of the memory
+    // pipeline and every wave waits until its own have been accepted (measured: 0.11-0.17 us per body).
+    uint32_t cp_lds_k = 0, cp_lds_v = 0;                   // set by top(): where the copy goes ...
+    const char* cp_k = nullptr;                            // ... and what it reads (wave-uniform)
+    const char* cp_v = nullptr;
+    const int cp_k_src = copy_k_lane_offset(lane), cp_v_src = copy_v_lane_offset(lane);
+    auto copy_quarter = [&](int q) {
+        if (q == 0) copy_1k_to_lds<0>(cp_lds_k, cp_k, cp_k_src);
+        if (q == 1) copy_1k_to_lds<1024>(cp_lds_k, cp_k, cp_k_src);
+        if (q == 2) copy_1k_to_lds<0>(cp_lds_v, cp_v, cp_v_src);
+        if (q == 3) copy_1k_to_lds<1024>(cp_lds_v, cp_v, cp_v_src);
+    };
     bf16x8 vpre[2], kpre[2];
-    auto fast_iter = [&](auto kin_tag, auto kout_tag, int hs, bool masked, const f32x16& s1, f32x16& s2,
+    auto fast_iter = [&](auto kin_tag, auto kout_tag, auto dma_tag, int hs, bool masked, const f32x16& s1, f32x16& s2,
                          const bf16x8 (&pop0)[2], bf16x8 (&pop1)[2]) {
-        constexpr bool KIN = decltype(kin_tag)::value, KOUT = decltype(kout_tag)::value;
+        constexpr bool KIN = decltype(kin_tag)::value, KOUT = decltype(kout_tag)::value, DMA = decltype(dma_tag)::value;
         // slot -> MFMA: values 0..7 = V^T P^T step u (page u / 4, dim block u % 4), 8..15 = K Q^T step u - 8
         constexpr int kWarm[16] = {0, 8, 1, 9, 2, 10, 3, 11, 4, 12, 5, 13, 6, 14, 7, 15};
         constexpr int kCold[16] = {0, 1, 2, 8, 3, 9, 4, 10, 5, 11, 6, 12, 7, 13, 14, 15};
@@ -375,6 +394,9 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             if (j + 1 < 16) t_next = __builtin_fmaf(s1[j + 1], c, nm);
             const float p = __builtin_amdgcn_exp2f(t_cur);
             if (j & 1) p_b = p; else p_a = p;
+            if constexpr (DMA) {
+                if ((j & 3) == 3) copy_quarter(j >> 2);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         l_part += p_b;
@@ -414,20 +436,39 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     const int clear_stage = (kCopy && it.ctx_len % kStageTok != 0 && it.ctx_len / kStageTok < n_stage)
                                 ? it.ctx_len / kStageTok : -1;
     StageFp8 st;
+    // Page of a stage this wave stages (a tile that ends inside the last page of the sequence repeats that
+    // page).  The id comes through the scalar cache.  Read where it is used, the latency of that
+    // dependent load would hold up every wave of the workgroup right after the barrier, when no wave
+    // has anything else to issue; so the id that top(i+1) needs is requested between the two iterations
+    // of body i, where the wait for it falls into a phase in which the other wave of the SIMD has work.
+    auto page_id = [&](int stage) { return bt[min(stage * 4 + (wave >> 1), last_page)]; };
+    int32_t pid_next;                                      // page id top(i) needs: that of stage i + 3
+    // top(i), bf16: a steady body always copies "stage i+3" into the ring slot of stage i-1, whose last
+    // reader finished before the barrier that ended body i-1; beyond the last stage that is the last
+    // page again (nobody reads it).  The bodies of the draining loop copy nothing.
     auto top = [&](int i) {
         if constexpr (kCopy) {
-            if (i + 3 < n_stage) stage_copy_bf16(a, bt, i + 3, last_page, g, wave, lane, lds);
+            const int64_t off = ((int64_t)pid_next * a.geo.Hkv + g) * 4096 + (wave & 1) * 2048;
+            cp_lds_k = lds_address(lds.k[(i + 3) % kPfRing]) + wave * 2048;
+            cp_lds_v = lds_address(lds.v[(i + 3) % kPfRing]) + wave * 2048;
+            cp_k = (const char*)a.k_cache + off;
+            cp_v = (const char*)a.v_cache + off;
         } else {
             if (i + 2 < n_stage) {
                 stage_store(st, lds.k[(i + 2) % kPfRing], lds.v[(i + 2) % kPfRing], (i + 2) * kStageTok, it.ctx_len, tid);
-                if (i + 3 < n_stage) stage_fetch(st, a, bt, (i + 3) * kStageTok, last_page, g, tid);
+                if (i + 3 < n_stage) stage_fetch(st, a, pid_next, g, tid);
             }
         }
     };
-    auto bottom = [&](int i) {
+    auto request_page_id = [&](int i) {                    // between the two iterations of body i
+        __builtin_amdgcn_sched_barrier(0);
+        pid_next = page_id(i + 4);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto bottom = [&](int i, auto steady_tag) {
         if constexpr (kCopy) {
-            // the copies of stage i+2 must have landed; those of stage i+3 (if any) may still fly
-            if (i + 3 < n_stage) pf_wait_copies<kCopiesPerStage>(); else pf_wait_copies<0>();
+            // the copies of stage i+2 must have landed; those this body issued (steady bodies) may still fly
+            if constexpr (decltype(steady_tag)::value) pf_wait_copies<kCopiesPerStage>(); else pf_wait_copies<0>();
         }
         __syncthreads();
         if constexpr (kCopy) {
@@ -438,16 +479,20 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         }
     };
     if constexpr (kCopy) {
-        stage_copy_bf16(a, bt, 0, last_page, g, wave, lane, lds);
-        if (n_stage > 1) stage_copy_bf16(a, bt, 1, last_page, g, wave, lane, lds);
-        if (n_stage > 2) { stage_copy_bf16(a, bt, 2, last_page, g, wave, lane, lds); pf_wait_copies<kCopiesPerStage>(); }
+        const int32_t p0 = page_id(0), p1 = page_id(1), p2 = page_id(2);
+        pid_next = page_id(3);
+        stage_copy_bf16(a, 0, p0, g, wave, lane, lds);
+        if (n_stage > 1) stage_copy_bf16(a, 1, p1, g, wave, lane, lds);
+        if (n_stage > 2) { stage_copy_bf16(a, 2, p2, g, wave, lane, lds); pf_wait_copies<kCopiesPerStage>(); }
         else pf_wait_copies<0>();
     } else {
+        const int32_t p0 = page_id(0), p1 = page_id(1), p2 = page_id(2);
+        pid_next = page_id(3);
         StageFp8 st1;
-        stage_fetch(st, a, bt, 0, last_page, g, tid);
-        if (n_stage > 1) stage_fetch(st1, a, bt, kStageTok, last_page, g, tid);
+        stage_fetch(st, a, p0, g, tid);
+        if (n_stage > 1) stage_fetch(st1, a, p1, g, tid);
         stage_store(st, lds.k[0], lds.v[0], 0, it.ctx_len, tid);
-        if (n_stage > 2) stage_fetch(st, a, bt, 2 * kStageTok, last_page, g, tid);
+        if (n_stage > 2) stage_fetch(st, a, p2, g, tid);
         if (n_stage > 1) stage_store(st1, lds.k[1], lds.v[1], kStageTok, it.ctx_len, tid);
     }
     __syncthreads();
@@ -480,25 +525,28 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     int i = 0;
     constexpr std::true_type yes{};
     constexpr std::false_type no{};
+    constexpr std::bool_constant<kCopy> dma{};
     vpre[0] = lds16(vptr(0));                              // V operands of the first iteration
     vpre[1] = lds16(vptr(0) + 1024);
     for (; i < n_plain; ++i) {
         top(i);
-        fast_iter(no, yes, 2 * i, false, sA, sB, popA, popB);
-        fast_iter(yes, no, 2 * i + 1, false, sB, sA, popB, popA);
-        bottom(i);
+        fast_iter(no, yes, dma, 2 * i, false, sA, sB, popA, popB);
+        request_page_id(i);
+        fast_iter(yes, no, no, 2 * i + 1, false, sB, sA, popB, popA);
+        bottom(i, yes);
     }
     for (; i < n_steady; ++i) {
         top(i);
-        fast_iter(no, yes, 2 * i, 2 * i + 2 >= hfull, sA, sB, popA, popB);
-        fast_iter(yes, no, 2 * i + 1, 2 * i + 3 >= hfull, sB, sA, popB, popA);
-        bottom(i);
+        fast_iter(no, yes, dma, 2 * i, 2 * i + 2 >= hfull, sA, sB, popA, popB);
+        request_page_id(i);
+        fast_iter(yes, no, no, 2 * i + 1, 2 * i + 3 >= hfull, sB, sA, popB, popA);
+        bottom(i, yes);
     }
     for (; i < n_stage; ++i) {
-        top(i);
+        if constexpr (!kCopy) top(i);
         if (2 * i < hend) slow_iter(2 * i, sA, sB, popA, popB);
         if (2 * i + 1 < hend) slow_iter(2 * i + 1, sB, sA, popB, popA);
-        bottom(i);
+        bottom(i, no);
     }
     // (the last body ended with a barrier: lds may be reused by the caller)
 
