@@ -288,6 +288,11 @@ extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
         return TS_ERR_HIP;
     }
     if (device < 0 || device >= n_dev) { g_create_error = "device index out of range"; return TS_ERR_INVALID_ARG; }
+    struct Restore {                                       // the caller's current device comes back on return
+        int prev = -1;
+        ~Restore() { if (prev >= 0) (void)hipSetDevice(prev); }
+    } restore;
+    if (hipGetDevice(&restore.prev) != hipSuccess || restore.prev == device) restore.prev = -1;
     e = hipSetDevice(device);
     if (e != hipSuccess) { g_create_error = std::string("hipSetDevice: ") + hipGetErrorString(e); return TS_ERR_HIP; }
     ts_ctx* c = new (std::nothrow) ts_ctx();
