@@ -142,6 +142,25 @@ def calibrate(nbytes: int = 2 << 30):
         b.record()
         torch.cuda.synchronize()
         out[name + "_GBps"] = moved * 10 / (a.elapsed_time(b) * 1e-3) / 1e9
+    del src, dst
+    # what the matrix cores sustain on data like the workload's (normally distributed bf16) and on
+    # constant operands: the clock the chip holds under a full MFMA stream depends on the data
+    g = torch.Generator(device="cuda").manual_seed(7)
+    normal = torch.randn(65536, device="cuda", generator=g).to(torch.bfloat16)
+    const = torch.full((65536,), 0.0078125, device="cuda", dtype=torch.bfloat16)
+    for name, ops, softmax in (("mfma_normal_TFLOPs", normal, False), ("mfma_softmax_normal_TFLOPs", normal, True),
+                               ("mfma_constant_TFLOPs", const, False)):
+        for _ in range(2):
+            ts.calib_mfma(ops, res, 4000, softmax)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        flops = 0
+        for _ in range(3):
+            flops += ts.calib_mfma(ops, res, 20000, softmax)
+        b.record()
+        torch.cuda.synchronize()
+        out[name] = flops / (a.elapsed_time(b) * 1e-3) / 1e12
     return out
 
 

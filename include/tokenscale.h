@@ -181,6 +181,15 @@ int ts_kernel_times(ts_ctx *ctx, ts_kernel_stats *out, int reset);
 int ts_calib_copy(void *stream, const void *src, void *dst, int64_t bytes);
 int ts_calib_read(void *stream, const void *src, void *result4, int64_t bytes);
 
+/* Calibration helper for the matrix cores: one resident workgroup per CU issues `iters` x 16
+ * bf16 32x32x16 MFMAs per wave (8 waves, two per SIMD) back to back, A operands read from LDS as in
+ * the prefill kernel; softmax != 0 adds that kernel's vector work per MFMA (multiply-add,
+ * exponential, add, half a pack).  operands: DEV, 131072 bytes of bf16 values of the caller's
+ * choosing (the rate the chip sustains depends on how many bits toggle: the clock it holds under
+ * this load is set by its power limit); result4: DEV, 4 bytes; iters: 1..200000; *flops (HOST) is
+ * set to the floating-point operations of the launch.  Asynchronous on `stream`. */
+int ts_calib_mfma(void *stream, const void *operands, void *result4, int iters, int softmax, int64_t *flops);
+
 /* Host only -- step a0.  Describes the work the planner makes of a batch, without touching a
  * GPU: how many decode split items, combine rows, prefill tiles and generic rows.
  * split_pages = 0 lets the planner choose. */

@@ -17,7 +17,7 @@ TS_VELOCITY_RESET, TS_VELOCITY_SYNC = 1, 2
 EXPORTS = ["ts_check_desc", "ts_cache_bytes", "ts_create", "ts_destroy", "ts_reserve", "ts_kv_append",
            "ts_mixed_paged_attention", "ts_token_velocity", "ts_last_error", "ts_set_option",
            "ts_plan_describe", "ts_plan_export", "ts_kernel_times", "ts_calib_copy",
-           "ts_calib_read"]
+           "ts_calib_read", "ts_calib_mfma"]
 
 KERNEL_NAMES = ["append", "decode", "combine", "prefill", "rows", "mixed"]
 
@@ -110,6 +110,8 @@ def load_library():
     lib.ts_calib_copy.restype = ctypes.c_int
     lib.ts_calib_read.argtypes = [vp, vp, vp, ctypes.c_int64]
     lib.ts_calib_read.restype = ctypes.c_int
+    lib.ts_calib_mfma.argtypes = [vp, vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]
+    lib.ts_calib_mfma.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -264,3 +266,13 @@ def calib_read(src, result4, nbytes: int, stream=None):
     rc = load_library().ts_calib_read(Context._stream(stream), _dev_ptr(src), _dev_ptr(result4), nbytes)
     if rc != TS_OK:
         raise TokenScaleError(rc, "ts_calib_read")
+
+
+def calib_mfma(operands, result4, iters: int, softmax: bool, stream=None) -> int:
+    """Launches the MFMA calibration stream; returns the floating-point operations of the launch."""
+    flops = ctypes.c_int64(0)
+    rc = load_library().ts_calib_mfma(Context._stream(stream), _dev_ptr(operands), _dev_ptr(result4), int(iters),
+                                      int(bool(softmax)), ctypes.byref(flops))
+    if rc != 0:
+        raise TokenScaleError(rc, "ts_calib_mfma")
+    return int(flops.value)

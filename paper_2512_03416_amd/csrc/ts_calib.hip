@@ -1,11 +1,74 @@
-// Bandwidth calibration kernels: a plain streaming copy and a streaming read of known size.
-// They give the HBM counters and the achievable-bandwidth figure a fixed point to be scaled
-// against; they are not part of the attention pass.
+// Calibration kernels: a plain streaming copy and a streaming read of known size, and a stream of
+// bf16 MFMAs on caller-supplied operands.  They give the HBM counters, the achievable-bandwidth figure
+// and the matrix-core rate the chip sustains on given data a fixed point; they are not part of the
+// attention pass.
 #include <hip/hip_runtime.h>
 
 #include "tokenscale.h"
+#include "ts_device.h"
 
 namespace {
+
+using ts::bf16x8;
+using ts::bf16x2;
+using ts::f32x2;
+using ts::f32x16;
+
+// One workgroup of 8 waves per CU, two waves per SIMD.  Per slot a wave issues one 32x32x16 bf16 MFMA
+// whose A operand it reads from LDS (16 bytes per lane, as the prefill kernel does) and, with SOFTMAX,
+// the vector work the prefill kernel does per MFMA: a fused multiply-add, an exponential, an add and
+// half a pack, none of them using a result of its own slot.  The scores fed to the exponential come
+// from the operand data as well (16 per lane, the same in every iteration, as far as the compiler
+// knows new ones), so every value in flight depends on that data.
+template <bool SOFTMAX>
+__global__ __launch_bounds__(512) void calib_mfma_kernel(const uint4* __restrict__ operands, float* result, int iters)
+{
+    __shared__ __align__(16) unsigned char lds[131072];
+    for (int i = threadIdx.x; i < 131072 / 16; i += blockDim.x) ((uint4*)lds)[i] = operands[i];
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    f32x16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    const bf16x8 b = __builtin_bit_cast(bf16x8, *(const uint4*)(lds + 65536 + threadIdx.x * 16));
+    const unsigned char* base = lds + lane * 16;
+    bf16x8 opnd[4];
+    for (int u = 0; u < 4; ++u) opnd[u] = __builtin_bit_cast(bf16x8, *(const uint4*)(base + u * 1024));
+    float lsum = 0.f, pa = 0.f, pb = 0.f, tn = 0.f;
+    uint32_t wacc = 0;
+    float x[16];
+    for (int j = 0; j < 16; ++j)
+        x[j] = __uint_as_float((uint32_t)((const uint16_t*)lds)[(threadIdx.x * 16 + j) & 65535] << 16);
+    for (int it = 0; it < iters; ++it) {
+        const unsigned char* p = base + ((it & 7) << 14);
+        if (SOFTMAX) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) asm volatile("" : "+v"(x[j]));
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[j & 3], b, acc[j & 3], 0, 0, 0);
+            opnd[j & 3] = __builtin_bit_cast(bf16x8, *(const uint4*)(p + j * 1024));
+            if (SOFTMAX) {
+                lsum += (j & 1) ? pa : pb;
+                if (j >= 2 && !(j & 1)) wacc ^= __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pa, pb}, bf16x2));
+                const float tc = tn;
+                tn = __builtin_fmaf(x[(j + 1) & 15], 0.1275f, -1.0f);
+                const float pw = __builtin_amdgcn_exp2f(tc);
+                if (j & 1) pb = pw; else pa = pw;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // keep the accumulators bounded: the magnitudes, and with them the bits that toggle, stay the same
+        if ((it & 15) == 15)
+            for (int i = 0; i < 4; ++i)
+                for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    }
+    float s = lsum + (float)wacc;
+    for (int i = 0; i < 4; ++i)
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+    if (s == 1.2345678e-30f) *result = s;       // practically never taken: keeps the arithmetic alive
+}
 
 __global__ __launch_bounds__(256) void calib_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
                                                          int64_t n16)
@@ -40,5 +103,23 @@ extern "C" int ts_calib_read(void* stream, const void* src, void* result4, int64
     if (!src || !result4 || bytes <= 0 || bytes % 16) return TS_ERR_INVALID_ARG;
     hipLaunchKernelGGL(calib_read_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
                        (unsigned*)result4, bytes / 16);
+    return hipGetLastError() == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+extern "C" int ts_calib_mfma(void* stream, const void* operands, void* result4, int iters, int softmax,
+                             int64_t* flops)
+{
+    if (!operands || !result4 || !flops || iters <= 0 || iters > 200000) return TS_ERR_INVALID_ARG;
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+        return TS_ERR_HIP;
+    if (softmax)
+        hipLaunchKernelGGL(calib_mfma_kernel<true>, dim3(n_cu), dim3(512), 0, (hipStream_t)stream,
+                           (const uint4*)operands, (float*)result4, iters);
+    else
+        hipLaunchKernelGGL(calib_mfma_kernel<false>, dim3(n_cu), dim3(512), 0, (hipStream_t)stream,
+                           (const uint4*)operands, (float*)result4, iters);
+    *flops = (int64_t)n_cu * 8 * iters * 16 * 32768;
     return hipGetLastError() == hipSuccess ? TS_OK : TS_ERR_HIP;
 }

@@ -403,3 +403,17 @@ def test_burst_replay_accounts_for_every_token():
     assert res["decode_tokens_counted"] == res["decode_tokens_submitted"]
     assert res["requests"] > 10 and res["first_tokens"] >= res["requests"] - 2
     assert res["completed"] >= res["first_tokens"] - 40 and res["completed"] > 0
+
+
+def test_mfma_calibration_stream_runs_and_counts_its_work():
+    """The calibration launch returns, leaves the result word alone and reports
+    CUs x 8 waves x iters x 16 MFMAs x 32768 flop."""
+    import paper_2512_03416_amd as ts
+    ops = torch.randn(65536, device="cuda").to(torch.bfloat16)
+    res = torch.zeros(1, dtype=torch.float32, device="cuda")
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    for softmax in (False, True):
+        flops = ts.calib_mfma(ops, res, 50, softmax)
+        torch.cuda.synchronize()
+        assert flops == n_cu * 8 * 50 * 16 * 32768
+        assert float(res.item()) == 0.0

@@ -151,3 +151,17 @@ def test_create_without_gpu_fails_loudly():
     with pytest.raises(ts.TokenScaleError) as e:
         ts.Context(D())
     assert e.value.code == binding.TS_ERR_HIP
+
+
+def test_calibration_helpers_reject_bad_arguments_before_touching_a_gpu():
+    lib = binding.load_library()
+    flops = ctypes.c_int64(-1)
+    one = ctypes.c_void_p(16)                                  # never dereferenced: the checks come first
+    assert lib.ts_calib_mfma(None, None, one, 10, 0, ctypes.byref(flops)) == -1
+    assert lib.ts_calib_mfma(None, one, None, 10, 0, ctypes.byref(flops)) == -1
+    assert lib.ts_calib_mfma(None, one, one, 0, 0, ctypes.byref(flops)) == -1
+    assert lib.ts_calib_mfma(None, one, one, 200001, 1, ctypes.byref(flops)) == -1
+    assert lib.ts_calib_mfma(None, one, one, 10, 1, None) == -1
+    assert flops.value == -1
+    assert lib.ts_calib_copy(None, one, one, 24) == -1         # not a multiple of 16
+    assert lib.ts_calib_read(None, one, None, 32) == -1
