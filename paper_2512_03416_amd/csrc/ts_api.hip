@@ -27,7 +27,8 @@ thread_local std::string g_create_error;
 constexpr int kRing = 4;
 
 struct HostSlot {
-    void* ptr = nullptr;
+    void* ptr = nullptr;             // pinned host memory ...
+    void* dev_ptr = nullptr;         // ... and the address the GPU reads it at
     size_t cap = 0;
     hipEvent_t ev = nullptr;
     bool pending = false;
@@ -53,11 +54,12 @@ struct ts_ctx {
     uint64_t prefill_tokens = 0, decode_tokens = 0, passes = 0;
     bool window_open = false;
     std::chrono::steady_clock::time_point t0;
-    hipEvent_t last_pass = nullptr;
-    bool have_last = false;
-    // the work-list buffer is reused by every call: a call on another stream than the previous one
-    // first waits for that one's kernels
-    hipEvent_t work_done = nullptr;
+    // One event per call, recorded behind its last kernel (the staging slot's): it frees the slot, it is
+    // what a call on another stream waits for (the work-list buffer, the partials and the queue heads
+    // are reused by every call), and it ends the last pass for the velocity counters.  (Every event
+    // record keeps the GPU idle for about 5 us, so a call records exactly one.)
+    HostSlot* cur_slot = nullptr;      // slot of the call in progress
+    hipEvent_t last_event = nullptr;   // event of the most recent call
     hipStream_t last_stream = nullptr;
     bool have_work = false;
     // optional per-kernel timing
@@ -136,17 +138,33 @@ int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out)
     HostSlot& s = c->ring[c->ring_pos];
     c->ring_pos = (c->ring_pos + 1) % kRing;
     if (s.pending) { TS_HIP(c, hipEventSynchronize(s.ev)); s.pending = false; }
-    if (!s.ev) TS_HIP(c, hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
+    // (no system-scope fence: the event only orders GPU work against GPU work and against the host
+    // overwriting a buffer the GPU has read)
+    if (!s.ev) TS_HIP(c, hipEventCreateWithFlags(&s.ev, hipEventDisableTiming | hipEventDisableSystemFence));
     if (bytes > s.cap) {
         if (s.ptr) TS_HIP(c, hipHostFree(s.ptr));
-        s.ptr = nullptr; s.cap = 0;
+        s.ptr = s.dev_ptr = nullptr; s.cap = 0;
         size_t cap = std::max<size_t>(bytes * 2, 1 << 16);
         if (hipHostMalloc(&s.ptr, cap, hipHostMallocDefault) != hipSuccess)
             return fail(c, TS_ERR_NOMEM, "pinned staging allocation failed");
+        if (hipHostGetDevicePointer(&s.dev_ptr, s.ptr, 0) != hipSuccess) {
+            (void)hipHostFree(s.ptr);
+            s.ptr = s.dev_ptr = nullptr;
+            return fail(c, TS_ERR_HIP, "pinned staging memory is not visible to the GPU");
+        }
         s.cap = cap;
     }
     *out = &s;
     return TS_OK;
+}
+
+// Brings the work lists from the pinned staging buffer into device memory.  A kernel instead of a copy
+// command: between two kernels of a stream the GPU loses no time, around a copy command it idled
+// 10 + 5 us per call (a twentieth of a decode step).
+__global__ __launch_bounds__(256) void upload_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
 struct WorkLayout {
@@ -175,7 +193,7 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
 {
     int rc = ensure_work(c, w.total);
     if (rc != TS_OK) return rc;
-    if (c->have_work && st != c->last_stream) TS_HIP(c, hipStreamWaitEvent(st, c->work_done, 0));
+    if (c->have_work && st != c->last_stream) TS_HIP(c, hipStreamWaitEvent(st, c->last_event, 0));
     HostSlot* slot = nullptr;
     rc = acquire_slot(c, w.total, &slot);
     if (rc != TS_OK) return rc;
@@ -191,9 +209,14 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
     if (!p.q_off.empty()) memcpy(h + w.q_off, p.q_off.data(), p.q_off.size() * sizeof(int32_t));
     if (!p.apt.empty()) memcpy(h + w.apt, p.apt.data(), p.apt.size() * sizeof(AppTile));
     if (!p.apr.empty()) memcpy(h + w.apr, p.apr.data(), p.apr.size() * sizeof(AppRow));
-    TS_HIP(c, hipMemcpyAsync(c->d_work, h, w.total, hipMemcpyHostToDevice, st));
-    TS_HIP(c, hipEventRecord(slot->ev, st));
-    slot->pending = true;
+    const int64_t n16 = (int64_t)(w.total / 16);           // (every list starts at a multiple of 16)
+    if (n16 > 0) {
+        const int blocks = (int)std::min<int64_t>(256, (n16 + 255) / 256);
+        hipLaunchKernelGGL(upload_kernel, dim3(blocks), dim3(256), 0, st, (const uint4*)slot->dev_ptr, (uint4*)c->d_work,
+                           n16);
+        TS_HIP(c, hipGetLastError());
+    }
+    c->cur_slot = slot;                                    // its event is recorded by mark_work_done
     return TS_OK;
 }
 
@@ -234,14 +257,25 @@ int drain_timed(ts_ctx* c)
     return TS_OK;
 }
 
-// Marks the end of a call's device work on its stream (see upload_plan).
+// Marks the end of a call's device work on its stream: the call's one event.  Runs on every path that
+// follows a successful upload_plan, error paths included (the upload kernel may still be reading the slot).
 int mark_work_done(ts_ctx* c, hipStream_t st)
 {
-    TS_HIP(c, hipEventRecord(c->work_done, st));
+    HostSlot* slot = c->cur_slot;
+    c->cur_slot = nullptr;
+    if (!slot) return TS_OK;
+    slot->pending = true;
     c->last_stream = st;
     c->have_work = true;
+    c->last_event = slot->ev;
+    TS_HIP(c, hipEventRecord(slot->ev, st));
     return TS_OK;
 }
+
+struct WorkDoneGuard {                                     // records the event when a call leaves early
+    ts_ctx* c; hipStream_t st;
+    ~WorkDoneGuard() { if (c->cur_slot) (void)mark_work_done(c, st); }
+};
 
 Geometry geometry_of(const ts_attn_desc& d)
 {
@@ -308,14 +342,6 @@ extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
             rc = TS_ERR_NOMEM;
         }
     }
-    if (rc == TS_OK && hipEventCreateWithFlags(&c->work_done, hipEventDisableTiming) != hipSuccess) {
-        c->err = "hipEventCreate failed";
-        rc = TS_ERR_HIP;
-    }
-    if (rc == TS_OK && hipEventCreateWithFlags(&c->last_pass, hipEventDisableTiming) != hipSuccess) {
-        c->err = "hipEventCreate failed";
-        rc = TS_ERR_HIP;
-    }
     if (rc != TS_OK) { g_create_error = c->err; ts_destroy(c); return rc; }
     *out = c;
     return TS_OK;
@@ -334,8 +360,6 @@ extern "C" int ts_destroy(ts_ctx* c)
         if (s.ptr) (void)hipHostFree(s.ptr);
         if (s.ev) (void)hipEventDestroy(s.ev);
     }
-    if (c->last_pass) (void)hipEventDestroy(c->last_pass);
-    if (c->work_done) (void)hipEventDestroy(c->work_done);
     for (auto& t : c->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     delete c;
@@ -425,6 +449,7 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     hipStream_t st = (hipStream_t)stream;
     rc = upload_plan(c, st, w);
     if (rc != TS_OK) return rc;
+    WorkDoneGuard guard_done{c, st};
     AppendArgs a{};
     a.geo = geometry_of(c->desc);
     a.k_new = k_new; a.v_new = v_new; a.k_cache = k_cache; a.v_cache = v_cache;
@@ -467,6 +492,7 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     hipStream_t st = (hipStream_t)stream;
     rc = upload_plan(c, st, w);
     if (rc != TS_OK) return rc;
+    WorkDoneGuard guard_done{c, st};
 
     const Geometry geo = geometry_of(c->desc);
     if (k_new) {
@@ -524,7 +550,6 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
         c->prefill_tokens += (uint64_t)p.info.prefill_tokens;
         c->decode_tokens += (uint64_t)p.info.decode_tokens;
         c->passes += 1;
-        if (hipEventRecord(c->last_pass, st) == hipSuccess) c->have_last = true;
     }
     return TS_OK;
 }
@@ -533,9 +558,9 @@ extern "C" int ts_token_velocity(ts_ctx* c, ts_velocity* out, int flags)
 {
     if (!c || !out) return TS_ERR_INVALID_ARG;
     if (flags & ~(TS_VELOCITY_RESET | TS_VELOCITY_SYNC)) return fail(c, TS_ERR_INVALID_ARG, "unknown flag");
-    if ((flags & TS_VELOCITY_SYNC) && c->have_last) {
+    if ((flags & TS_VELOCITY_SYNC) && c->have_work) {
         DeviceGuard guard(c->device);
-        TS_HIP(c, hipEventSynchronize(c->last_pass));
+        TS_HIP(c, hipEventSynchronize(c->last_event));     // the most recent call's end (a pass or an append)
     }
     std::lock_guard<std::mutex> lk(c->mu);
     ts_velocity v{};
