@@ -142,8 +142,10 @@ typedef struct {
 } ts_velocity;
 
 #define TS_VELOCITY_RESET 1   /* start a new window after reporting                         */
-#define TS_VELOCITY_SYNC  2   /* wait for the last pass to finish on the GPU before reading
-                                 the clock (otherwise the call touches no GPU state)        */
+#define TS_VELOCITY_SYNC  2   /* wait for the context's last call to finish on the GPU before
+                                 reading the clock (otherwise the call touches no GPU state).
+                                 It orders nothing but the clock: to read `out` on the host,
+                                 synchronise the stream as usual                            */
 int ts_token_velocity(ts_ctx *ctx, ts_velocity *out, int flags);
 
 /* Text of the last error of this context ("" if none); valid until the next call on it.
