@@ -417,3 +417,36 @@ def test_mfma_calibration_stream_runs_and_counts_its_work():
         torch.cuda.synchronize()
         assert flops == n_cu * 8 * 50 * 16 * 32768
         assert float(res.item()) == 0.0
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_seeded_random_batches(seed):
+    """Batches drawn from a seeded generator: random head geometry, cache type, number of sequences,
+    a length mix of empty sequences, decode rows and chunks of any size over prefixes of any length
+    (page-aligned or not), persistent or separate launches, forced or automatic decode splits."""
+    rng = np.random.default_rng(1000 + seed)
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    group = int(rng.choice([1, 2, 3, 4, 8]))
+    kv = str(rng.choice(["bf16", "fp8"]))
+    shape = AttnShape(hkv * group, hkv, 128, "bf16", kv)
+    n = int(rng.integers(1, 14))
+    q, c = [], []
+    for _ in range(n):
+        kind = rng.choice(["empty", "decode", "decode", "decode", "chunk", "chunk"])
+        if kind == "empty":
+            ql, pre = 0, int(rng.integers(0, 200))
+        elif kind == "decode":
+            ql, pre = 1, int(rng.choice([0, int(rng.integers(0, 64)), int(rng.integers(0, 3000))]))
+        else:
+            ql = int(rng.choice([2, int(rng.integers(2, 40)), int(rng.integers(40, 700))]))
+            pre = int(rng.choice([0, 16 * int(rng.integers(0, 20)), int(rng.integers(0, 1500))]))
+        q.append(ql)
+        c.append(ql + pre)
+    if sum(q) == 0:
+        q[0], c[0] = 1, c[0] + 1
+    opts = {"mixed_persistent": int(rng.integers(0, 2))}
+    if rng.integers(0, 2):
+        opts["decode_split_pages"] = int(rng.choice([8, 13, 40]))
+    b = make_batch(shape, q, c, seed=2000 + seed, pool_rule=1.3, value_mult=0.5)
+    print(f"[case] random batch {seed}: q={q} ctx={c}", flush=True)
+    check(b, options=opts)
