@@ -161,6 +161,10 @@ const char *ts_last_error(const ts_ctx *ctx);
  *   "xcd_count"           accelerator dies the prefill launch order is laid out for (default 8)
  *   "kernel_timing"       N > 0 = record HIP events around the launches of every N-th call
  *                         (see ts_kernel_times), 0 = off
+ *   "validate_block_table"  debug aid, 0 (default) / 1: the GPU calls first check, on the GPU, that
+ *                         every page id the batch uses lies in [0, num_pages), wait for the answer
+ *                         (the call is then synchronous) and fail with TS_ERR_INVALID_ARG, caches
+ *                         untouched, if one does not
  * Unknown names give TS_ERR_INVALID_ARG. */
 int ts_set_option(ts_ctx *ctx, const char *name, int64_t value);
 

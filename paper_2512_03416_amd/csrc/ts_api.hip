@@ -62,6 +62,7 @@ struct ts_ctx {
     hipEvent_t last_event = nullptr;   // event of the most recent call
     hipStream_t last_stream = nullptr;
     bool have_work = false;
+    bool validate_pages = false;       // debug: check the page ids of a batch before anything is launched
     // optional per-kernel timing
     int timing = 0;                    // 0 = off, N = time the launches of every N-th pass
     uint64_t timing_pass = 0;
@@ -167,6 +168,21 @@ __global__ __launch_bounds__(256) void upload_kernel(const uint4* __restrict__ s
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Debug check of the device-side page table: every page a sequence of the batch uses must lie in
+// [0, num_pages).  result[0] counts the offenders, result[1..2] = (sequence, page index) of one of them.
+__global__ __launch_bounds__(256) void check_pages_kernel(const SeqMeta* __restrict__ seqs, const int32_t* __restrict__ bt,
+                                                          int max_pages, int64_t num_pages, int32_t* result)
+{
+    const int s = blockIdx.x;
+    const int used = (seqs[s].ctx_len + kPage - 1) / kPage;
+    for (int p = threadIdx.x; p < used; p += blockDim.x) {
+        const int32_t id = bt[(int64_t)s * max_pages + p];
+        if (id < 0 || id >= num_pages) {
+            if (atomicAdd(&result[0], 1) == 0) { result[1] = s; result[2] = p; }
+        }
+    }
+}
+
 struct WorkLayout {
     size_t seqs, dec, cmb, pf, pfmap, rows, queue, q_off, apt, apr, total;
 };
@@ -217,6 +233,25 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
         TS_HIP(c, hipGetLastError());
     }
     c->cur_slot = slot;                                    // its event is recorded by mark_work_done
+    return TS_OK;
+}
+
+// Debug option "validate_block_table": runs the check on the call's stream and waits for it, so that a
+// bad page id is reported before any kernel of the pass has touched the caches.
+int check_pages(ts_ctx* c, hipStream_t st, const WorkLayout& w, const int32_t* block_table, int num_seqs)
+{
+    if (!c->validate_pages || num_seqs <= 0) return TS_OK;
+    int32_t* res = c->d_q_ctr + 120;                       // (the queue heads use the first 65 words)
+    TS_HIP(c, hipMemsetAsync(res, 0, 4 * sizeof(int32_t), st));
+    hipLaunchKernelGGL(check_pages_kernel, dim3((unsigned)num_seqs), dim3(256), 0, st, (const SeqMeta*)(c->d_work + w.seqs),
+                       block_table, c->desc.max_pages_per_seq, (int64_t)c->desc.num_pages, res);
+    TS_HIP(c, hipGetLastError());
+    int32_t host[4] = {0, 0, 0, 0};
+    TS_HIP(c, hipMemcpyAsync(host, res, sizeof host, hipMemcpyDeviceToHost, st));
+    TS_HIP(c, hipStreamSynchronize(st));
+    if (host[0] != 0)
+        return fail(c, TS_ERR_INVALID_ARG, "block_table: " + std::to_string(host[0]) + " page id(s) outside [0, num_pages), e.g. sequence " +
+                                               std::to_string(host[1]) + ", page " + std::to_string(host[2]));
     return TS_OK;
 }
 
@@ -419,6 +454,10 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         c->opt.xcds = (int32_t)value;
         return TS_OK;
     }
+    if (!strcmp(name, "validate_block_table")) {
+        c->validate_pages = value != 0;
+        return TS_OK;
+    }
     if (!strcmp(name, "kernel_timing")) {
         if (value < 0 || value > 1024) return fail(c, TS_ERR_INVALID_ARG, "kernel_timing must be 0..1024");
         c->timing = (int)value;
@@ -451,6 +490,8 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     rc = upload_plan(c, st, w);
     if (rc != TS_OK) return rc;
     WorkDoneGuard guard_done{c, st};
+    rc = check_pages(c, st, w, block_table, num_seqs);
+    if (rc != TS_OK) return rc;
     AppendArgs a{};
     a.geo = geometry_of(c->desc);
     a.k_new = k_new; a.v_new = v_new; a.k_cache = k_cache; a.v_cache = v_cache;
@@ -494,6 +535,8 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     rc = upload_plan(c, st, w);
     if (rc != TS_OK) return rc;
     WorkDoneGuard guard_done{c, st};
+    rc = check_pages(c, st, w, block_table, num_seqs);
+    if (rc != TS_OK) return rc;
 
     const Geometry geo = geometry_of(c->desc);
     if (k_new) {

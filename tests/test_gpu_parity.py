@@ -311,6 +311,47 @@ def test_errors_have_no_side_effects_and_empty_batches_are_fine():
     ctx.close()
 
 
+def test_block_table_validation_option_catches_bad_page_ids():
+    """Debug option: a page id outside the pool in a page the batch uses fails the call before any
+    kernel has touched the caches; ids in unused entries of the table are never looked at."""
+    import paper_2512_03416_amd as ts
+    from paper_2512_03416_amd import binding
+    g = gpu()
+    b = g.to_dev(make_batch(AttnShape(8, 2, 128, "bf16", "bf16"), [1, 40, 3], [70, 90, 3], seed=63))
+    ctx = ts.Context(g.make_desc(b))
+    ctx.set_option("validate_block_table", 1)
+    kc, vc = g.new_caches(b)
+    out = torch.zeros_like(b.q)
+    before_k, before_v = kc.clone(), vc.clone()
+    table = b.block_table.copy()
+    used = [(int(c) + 15) // 16 for c in b.ctx_lens]
+    for s in range(len(used)):
+        table[s, used[s]:] = -1                                  # unused entries: anything goes
+    good = torch.from_numpy(table).cuda()
+    for s, p, bad_id in ((1, used[1] - 1, b.num_pages), (0, 0, -1), (2, 0, 2 ** 31 - 1)):
+        bad = table.copy()
+        bad[s, p] = bad_id
+        bt = torch.from_numpy(bad).cuda()
+        for call in ("attention", "append"):
+            with pytest.raises(ts.TokenScaleError) as e:
+                if call == "attention":
+                    ctx.mixed_paged_attention(b.q, b.k_new, b.v_new, kc, vc, None, None, bt, b.q_lens, b.ctx_lens, 0.0, out)
+                else:
+                    ctx.kv_append(b.k_new, b.v_new, kc, vc, None, None, bt, b.q_lens, b.ctx_lens)
+            assert e.value.code == binding.TS_ERR_INVALID_ARG
+            assert f"sequence {s}, page {p}" in ctx.last_error()
+    torch.cuda.synchronize()
+    assert torch.equal(kc, before_k) and torch.equal(vc, before_v) and float(out.float().abs().sum()) == 0.0
+    # the same table without the planted ids passes, and the pass still matches the oracle
+    ctx.set_option("validate_block_table", 1)
+    b.block_table = table
+    ref, rk, rv = oracle.run_batch(W.to_cpu(make_batch(AttnShape(8, 2, 128, "bf16", "bf16"), [1, 40, 3], [70, 90, 3], seed=63)))
+    o, gk, gv = g.run_batch(b, ctx=ctx)
+    assert same_bytes(gk, rk) and same_bytes(gv, rv)
+    assert float(np.max(np.abs(o - ref))) <= TOL["bf16"]
+    ctx.close()
+
+
 def test_run_to_run_identical_and_default_scale():
     g = gpu()
     shape = AttnShape(32, 8, 128, "bf16", "bf16")
