@@ -21,7 +21,7 @@
  * the tests in tests/test_oracle_pins.py (dense brute force, closed forms, invariants,
  * exhaustive e4m3 nearest-value search).
  *
- * Cache element order (a choice of this build, the paper is silent): per (page, kv head)
+ * Cache element order (a choice of this library, the paper is silent): per (page, kv head)
  *   K tile: [D/x][16 slots][x]  with x = 16 bytes / element size  (dim-chunks of 16 bytes)
  *   V tile: [D][16 slots]       (token index fastest)
  * tiles ordered [page][kv head].
