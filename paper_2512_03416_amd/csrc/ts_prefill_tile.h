@@ -185,7 +185,6 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // row of this lane pair: rho = 32*wave + n  ->  (token rho / G, head rho % G)
     const int rho = 32 * wave + n;
     const int t_raw = rho / G;
-    const bool row_ok = t_raw < it.tok_count;
     const int tok = min(t_raw, it.tok_count - 1);          // padding rows repeat the last token
     const int hd = rho - t_raw * G;
     bf16x8 qb[KS];                                          // Q^T operands: dims 16 s + 8 h .. + 7 of the row
@@ -548,23 +547,39 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         if (2 * i + 1 < hend) slow_iter(2 * i + 1, sB, sA, popB, popA);
         bottom(i, no);
     }
-    // (the last body ended with a barrier: lds may be reused by the caller)
-
+    // The last body ended with a barrier and no copy is in flight: LDS is free.  The rows leave through it:
+    // a lane holds 4-dim pieces of its row (8 bytes each), written directly they would reach memory
+    // as 16 stores of 32 scattered 16-byte runs per wave; staged in LDS (row stride 272 bytes), 16 lanes
+    // store one whole 256-byte row as 16-byte pieces and an instruction covers 4 rows.
+    constexpr int kOutStride = 272;
+    unsigned char* ob = (unsigned char*)&lds + wave * (32 * kOutStride);
     const float vscale = (sizeof(KT) == 1) ? a.v_scale[g] : 1.0f;
     const float l_row = l_part + __shfl_xor(l_part, 32, 64);
-    if (row_ok) {
-        const float inv = vscale / l_row;
-        uint16_t* o = (uint16_t*)a.out + ((int64_t)(it.row0 + it.tok_begin + tok) * Hq + g * G + hd) * D + 4 * h;
+    const float inv = vscale / l_row;
 #pragma unroll
-        for (int b = 0; b < DB; ++b)
+    for (int b = 0; b < DB; ++b)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                uint2 w;
-                w.x = pack2(acc[b][4 * j] * inv, acc[b][4 * j + 1] * inv);
-                w.y = pack2(acc[b][4 * j + 2] * inv, acc[b][4 * j + 3] * inv);
-                *(uint2*)(o + 32 * b + 8 * j) = w;
-            }
+        for (int j = 0; j < 4; ++j) {
+            uint2 w;
+            w.x = pack2(acc[b][4 * j] * inv, acc[b][4 * j + 1] * inv);
+            w.y = pack2(acc[b][4 * j + 2] * inv, acc[b][4 * j + 3] * inv);
+            *(uint2*)(ob + n * kOutStride + 64 * b + 16 * j + 8 * h) = w;
+        }
+    __builtin_amdgcn_wave_barrier();                       // (the rows are read back by other lanes of this wave)
+    const float inv_g = 1.0f / (float)G;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + (lane >> 4);                 // row of the wave, 16 lanes per row
+        const int rho_r = 32 * wave + r;
+        const int t_r = (int)(((float)rho_r + 0.5f) * inv_g);      // rho_r / G (exact for rho_r < 256, G <= 16)
+        const int hd_r = rho_r - t_r * G;
+        const uint4 v = *(const uint4*)(ob + r * kOutStride + (lane & 15) * 16);
+        if (t_r < it.tok_count) {
+            uint16_t* o = (uint16_t*)a.out + ((int64_t)(it.row0 + it.tok_begin + t_r) * Hq + g * G + hd_r) * D;
+            *(uint4*)(o + (lane & 15) * 8) = v;
+        }
     }
+    __syncthreads();                                       // LDS may be reused by the caller
 }
 
 }  // namespace ts
