@@ -24,7 +24,9 @@
 //     with scheduling barriers (left to itself the compiler puts the phases one after the other);
 //   - bf16 caches: the memory system copies the tiles straight into LDS (no registers, no vector
 //     instructions); fp8 caches are widened to bf16 by the threads while being staged, so the
-//     multiply loop is the same.
+//     multiply loop is the same;
+//   - the finished rows are normalised, packed to bf16 and passed through LDS once more, so that they
+//     reach memory as whole 256-byte rows.
 #pragma once
 #include <type_traits>
 #include "ts_device.h"
