@@ -146,7 +146,8 @@ int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out)
         if (s.ptr) TS_HIP(c, hipHostFree(s.ptr));
         s.ptr = s.dev_ptr = nullptr; s.cap = 0;
         size_t cap = std::max<size_t>(bytes * 2, 1 << 16);
-        if (hipHostMalloc(&s.ptr, cap, hipHostMallocDefault) != hipSuccess)
+        // (coherent: the GPU reads it uncached over PCIe, so a slot that is filled again is never seen stale)
+        if (hipHostMalloc(&s.ptr, cap, hipHostMallocCoherent) != hipSuccess)
             return fail(c, TS_ERR_NOMEM, "pinned staging allocation failed");
         if (hipHostGetDevicePointer(&s.dev_ptr, s.ptr, 0) != hipSuccess) {
             (void)hipHostFree(s.ptr);

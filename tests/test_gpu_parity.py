@@ -491,3 +491,36 @@ def test_seeded_random_batches(seed):
     b = make_batch(shape, q, c, seed=2000 + seed, pool_rule=1.3, value_mult=0.5)
     print(f"[case] random batch {seed}: q={q} ctx={c}", flush=True)
     check(b, options=opts)
+
+
+def test_one_context_many_different_batches_in_a_row():
+    """Twelve batches of different shape through one context, back to back: the staging ring for the work
+    lists (four slots) is refilled several times, and every pass must be planned from its own lists."""
+    import paper_2512_03416_amd as ts
+    g = gpu()
+    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+    rng = np.random.default_rng(77)
+    batches = []
+    for i in range(12):
+        n = int(rng.integers(1, 9))
+        q = [int(rng.choice([0, 1, 1, 1, int(rng.integers(2, 300))])) for _ in range(n)]
+        if sum(q) == 0:
+            q[0] = 1
+        c = [ql + int(rng.integers(0, 900)) for ql in q]
+        batches.append(make_batch(shape, q, c, seed=300 + i, pool_rule=1.3, value_mult=0.5))
+    num_pages = max(b.num_pages for b in batches)
+    stride = max(b.max_pages_per_seq for b in batches)
+    refs = [oracle.run_batch(W.to_cpu(b)) for b in batches]
+    ctx = ts.Context(ts.Desc.make(8, 2, 128, "bf16", "bf16", num_pages, stride))
+    for i, b in enumerate(batches):
+        table = np.full((b.num_seqs, stride), -1, dtype=np.int32)
+        table[:, :b.block_table.shape[1]] = b.block_table
+        b.block_table = table
+        b.num_pages = num_pages
+        print(f"[case] batch {i} on the shared context: q={list(b.q_lens)} ctx={list(b.ctx_lens)}", flush=True)
+        out, gk, gv = g.run_batch(b, ctx=ctx)
+        ref, rk, rv = refs[i]
+        n_el = rk.size                                          # the oracle's pool is the batch's own, smaller one
+        assert same_bytes(gk[:n_el], rk) and same_bytes(gv[:n_el], rv)
+        assert float(np.max(np.abs(out - ref))) <= TOL["bf16"]
+    ctx.close()
