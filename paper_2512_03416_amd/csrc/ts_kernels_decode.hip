@@ -13,20 +13,43 @@ __global__ __launch_bounds__(64 * kDecWaves) void decode_kernel(AttnArgs a)
 }
 
 // Merge of a row's splits, in split order:  M = max m_i, out = sum o_i 2^(m_i-M) / sum l_i 2^(m_i-M).
+// The partials of up to eight splits are requested together and then added one after the other: the
+// sums keep their order, and a row of ten splits waits for four loads instead of thirty.
 __global__ __launch_bounds__(128) void combine_kernel(AttnArgs a)
 {
+    constexpr int kBatch = 8;
     const CmbItem it = a.cmb[blockIdx.x];
     const int h = blockIdx.y, d = threadIdx.x;
     const int Hq = a.geo.Hq, D = a.geo.D;
+    const float* ml = a.part_ml + ((int64_t)it.part_begin * Hq + h) * 2;      // split k: ml[k * Hq * 2 + {0, 1}]
+    const float* po = a.part_o + ((int64_t)it.part_begin * Hq + h) * D + d;    // split k: po[k * Hq * D]
+    const int64_t ml_step = (int64_t)Hq * 2, po_step = (int64_t)Hq * D;
     float M = -INFINITY;
-    for (int k = 0; k < it.n_split; ++k)
-        M = fmaxf(M, a.part_ml[((int64_t)(it.part_begin + k) * Hq + h) * 2]);
+    for (int k0 = 0; k0 < it.n_split; k0 += kBatch) {
+        float m[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) m[j] = k0 + j < it.n_split ? ml[(k0 + j) * ml_step] : -INFINITY;
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) M = fmaxf(M, m[j]);
+    }
     float o = 0.0f, L = 0.0f;
-    for (int k = 0; k < it.n_split; ++k) {
-        const int64_t p = (int64_t)(it.part_begin + k) * Hq + h;
-        const float w = __builtin_amdgcn_exp2f(a.part_ml[p * 2] - M);
-        L += a.part_ml[p * 2 + 1] * w;
-        o += a.part_o[p * D + d] * w;
+    for (int k0 = 0; k0 < it.n_split; k0 += kBatch) {
+        float m[kBatch], l[kBatch], v[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const bool in = k0 + j < it.n_split;
+            m[j] = in ? ml[(k0 + j) * ml_step] : 0.0f;
+            l[j] = in ? ml[(k0 + j) * ml_step + 1] : 0.0f;
+            v[j] = in ? po[(k0 + j) * po_step] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            if (k0 + j < it.n_split) {
+                const float w = __builtin_amdgcn_exp2f(m[j] - M);
+                L += l[j] * w;
+                o += v[j] * w;
+            }
+        }
     }
     const float vscale = (a.geo.kv_dtype == TS_FP8_E4M3) ? a.v_scale[h / a.geo.G] : 1.0f;
     ((uint16_t*)a.out)[((int64_t)it.row * Hq + h) * D + d] = (uint16_t)float_to_bf16_bits(o * vscale / L);
