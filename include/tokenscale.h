@@ -224,7 +224,7 @@ int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int3
  *   TS_LIST_QUEUE   (kind 0 decode / 1 prefill, item, kv_head, 0)   per-die queues, concatenated
  *   TS_LIST_QOFF    (offset)                                        n_dies + 1 offsets into the queue
  *   TS_LIST_APPEND  (seq, page_index, slot_lo, slot_hi, row_of_slot_0, 0, 0, 0)   page-wise append work
- *   TS_LIST_APPEND_ROWS (row, seq)                                  tokens appended one by one
+ *   TS_LIST_APPEND_ROWS (row, seq, pos, 0)                          tokens appended one by one
  * wg_slots = 0 uses the default number of resident decode workgroups. */
 enum { TS_LIST_DECODE = 0, TS_LIST_COMBINE = 1, TS_LIST_PREFILL = 2, TS_LIST_PFMAP = 3, TS_LIST_ROWS = 4,
        TS_LIST_QUEUE = 5, TS_LIST_QOFF = 6, TS_LIST_APPEND = 7,

@@ -157,7 +157,7 @@ def plan_describe(desc: Desc, q_lens, ctx_lens, split_pages: int = 0) -> PlanInf
 
 PLAN_LISTS = {"decode": (0, 8), "combine": (1, 4), "prefill": (2, 8), "pfmap": (3, 2), "rows": (4, 4),
               "queue": (5, 4), "qoff": (6, 1), "append": (7, 8),
-              "append_rows": (8, 2)}
+              "append_rows": (8, 4)}
 
 
 def plan_export(desc: Desc, q_lens, ctx_lens, which: str, split_pages: int = 0, wg_slots: int = 0) -> np.ndarray:

@@ -71,6 +71,8 @@ constexpr int kAppendTileMin = 8;   // sequences with at least this many new tok
 struct AppRow {           // one new token that is appended on its own
     int32_t row;
     int32_t seq;
+    int32_t pos;          // its position in the sequence (prefix + index among the new tokens)
+    int32_t pad;
 };
 
 struct RowItem {          // one query row for the generic kernel

@@ -30,31 +30,43 @@ template <typename SRC, typename DST>
 __global__ __launch_bounds__(256) void append_token_kernel(AppendArgs a)
 {
     const AppRow r = a.apr[blockIdx.x];
-    const int row = r.row, lo = r.seq;
+    const int row = r.row, pos = r.pos;
     const int Hkv = a.geo.Hkv, D = a.geo.D;
-    const SeqMeta m = a.seqs[lo];
-    const int pos = m.prefix + (row - m.q_off);
-    const int64_t page = a.block_table[(int64_t)lo * a.geo.max_pages + (pos >> 4)];
-    const int slot = pos & 15;
     constexpr int X = 16 / (int)sizeof(DST);       // elements per 16-byte dim-chunk
     const int n_elems = Hkv * D;
     const SRC* ks = (const SRC*)a.k_new + (int64_t)row * n_elems;
     const SRC* vs = (const SRC*)a.v_new + (int64_t)row * n_elems;
     DST* kc = (DST*)a.k_cache;
     DST* vc = (DST*)a.v_cache;
-    for (int e = threadIdx.x; e < n_elems; e += blockDim.x) {
-        const int g = e / D, dim = e - g * D;
-        const int64_t tile = tile_elem_base(page, Hkv, g, D);
-        const int64_t kidx = tile + (dim / X) * (kPage * X) + slot * X + (dim % X);
-        const int64_t vidx = tile + dim * kPage + slot;
-        if constexpr (sizeof(DST) == 1) {
-            const float kf = Elem<SRC>::load(ks, e) / a.k_scale[g];
-            const float vf = Elem<SRC>::load(vs, e) / a.v_scale[g];
-            __builtin_nontemporal_store((uint8_t)float_to_e4m3_bits(kf), &kc[kidx]);
-            __builtin_nontemporal_store((uint8_t)float_to_e4m3_bits(vf), &vc[vidx]);
-        } else {
-            __builtin_nontemporal_store((DST)ks[e], &kc[kidx]);   // same element type: plain copy of the bits
-            __builtin_nontemporal_store((DST)vs[e], &vc[vidx]);
+    // (the values are requested before the page id is needed: the two loads wait together)
+    const int32_t* page_ptr = a.block_table + (int64_t)r.seq * a.geo.max_pages + (pos >> 4);
+    const int slot = pos & 15;
+    for (int e0 = 0; e0 < n_elems; e0 += 4 * 256) {
+        SRC kv[4], vv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = e0 + i * 256 + threadIdx.x;
+            kv[i] = e < n_elems ? ks[e] : SRC(0);
+            vv[i] = e < n_elems ? vs[e] : SRC(0);
+        }
+        const int64_t page = *page_ptr;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = e0 + i * 256 + threadIdx.x;
+            if (e >= n_elems) continue;
+            const int g = e / D, dim = e - g * D;
+            const int64_t tile = tile_elem_base(page, Hkv, g, D);
+            const int64_t kidx = tile + (dim / X) * (kPage * X) + slot * X + (dim % X);
+            const int64_t vidx = tile + dim * kPage + slot;
+            if constexpr (sizeof(DST) == 1) {
+                const float kf = Elem<SRC>::load(&kv[i], 0) / a.k_scale[g];
+                const float vf = Elem<SRC>::load(&vv[i], 0) / a.v_scale[g];
+                __builtin_nontemporal_store((uint8_t)float_to_e4m3_bits(kf), &kc[kidx]);
+                __builtin_nontemporal_store((uint8_t)float_to_e4m3_bits(vf), &vc[vidx]);
+            } else {
+                __builtin_nontemporal_store((DST)kv[i], &kc[kidx]);   // same element type: plain copy of the bits
+                __builtin_nontemporal_store((DST)vv[i], &vc[vidx]);
+            }
         }
     }
 }

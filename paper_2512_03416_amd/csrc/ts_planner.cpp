@@ -215,7 +215,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     for (int s = 0; s < num_seqs; ++s) {
         const SeqMeta& m = p.seqs[s];
         if (!page_wise || m.q_len < kAppendTileMin) {
-            for (int32_t i = 0; i < m.q_len; ++i) p.apr.push_back(AppRow{m.q_off + i, s});
+            for (int32_t i = 0; i < m.q_len; ++i) p.apr.push_back(AppRow{m.q_off + i, s, m.prefix + i, 0});
             continue;
         }
         for (int32_t pg = m.prefix / kPage; pg <= (m.ctx_len - 1) / kPage; ++pg) {

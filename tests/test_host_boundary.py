@@ -129,7 +129,7 @@ def test_plan_append_pages_cover_every_new_token_of_the_chunks_once():
     assert len(seen) == int(q_lens[q_lens >= 8].sum())
     # the other tokens, and all tokens of shapes the page-wise kernel does not take, go one by one
     rows = binding.plan_export(desc, q_lens, ctx, "append_rows")
-    want = [(q_off[s] + i, s) for s in range(len(q_lens)) if q_lens[s] < 8 for i in range(q_lens[s])]
+    want = [(q_off[s] + i, s, prefix[s] + i, 0) for s in range(len(q_lens)) if q_lens[s] < 8 for i in range(q_lens[s])]
     assert [tuple(r) for r in rows] == want
     d64 = binding.Desc.make(4, 1, 64, "f32", "f32", 4096, 16)
     assert len(binding.plan_export(d64, q_lens, ctx, "append")) == 0
