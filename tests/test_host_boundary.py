@@ -165,3 +165,82 @@ def test_calibration_helpers_reject_bad_arguments_before_touching_a_gpu():
     assert flops.value == -1
     assert lib.ts_calib_copy(None, one, one, 24) == -1         # not a multiple of 16
     assert lib.ts_calib_read(None, one, None, 32) == -1
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_plan_invariants_on_seeded_random_batches(seed):
+    """Every list of the planner against what the batch demands, for random mixes of empty sequences,
+    decode rows and chunks: each cache page of a decode row in exactly one item, partial slots
+    contiguous per split row, each chunk token in exactly one tile, each (tile, head) once in the launch
+    order and once in the queues, each (decode item, head) once in the queues, append work covering each
+    new token once."""
+    rng = np.random.default_rng(4000 + seed)
+    hkv = int(rng.choice([1, 2, 8]))
+    group = int(rng.choice([1, 4, 8]))
+    desc = binding.Desc.make(hkv * group, hkv, 128, "bf16", str(rng.choice(["bf16", "fp8"])), 1 << 16, 1024)
+    n = int(rng.integers(1, 40))
+    kinds = rng.choice(["empty", "decode", "decode", "chunk"], size=n)
+    ql = np.array([0 if k == "empty" else 1 if k == "decode" else int(rng.integers(2, 900)) for k in kinds], dtype=np.int32)
+    ctx = ql + rng.integers(0, 6000, size=n).astype(np.int32)
+    split = int(rng.choice([0, 0, 8, 37]))
+    slots = int(rng.choice([0, 96, 768]))
+    exp = lambda which: binding.plan_export(desc, ql, ctx, which, split, slots)
+    q_off = np.concatenate([[0], np.cumsum(ql)])
+    pages = -(-ctx // 16)
+    tile_tokens = 256 // group
+
+    dec, cmb = exp("decode"), exp("combine")
+    cover, slots_of = {}, {}
+    for row, seq, n_keys, pb, pe, part, *_ in dec:
+        assert ql[seq] == 1 and row == q_off[seq] and n_keys == ctx[seq] and 0 <= pb < pe <= pages[seq]
+        cover.setdefault(seq, []).extend(range(pb, pe))
+        slots_of.setdefault(seq, []).append(part)
+    assert set(cover) == {s for s in range(n) if ql[s] == 1}
+    for s, pg in cover.items():
+        assert sorted(pg) == list(range(pages[s]))
+    split_rows = {s for s, p in slots_of.items() if len(p) > 1}
+    assert all(p == [-1] for s, p in slots_of.items() if s not in split_rows)
+    used = []
+    assert len(cmb) == len(split_rows)
+    for row, begin, n_split, _ in cmb:
+        s = int(np.searchsorted(q_off, row, side="right") - 1)
+        while ql[s] == 0:
+            s += 1
+        assert s in split_rows and sorted(slots_of[s]) == list(range(begin, begin + n_split))
+        used.extend(range(begin, begin + n_split))
+    assert sorted(used) == list(range(len(used)))
+
+    pf = exp("prefill")
+    toks = {}
+    for seq, row0, q_len, prefix, t0, cnt, ctx_len, _ in pf:
+        assert ql[seq] > 1 and row0 == q_off[seq] and q_len == ql[seq] and prefix == ctx[seq] - ql[seq] and ctx_len == ctx[seq]
+        assert t0 % tile_tokens == 0 and 0 < cnt <= tile_tokens
+        toks.setdefault(seq, []).extend(range(t0, t0 + cnt))
+    assert set(toks) == {s for s in range(n) if ql[s] > 1}
+    for s, t in toks.items():
+        assert sorted(t) == list(range(ql[s]))
+
+    pfmap = exp("pfmap")
+    live = [(int(t), int(g)) for t, g in pfmap if t >= 0]
+    assert sorted(live) == sorted((t, g) for t in range(len(pf)) for g in range(hkv))
+
+    queue, qoff = exp("queue"), exp("qoff")[:, 0]
+    if len(dec) and len(pf):                                  # a mixed batch has per-die queues
+        assert len(qoff) == 9 and qoff[0] == 0 and qoff[-1] == len(queue) and np.all(np.diff(qoff) >= 0)
+        d_entries = sorted((int(i), int(g)) for k, i, g, _ in queue if k == 0)
+        p_entries = sorted((int(i), int(g)) for k, i, g, _ in queue if k == 1)
+        assert d_entries == sorted((i, g) for i in range(len(dec)) for g in range(hkv))
+        assert p_entries == sorted((t, g) for t in range(len(pf)) for g in range(hkv))
+    else:
+        assert len(queue) == 0
+
+    seen = set()
+    for seq, pg, lo, hi, row0, *_ in exp("append"):
+        for slot in range(lo, hi):
+            pos = pg * 16 + slot
+            assert (seq, pos) not in seen and row0 + slot == q_off[seq] + pos - (ctx[seq] - ql[seq])
+            seen.add((seq, pos))
+    for row, seq, pos, _ in exp("append_rows"):
+        assert (seq, pos) not in seen and row == q_off[seq] + pos - (ctx[seq] - ql[seq])
+        seen.add((seq, pos))
+    assert seen == {(s, p) for s in range(n) for p in range(ctx[s] - ql[s], ctx[s])}
