@@ -524,3 +524,40 @@ def test_one_context_many_different_batches_in_a_row():
         assert same_bytes(gk[:n_el], rk) and same_bytes(gv[:n_el], rv)
         assert float(np.max(np.abs(out - ref))) <= TOL["bf16"]
     ctx.close()
+
+
+def test_reserve_then_no_growth_and_kernel_timing_counts():
+    """ts_reserve sizes the scratch for the largest batch to come (a pass within it matches the oracle);
+    with kernel timing on every pass, ts_kernel_times counts one launch of each kernel the batch
+    needs per pass, reports positive means, and forgets them on reset."""
+    import paper_2512_03416_amd as ts
+    from paper_2512_03416_amd import binding
+    g = gpu()
+    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+    mk = lambda: make_batch(shape, [1, 1, 200, 1], [3000, 555, 420, 64], seed=71, value_mult=0.5)
+    b = g.to_dev(mk())
+    ctx = ts.Context(g.make_desc(b))
+    with pytest.raises(ts.TokenScaleError) as e:
+        ctx.reserve(-1, 4, 100)
+    assert e.value.code == binding.TS_ERR_INVALID_ARG
+    ctx.reserve(4096, 64, 4096)
+    ctx.set_option("decode_split_pages", 8)                  # split rows: decode, combine and prefill all run
+    ctx.set_option("mixed_persistent", 0)
+    ctx.set_option("kernel_timing", 1)
+    ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
+    for _ in range(3):
+        out, gk, gv = g.run_batch(b, ctx=ctx)
+    assert same_bytes(gk, rk) and same_bytes(gv, rv)
+    assert float(np.max(np.abs(out - ref))) <= TOL["bf16"]
+    kt = ctx.kernel_times()
+    # each run_batch = one prefix append + one pass (append, decode, combine, prefill)
+    assert kt["append"][0] == 6 and kt["decode"][0] == 3 and kt["combine"][0] == 3 and kt["prefill"][0] == 3
+    assert kt["mixed"][0] == 0 and kt["rows"][0] == 0
+    assert all(v[1] > 0 for k, v in kt.items() if v[0])
+    again = ctx.kernel_times(reset=True)
+    assert again == kt
+    assert all(v == (0, 0.0) for v in ctx.kernel_times().values())
+    ctx.set_option("kernel_timing", 0)
+    g.run_batch(b, ctx=ctx)
+    assert all(v == (0, 0.0) for v in ctx.kernel_times().values())
+    ctx.close()
