@@ -370,6 +370,8 @@ extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
     if (!c) { g_create_error = "out of host memory"; return TS_ERR_NOMEM; }
     c->desc = *desc;
     c->device = device;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0) c->opt.n_cu = cus;
     rc = ensure_work(c, 1 << 16);
     if (rc == TS_OK) rc = ensure_partials(c, 1024);
     if (rc == TS_OK) {
@@ -524,6 +526,7 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     if (desc_uses_mfma(c->desc)) {
         const int slots = decode_resident_workgroups(c->desc.kv_dtype);
         if (slots > 0) c->opt.wg_slots = slots;
+
     }
     build_plan(c->desc, q_lens, ctx_lens, num_seqs, c->opt, &c->plan);
     const Plan& p = c->plan;

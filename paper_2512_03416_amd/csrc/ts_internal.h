@@ -99,6 +99,7 @@ struct Plan {
 struct PlanOptions {
     int32_t split_pages = 0;    // 0 = auto
     int32_t wg_slots = 768;     // decode workgroups resident at once (256 CUs x 3)
+    int32_t n_cu = 256;         // compute units of the GPU
     int32_t xcds = 8;           // accelerator dies; workgroup i is dispatched to die i % xcds
     bool mixed_persistent = true; // decode items and prefill tiles in one persistent launch
     bool generic_only = false;  // every row through the generic kernel

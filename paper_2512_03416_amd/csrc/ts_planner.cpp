@@ -87,19 +87,25 @@ int validate_batch(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* 
 
 // Pages per decode item.  A row that fits one item is finished by its workgroup without any
 // partial result in HBM, so rows are cut only (a) when they exceed one workgroup slot's fair share
-// of the batch (they would otherwise finish last), or (b) when the batch has too few rows to
-// occupy every slot.  In a mixed batch whose prefill tiles fill the chip on their own (persistent
-// launch: one resident workgroup per CU, a third of the stand-alone decode slots), (b) does not apply
-// and the fair share in (a) is that of a resident workgroup: measured on the burst configuration,
-// 706 -> 692 us and no combine launch.
+// of the batch (they would otherwise finish last), or (b) when the batch has fewer (row, KV head)
+// pairs than the GPU has CUs: then the pages are dealt out so that there is about one workgroup per
+// CU.  Pieces have at least 32 pages.  (Measured on 2-64 rows of 1500-6000 tokens: more and shorter
+// items than that only add start-up, merge and combine work; 8 rows of 1500 tokens take 22 us per
+// pass in pieces of 32 pages against 26 us in pieces of 8, next to a 256-token chunk 50 against 64 us;
+// for 16-48 rows every choice between 32 and 128 pages lies within 10 % of the best.)
+// In a mixed batch whose prefill tiles fill the chip on their own (persistent launch: one resident
+// workgroup per CU, a third of the stand-alone decode slots), (b) does not apply and the fair share
+// in (a) is that of a resident workgroup: measured on the burst configuration, 706 -> 692 us and no
+// combine launch.
 static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int64_t n_rows, int Hkv,
-                                int32_t wg_slots, bool filled_by_prefill)
+                                int32_t wg_slots, int32_t n_cu, bool filled_by_prefill)
 {
     const int64_t slots = std::max<int32_t>(1, filled_by_prefill ? wg_slots / 3 : wg_slots);
     int64_t L = std::max<int64_t>(32, (decode_tiles + slots - 1) / slots);
-    const int64_t want_items = (3 * slots / 2 + Hkv - 1) / Hkv;        // per KV head
-    if (!filled_by_prefill && n_rows < want_items && decode_pages > 0)
-        L = std::min<int64_t>(L, std::max<int64_t>(8, (decode_pages + want_items - 1) / want_items));
+    if (!filled_by_prefill && n_rows * Hkv < n_cu && decode_pages > 0) {
+        const int64_t want_items = (n_cu + Hkv - 1) / Hkv;             // per KV head
+        L = std::min<int64_t>(L, std::max<int64_t>(32, (decode_pages + want_items - 1) / want_items));
+    }
     return (int32_t)std::min<int64_t>(L, 1 << 20);
 }
 
@@ -234,7 +240,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     const int32_t L = opt.split_pages > 0
                           ? opt.split_pages
                           : auto_split_pages(decode_tiles, decode_pages, p.info.decode_tokens, Hkv, opt.wg_slots,
-                                             filled_by_prefill);
+                                             std::max(1, opt.n_cu), filled_by_prefill);
     p.info.split_pages = L;
     p.info.tile_tokens = TT;
 
