@@ -206,7 +206,11 @@ WorkLayout layout_of(const Plan& p)
     return w;
 }
 
-int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
+struct UploadJob { const uint4* src = nullptr; uint4* dst = nullptr; int64_t n16 = 0; int blocks = 0; const char* host_lists = nullptr; };
+
+// Fills a staging slot with the work lists.  With `defer` the copy to the device is left to the caller
+// (it rides along in the append launch, see AppendArgs), else it is launched here.
+int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w, UploadJob* defer = nullptr)
 {
     int rc = ensure_work(c, w.total);
     if (rc != TS_OK) return rc;
@@ -227,13 +231,17 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w)
     if (!p.apt.empty()) memcpy(h + w.apt, p.apt.data(), p.apt.size() * sizeof(AppTile));
     if (!p.apr.empty()) memcpy(h + w.apr, p.apr.data(), p.apr.size() * sizeof(AppRow));
     const int64_t n16 = (int64_t)(w.total / 16);           // (every list starts at a multiple of 16)
+    const int blocks = (int)std::min<int64_t>(256, (n16 + 255) / 256);
+    c->cur_slot = slot;                                    // its event is recorded by mark_work_done
+    if (defer) {
+        *defer = UploadJob{(const uint4*)slot->dev_ptr, (uint4*)c->d_work, n16, blocks, (const char*)slot->dev_ptr};
+        return TS_OK;
+    }
     if (n16 > 0) {
-        const int blocks = (int)std::min<int64_t>(256, (n16 + 255) / 256);
         hipLaunchKernelGGL(upload_kernel, dim3(blocks), dim3(256), 0, st, (const uint4*)slot->dev_ptr, (uint4*)c->d_work,
                            n16);
         TS_HIP(c, hipGetLastError());
     }
-    c->cur_slot = slot;                                    // its event is recorded by mark_work_done
     return TS_OK;
 }
 
@@ -490,7 +498,10 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     c->plan.queue.clear(); c->plan.q_off.clear();
     const WorkLayout w = layout_of(c->plan);
     hipStream_t st = (hipStream_t)stream;
-    rc = upload_plan(c, st, w);
+    // token rows and no page check: the upload rides along in the token kernel's launch
+    const bool ride = !c->plan.apr.empty() && !c->validate_pages;
+    UploadJob job;
+    rc = upload_plan(c, st, w, ride ? &job : nullptr);
     if (rc != TS_OK) return rc;
     WorkDoneGuard guard_done{c, st};
     rc = check_pages(c, st, w, block_table, num_seqs);
@@ -503,6 +514,10 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     a.num_seqs = num_seqs; a.total_tokens = (int32_t)c->plan.info.total_tokens;
     a.apt = (const AppTile*)(c->d_work + w.apt); a.n_apt = (int32_t)c->plan.apt.size();
     a.apr = (const AppRow*)(c->d_work + w.apr); a.n_apr = (int32_t)c->plan.apr.size();
+    if (ride) {
+        a.apr = (const AppRow*)(job.host_lists + w.apr);
+        a.up_src = job.src; a.up_dst = job.dst; a.up_n16 = job.n16; a.up_blocks = job.blocks;
+    }
     hipError_t e = (hipError_t)timed_launch(c, TS_K_APPEND, true, st, [&] { return launch_append(a, stream); });
     if (e != hipSuccess) return hip_fail(c, e, "append launch");
     return mark_work_done(c, st);
@@ -536,7 +551,10 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     if (rc != TS_OK) return rc;
     const WorkLayout w = layout_of(p);
     hipStream_t st = (hipStream_t)stream;
-    rc = upload_plan(c, st, w);
+    // token rows to append and no page check: the upload rides along in the token kernel's launch
+    const bool ride = k_new && !p.apr.empty() && !c->validate_pages;
+    UploadJob job;
+    rc = upload_plan(c, st, w, ride ? &job : nullptr);
     if (rc != TS_OK) return rc;
     WorkDoneGuard guard_done{c, st};
     rc = check_pages(c, st, w, block_table, num_seqs);
@@ -552,6 +570,10 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
         ap.num_seqs = num_seqs; ap.total_tokens = (int32_t)p.info.total_tokens;
         ap.apt = (const AppTile*)(c->d_work + w.apt); ap.n_apt = (int32_t)p.apt.size();
         ap.apr = (const AppRow*)(c->d_work + w.apr); ap.n_apr = (int32_t)p.apr.size();
+        if (ride) {
+            ap.apr = (const AppRow*)(job.host_lists + w.apr);
+            ap.up_src = job.src; ap.up_dst = job.dst; ap.up_n16 = job.n16; ap.up_blocks = job.blocks;
+        }
         hipError_t e = (hipError_t)timed_launch(c, TS_K_APPEND, true, st, [&] { return launch_append(ap, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "append launch");
     }

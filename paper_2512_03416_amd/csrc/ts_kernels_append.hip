@@ -5,7 +5,9 @@
 // (Sec. 3.4).  Two kernels:
 //   - append_token_kernel: one workgroup per new token of a short sequence (decode rows): looks up the
 //     token's page and slot and scatters its Hkv x D values of K (16-byte dim-chunks) and V
-//     (token-fastest tile) into place;
+//     (token-fastest tile) into place.  The copy of the call's work lists from the pinned staging
+//     buffer to device memory can ride along as extra workgroups of the same launch (a launch costs
+//     more than either job: a decode step then has one kernel less in front of the scan);
 //   - append_tile_kernel: one workgroup per (cache page, KV head) of a chunk: loads the page's up
 //     to 16 new rows with full 256-byte reads, turns them into the K tile and -- through LDS --
 //     into the token-fastest V tile, and writes whole 16-byte vectors.  (Scattering a chunk token
@@ -29,6 +31,12 @@ template <> struct Elem<uint16_t> {
 template <typename SRC, typename DST>
 __global__ __launch_bounds__(256) void append_token_kernel(AppendArgs a)
 {
+    if ((int)blockIdx.x >= a.n_apr) {                  // work-list upload riding along
+        const int64_t stride = (int64_t)a.up_blocks * blockDim.x;
+        for (int64_t i = (int64_t)(blockIdx.x - a.n_apr) * blockDim.x + threadIdx.x; i < a.up_n16; i += stride)
+            ((uint4*)a.up_dst)[i] = ((const uint4*)a.up_src)[i];
+        return;
+    }
     const AppRow r = a.apr[blockIdx.x];
     const int row = r.row, pos = r.pos;
     const int Hkv = a.geo.Hkv, D = a.geo.D;
@@ -161,7 +169,7 @@ int launch_append(const AppendArgs& a, void* stream)
     hipStream_t st = (hipStream_t)stream;
     dim3 block(256);
     if (a.n_apr > 0) {
-        dim3 grid((unsigned)a.n_apr);
+        dim3 grid((unsigned)(a.n_apr + a.up_blocks));
         if (a.geo.q_dtype == TS_F32 && a.geo.kv_dtype == TS_F32)
             hipLaunchKernelGGL((append_token_kernel<float, float>), grid, block, 0, st, a);
         else if (a.geo.q_dtype == TS_BF16 && a.geo.kv_dtype == TS_BF16)
