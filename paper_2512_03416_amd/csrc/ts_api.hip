@@ -498,8 +498,8 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     c->plan.queue.clear(); c->plan.q_off.clear();
     const WorkLayout w = layout_of(c->plan);
     hipStream_t st = (hipStream_t)stream;
-    // token rows and no page check: the upload rides along in the token kernel's launch
-    const bool ride = !c->plan.apr.empty() && !c->validate_pages;
+    // no page check: the upload rides along in the first append launch
+    const bool ride = !c->validate_pages;
     UploadJob job;
     rc = upload_plan(c, st, w, ride ? &job : nullptr);
     if (rc != TS_OK) return rc;
@@ -515,7 +515,8 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     a.apt = (const AppTile*)(c->d_work + w.apt); a.n_apt = (int32_t)c->plan.apt.size();
     a.apr = (const AppRow*)(c->d_work + w.apr); a.n_apr = (int32_t)c->plan.apr.size();
     if (ride) {
-        a.apr = (const AppRow*)(job.host_lists + w.apr);
+        a.apr_host = (const AppRow*)(job.host_lists + w.apr);
+        a.apt_host = (const AppTile*)(job.host_lists + w.apt);
         a.up_src = job.src; a.up_dst = job.dst; a.up_n16 = job.n16; a.up_blocks = job.blocks;
     }
     hipError_t e = (hipError_t)timed_launch(c, TS_K_APPEND, true, st, [&] { return launch_append(a, stream); });
@@ -551,8 +552,8 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     if (rc != TS_OK) return rc;
     const WorkLayout w = layout_of(p);
     hipStream_t st = (hipStream_t)stream;
-    // token rows to append and no page check: the upload rides along in the token kernel's launch
-    const bool ride = k_new && !p.apr.empty() && !c->validate_pages;
+    // new tokens to append and no page check: the upload rides along in the first append launch
+    const bool ride = k_new && !c->validate_pages;
     UploadJob job;
     rc = upload_plan(c, st, w, ride ? &job : nullptr);
     if (rc != TS_OK) return rc;
@@ -571,7 +572,8 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
         ap.apt = (const AppTile*)(c->d_work + w.apt); ap.n_apt = (int32_t)p.apt.size();
         ap.apr = (const AppRow*)(c->d_work + w.apr); ap.n_apr = (int32_t)p.apr.size();
         if (ride) {
-            ap.apr = (const AppRow*)(job.host_lists + w.apr);
+            ap.apr_host = (const AppRow*)(job.host_lists + w.apr);
+            ap.apt_host = (const AppTile*)(job.host_lists + w.apt);
             ap.up_src = job.src; ap.up_dst = job.dst; ap.up_n16 = job.n16; ap.up_blocks = job.blocks;
         }
         hipError_t e = (hipError_t)timed_launch(c, TS_K_APPEND, true, st, [&] { return launch_append(ap, stream); });

@@ -136,10 +136,12 @@ struct AppendArgs {
     const SeqMeta* seqs; int32_t num_seqs; int32_t total_tokens;
     const AppTile* apt; int32_t n_apt;
     const AppRow* apr; int32_t n_apr;
-    // Work-list upload riding along in the launch of the token kernel (up_blocks > 0): extra workgroups
-    // copy up_n16 16-byte pieces from the pinned staging buffer to device memory, and apr then points
-    // into the staging buffer itself (the device copy does not exist before this launch has finished).
+    // Work-list upload riding along in the first append launch (up_blocks > 0): extra workgroups copy
+    // up_n16 16-byte pieces from the pinned staging buffer to device memory, and that launch reads its
+    // own list from the staging buffer (apr_host / apt_host: the device copy does not exist before the
+    // launch has finished).
     const void* up_src; void* up_dst; int64_t up_n16; int32_t up_blocks;
+    const AppRow* apr_host; const AppTile* apt_host;
 };
 
 struct AttnArgs {

@@ -89,6 +89,12 @@ __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
     __shared__ __align__(16) uint16_t ks[16 * kRowPad];
     __shared__ __align__(16) uint16_t vs[16 * kRowPad];
     const int Hkv = a.geo.Hkv;
+    if ((int)blockIdx.x >= a.n_apt * Hkv) {            // work-list upload riding along
+        const int64_t stride = (int64_t)a.up_blocks * blockDim.x;
+        for (int64_t i = (int64_t)(blockIdx.x - a.n_apt * Hkv) * blockDim.x + threadIdx.x; i < a.up_n16; i += stride)
+            ((uint4*)a.up_dst)[i] = ((const uint4*)a.up_src)[i];
+        return;
+    }
     const int g = blockIdx.x % Hkv;
     const AppTile it = a.apt[blockIdx.x / Hkv];
     const int tid = threadIdx.x, t = tid >> 4, c = tid & 15;
@@ -163,11 +169,16 @@ __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
     }
 }
 
-int launch_append(const AppendArgs& a, void* stream)
+int launch_append(const AppendArgs& args, void* stream)
 {
-    if (a.total_tokens <= 0) return (int)hipSuccess;
+    if (args.total_tokens <= 0) return (int)hipSuccess;
     hipStream_t st = (hipStream_t)stream;
     dim3 block(256);
+    AppendArgs a = args;
+    // the upload (if any) rides in the first launch, which then reads its own list from the staging buffer
+    if (a.up_blocks > 0) {
+        if (a.n_apr > 0) a.apr = a.apr_host; else a.apt = a.apt_host;
+    }
     if (a.n_apr > 0) {
         dim3 grid((unsigned)(a.n_apr + a.up_blocks));
         if (a.geo.q_dtype == TS_F32 && a.geo.kv_dtype == TS_F32)
@@ -178,11 +189,13 @@ int launch_append(const AppendArgs& a, void* stream)
             hipLaunchKernelGGL((append_token_kernel<uint16_t, uint8_t>), grid, block, 0, st, a);
         else
             return (int)hipErrorInvalidValue;
+        a.up_blocks = 0;                               // done; the page-wise kernel finds its list on the device
+        a.apt = args.apt;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.n_apt == 0) return (int)e;
     if (a.geo.q_dtype != TS_BF16 || a.geo.D != 128) return (int)hipErrorInvalidValue;
-    dim3 tgrid((unsigned)a.n_apt * (unsigned)a.geo.Hkv);
+    dim3 tgrid((unsigned)a.n_apt * (unsigned)a.geo.Hkv + (unsigned)a.up_blocks);
     if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((append_tile_kernel<uint16_t>), tgrid, block, 0, st, a);
     else hipLaunchKernelGGL((append_tile_kernel<uint8_t>), tgrid, block, 0, st, a);
     return (int)hipGetLastError();
