@@ -1,5 +1,6 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times: the whole
-batch runs on the GPU, a seeded sample of its rows is recomputed by the oracle one by one."""
+batch runs on the GPU, a seeded sample of its rows is recomputed by the oracle one by one, and the
+cache pages of the sampled sequences are compared byte for byte with the oracle's."""
 import numpy as np
 import pytest
 import torch
@@ -9,17 +10,12 @@ import workloads as W
 
 pytestmark = pytest.mark.gpu
 
+_ES = {"f32": 4, "bf16": 2, "fp8": 1}
 
-def _sampled_check(batch, seq_sample, row_stride, tol):
-    import gpu_harness as g
-    print(f"[case] {batch.name} full size S={batch.num_seqs} T={batch.total_q} sample={list(seq_sample)}",
-          flush=True)
-    out, _, _ = g.run_batch(batch)
-    assert np.all(np.isfinite(out))
-    q_off = np.concatenate([[0], np.cumsum(batch.q_lens)])
-    sub = W.to_cpu(W.select_sequences(batch, seq_sample))
+
+def _oracle_caches(sub):
+    """Fresh oracle caches holding the sub-batch's prefix and new tokens."""
     sh = sub.shape
-    ref_out, _, _ = None, None, None
     kc = oracle.new_cache(sub.num_pages, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
     vc = oracle.new_cache(sub.num_pages, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
     ks = None if sub.k_scale is None else oracle.raw(sub.k_scale)
@@ -31,6 +27,66 @@ def _sampled_check(batch, seq_sample, row_stride, tol):
                          sub.block_table, pre, pre, sub.num_pages)
     oracle.kv_append(*args, oracle.raw(sub.k_new), oracle.raw(sub.v_new), kc, vc, ks, vs, sub.block_table,
                      sub.q_lens, sub.ctx_lens, sub.num_pages)
+    return args, kc, vc, ks, vs
+
+
+def _run_gpu_keep_caches(batch):
+    """One pass through the C ABI exactly as gpu_harness.run_batch does, but the caches stay on the
+    GPU (they are gigabytes at these sizes); returns (out float64 numpy, k cache, v cache, page bytes)."""
+    import gpu_harness as g
+    import paper_2512_03416_amd as ts
+    batch = g.to_dev(batch)
+    sh = batch.shape
+    ctx = ts.Context(g.make_desc(batch))
+    kc, vc = g.new_caches(batch)
+    bt = torch.from_numpy(batch.block_table).to("cuda").contiguous()
+    pre = batch.prefix_lens
+    if int(pre.sum()) > 0:
+        ctx.kv_append(batch.k_prefix, batch.v_prefix, kc, vc, batch.k_scale, batch.v_scale, bt, pre, pre)
+    out = torch.full((batch.total_q, sh.num_q_heads, sh.head_dim), float("nan"), dtype=batch.q.dtype,
+                     device="cuda")
+    ctx.mixed_paged_attention(batch.q, batch.k_new, batch.v_new, kc, vc, batch.k_scale, batch.v_scale, bt,
+                              batch.q_lens, batch.ctx_lens, batch.sm_scale, out)
+    torch.cuda.synchronize()
+    ctx.close()
+    page_bytes = sh.num_kv_heads * 16 * sh.head_dim * _ES[sh.kv_dtype]
+    return out.double().cpu().numpy(), kc.view(-1, page_bytes), vc.view(-1, page_bytes), page_bytes
+
+
+def _check_cache_pages(batch, sub, seq_sample, gk, gv, ok, ov, page_bytes):
+    """Every page of every sampled sequence: the GPU's bytes at its page id against the oracle's at the
+    sub-batch's page id, whole pages (all KV heads, all 16 slots, untouched slots included).  Pure
+    indexing through the two page tables; nothing here knows the order of elements inside a page."""
+    ok = ok.view(np.uint8).reshape(-1, page_bytes)
+    ov = ov.view(np.uint8).reshape(-1, page_bytes)
+    n_pages = 0
+    for i, s in enumerate(seq_sample):
+        used = (int(batch.ctx_lens[s]) + 15) // 16
+        gpu_ids = torch.from_numpy(batch.block_table[s, :used].astype(np.int64)).cuda()
+        ref_ids = sub.block_table[i, :used].astype(np.int64)
+        assert np.array_equal(gk[gpu_ids].cpu().numpy(), ok[ref_ids]), f"K cache pages of sequence {s} differ"
+        assert np.array_equal(gv[gpu_ids].cpu().numpy(), ov[ref_ids]), f"V cache pages of sequence {s} differ"
+        n_pages += used
+    return n_pages
+
+
+def _sampled_check(batch, seq_sample, row_stride, tol, tile_rows=()):
+    """tile_rows: (sequence, first chunk token, count) runs of consecutive chunk rows that the oracle
+    recomputes in full, on top of the strided sample."""
+    print(f"[case] {batch.name} full size S={batch.num_seqs} T={batch.total_q} sample={list(seq_sample)}",
+          flush=True)
+    out, gk, gv, page_bytes = _run_gpu_keep_caches(batch)
+    assert np.all(np.isfinite(out))
+    # pages the batch does not use must still hold the fill pattern (a stray store would show here)
+    used_ids = np.unique(batch.block_table[batch.block_table >= 0])
+    unused = np.setdiff1d(np.arange(batch.num_pages), used_ids)
+    if unused.size:
+        pick = torch.from_numpy(unused[:: max(1, unused.size // 4096)].astype(np.int64)).cuda()
+        assert bool((gk[pick] == 0xFF).all()) and bool((gv[pick] == 0xFF).all()), "an unused page was written"
+    q_off = np.concatenate([[0], np.cumsum(batch.q_lens)])
+    sub = W.to_cpu(W.select_sequences(batch, seq_sample))
+    args, kc, vc, ks, vs = _oracle_caches(sub)
+    n_pages = _check_cache_pages(batch, sub, seq_sample, gk, gv, kc, vc, page_bytes)
     ref = oracle.mixed_paged_attention(*args, oracle.raw(sub.q), kc, vc, ks, vs, sub.block_table, sub.q_lens,
                                        sub.ctx_lens, sub.sm_scale, sub.num_pages, row_stride=row_stride)
     worst, n_rows, o = 0.0, 0, 0
@@ -43,7 +99,27 @@ def _sampled_check(batch, seq_sample, row_stride, tol):
             worst = max(worst, float(np.max(np.abs(got[sel] - want[sel]))))
         n_rows += int(sel.sum())
         o += ql
-    print(f"       {n_rows} sampled rows, max abs err {worst:.3e} (bar {tol})", flush=True)
+    # whole runs of consecutive chunk rows (complete query tiles of the prefill kernel): the oracle
+    # sees the chunk tokens in front of the run as cached prefix, which is the same attention problem
+    sub_q_off = np.concatenate([[0], np.cumsum(sub.q_lens)])
+    sub_p_off = np.concatenate([[0], np.cumsum(sub.prefix_lens)])
+    for s, t0, cnt in tile_rows:
+        i = list(seq_sample).index(s)
+        ql, pre = int(sub.q_lens[i]), int(sub.prefix_lens[i])
+        assert 0 <= t0 and t0 + cnt <= ql
+        a, b = int(sub_q_off[i]), int(sub_p_off[i])
+        run = W.make_batch(sub.shape, [cnt], [pre + t0 + cnt], seed=5, sm_scale=sub.sm_scale)
+        run.q = sub.q[a + t0:a + t0 + cnt].clone()
+        run.k_new, run.v_new = sub.k_new[a + t0:a + t0 + cnt].clone(), sub.v_new[a + t0:a + t0 + cnt].clone()
+        run.k_prefix = torch.cat([sub.k_prefix[b:b + pre], sub.k_new[a:a + t0]]).contiguous()
+        run.v_prefix = torch.cat([sub.v_prefix[b:b + pre], sub.v_new[a:a + t0]]).contiguous()
+        run.k_scale, run.v_scale = sub.k_scale, sub.v_scale
+        want, _, _ = oracle.run_batch(run)
+        got = out[q_off[s] + t0:q_off[s] + t0 + cnt]
+        worst = max(worst, float(np.max(np.abs(got - want))))
+        n_rows += cnt
+    print(f"       {n_rows} sampled rows, max abs err {worst:.3e} (bar {tol}); {n_pages} cache pages byte-equal",
+          flush=True)
     assert n_rows > 0 and worst <= tol
 
 
@@ -58,7 +134,9 @@ def test_config2_decode_full_size_sampled():
 def test_config4_burst_full_size_sampled():
     b = W.config4(device="cuda")
     dec = np.random.default_rng(8).choice(128, size=6, replace=False).tolist()
-    _sampled_check(b, sorted(dec) + [128, 131], 7, 2e-2)      # every 7th row of the sample, two chunks included
+    # every 7th row of the sample, two chunks included, plus whole query tiles (64 tokens x 4 heads) of one
+    # chunk: one in the middle with its neighbours' edges, and the chunk's last
+    _sampled_check(b, sorted(dec) + [128, 131], 7, 2e-2, tile_rows=[(131, 1000, 100), (131, 2048 - 64, 64)])
 
 
 def test_config5_fp8_full_size_sampled():
@@ -66,7 +144,8 @@ def test_config5_fp8_full_size_sampled():
     assert b.shape.kv_dtype == "fp8" and b.num_seqs == 528
     dec = np.random.default_rng(9).choice(512, size=5, replace=False).tolist()
     longest = int(np.argmax(b.ctx_lens[:512]))
-    _sampled_check(b, sorted(set(dec + [longest])) + [512, 527], 61, 6e-2)   # two chunks, every 61st row of the sample
+    # two chunks, every 61st row of the sample, plus two whole query tiles (32 tokens x 8 heads) and the edges around them
+    _sampled_check(b, sorted(set(dec + [longest])) + [512, 527], 61, 6e-2, tile_rows=[(527, 2040, 80)])
 
 
 @pytest.mark.parametrize("step", [0, 3])

@@ -236,6 +236,59 @@ def test_unused_slots_are_poison_and_never_read():
 
 
 # ------------------------------------------------------------------------------------------
+# row sampling (the full-size GPU parity tests and the bench's CPU leg recompute a sample of rows)
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("kv", ["f32", "bf16", "fp8"])
+def test_row_sampling_selects_exactly_the_strided_rows(kv):
+    """row_stride = k, row_offset = o must give rows o, o+k, ... bit-identical to the same rows of
+    the run over all rows (which the dense brute force pins), and leave every other row untouched."""
+    shape = AttnShape(8, 2, 64, "f32" if kv == "f32" else "bf16", kv)
+    b = make_batch(shape, [1, 9, 0, 1, 23, 1], [40, 9, 17, 1, 60, 33], seed=41, pool_rule=1.5)
+    sh = b.shape
+    args = (sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.q_dtype, sh.kv_dtype)
+    full, kc, vc = oracle.run_batch(b)
+    T = b.total_q
+    assert T == 35 and np.all(np.isfinite(full))
+    assert np.max(np.abs(full - dense_bruteforce(b))) <= 1e-12
+    ks = None if b.k_scale is None else oracle.raw(b.k_scale)
+    vs = None if b.v_scale is None else oracle.raw(b.v_scale)
+    for stride, off in [(1, 0), (2, 0), (2, 1), (3, 2), (7, 5), (7, 0), (34, 34), (35, 0), (100, 3), (1, 12),
+                        (5, 35), (4, 1000), (0, 0)]:
+        got = oracle.mixed_paged_attention(*args, oracle.raw(b.q), kc, vc, ks, vs, b.block_table, b.q_lens,
+                                           b.ctx_lens, b.sm_scale, b.num_pages, row_stride=stride,
+                                           row_offset=off)
+        want_rows = list(range(off, T, max(stride, 1)))      # a stride below 1 means every row
+        sel = np.zeros(T, dtype=bool)
+        sel[want_rows] = True
+        assert np.array_equal(got[sel], full[sel]), (stride, off)
+        assert np.all(np.isnan(got[~sel])), (stride, off)
+        assert int((~np.isnan(got[:, 0, 0])).sum()) == len(want_rows)
+
+
+def test_row_sampling_rows_belong_to_the_right_sequence():
+    """A sampled row must be computed with its own sequence's page list and key count: compare with
+    the one-row entry point called with those, sequence by sequence."""
+    b = make_batch(AttnShape(4, 2, 64, "bf16", "bf16"), [5, 1, 12], [21, 70, 12], seed=42, pool_rule=1.2)
+    sh = b.shape
+    args = (sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.q_dtype, sh.kv_dtype)
+    _, kc, vc = oracle.run_batch(b)
+    got = oracle.mixed_paged_attention(*args, oracle.raw(b.q), kc, vc, None, None, b.block_table, b.q_lens,
+                                       b.ctx_lens, b.sm_scale, b.num_pages, row_stride=4, row_offset=3)
+    q_off = np.concatenate([[0], np.cumsum(b.q_lens)])
+    n = 0
+    for row in range(3, b.total_q, 4):
+        s = int(np.searchsorted(q_off, row, side="right") - 1)
+        n_keys = int(b.ctx_lens[s] - b.q_lens[s] + (row - q_off[s]) + 1)
+        for h in range(sh.num_q_heads):
+            _, o = oracle.attention_row(*args, oracle.raw(b.q), kc, vc, None, None, b.block_table[s], n_keys,
+                                        row, h, b.sm_scale, b.num_pages)
+            assert np.array_equal(got[row, h], o)
+        n += 1
+    assert n == 4
+
+
+# ------------------------------------------------------------------------------------------
 # chunking
 # ------------------------------------------------------------------------------------------
 
