@@ -91,7 +91,9 @@ int ts_destroy(ts_ctx *ctx);
 
 /* Pre-sizes scratch for batches of up to max_tokens query tokens, max_seqs sequences and
  * max_ctx_pages cache pages in total over the batch (sum over sequences of ceil(ctx/16)), so
- * that later GPU calls never allocate.  Without it scratch grows on demand, which synchronises
+ * that later GPU calls with batches inside these limits never allocate.  The sizes follow the
+ * options in force at the call ("decode_split_pages", "xcd_count"): set those first, or call
+ * ts_reserve again after changing them.  Without it scratch grows on demand, which synchronises
  * the device once per growth. */
 int ts_reserve(ts_ctx *ctx, int64_t max_tokens, int64_t max_seqs, int64_t max_ctx_pages);
 
@@ -155,7 +157,7 @@ const char *ts_last_error(const ts_ctx *ctx);
 /* Tuning knobs (all optional).  Names:
  *   "decode_split_pages"  longest page range of one decode item (0 = choose from the batch)
  *   "prefill_path"        0 = MFMA tiles where supported, 1 = force the generic row kernel
- *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave (process-wide)
+ *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave
  *   "mixed_persistent"    1 (default) = decode items and prefill tiles of a mixed batch share one
  *                         persistent launch; 0 = decode kernel, then prefill kernel
  *   "xcd_count"           accelerator dies the prefill launch order is laid out for (default 8)
@@ -168,9 +170,15 @@ const char *ts_last_error(const ts_ctx *ctx);
  * Unknown names give TS_ERR_INVALID_ARG. */
 int ts_set_option(ts_ctx *ctx, const char *name, int64_t value);
 
-/* Optional per-kernel timing with HIP events recorded on the caller's stream around each launch
+/* Reads an option back (same names as ts_set_option), and the read-only counter
+ *   "scratch_allocations"  device and pinned-host allocations this context has made so far
+ * (creation and ts_reserve included): a serving loop that must not allocate reads it before and
+ * after its calls. */
+int ts_get_option(const ts_ctx *ctx, const char *name, int64_t *value);
+
+/* Measurement aid, not a step of the pass: optional per-kernel timing with HIP events recorded on the caller's stream around each launch
  * (enable with ts_set_option(ctx, "kernel_timing", N): every N-th call is timed; two event records
- * per timed launch).
+ * per timed launch, each of which idles the GPU for a few microseconds).
  * ts_kernel_times waits for the recorded events, then reports, per kernel, the number of timed
  * launches and their mean duration in milliseconds since the last reset. */
 enum { TS_K_APPEND = 0, TS_K_DECODE = 1, TS_K_COMBINE = 2, TS_K_PREFILL = 3, TS_K_ROWS = 4, TS_K_MIXED = 5,
@@ -180,21 +188,6 @@ typedef struct {
     double mean_ms[TS_K_COUNT];
 } ts_kernel_stats;
 int ts_kernel_times(ts_ctx *ctx, ts_kernel_stats *out, int reset);
-
-/* Calibration helpers for bandwidth measurements: a plain streaming copy (dst[i] = src[i]) and a
- * streaming read (sum into a 4-byte result) of `bytes` bytes (multiple of 16) of DEV memory,
- * launched on `stream`.  They let a profile be scaled against a kernel of known traffic. */
-int ts_calib_copy(void *stream, const void *src, void *dst, int64_t bytes);
-int ts_calib_read(void *stream, const void *src, void *result4, int64_t bytes);
-
-/* Calibration helper for the matrix cores: one resident workgroup per CU issues `iters` x 16
- * bf16 32x32x16 MFMAs per wave (8 waves, two per SIMD) back to back, A operands read from LDS as in
- * the prefill kernel; softmax != 0 adds that kernel's vector work per MFMA (multiply-add,
- * exponential, add, half a pack).  operands: DEV, 131072 bytes of bf16 values of the caller's
- * choosing (the rate the chip sustains depends on how many bits toggle: the clock it holds under
- * this load is set by its power limit); result4: DEV, 4 bytes; iters: 1..200000; *flops (HOST) is
- * set to the floating-point operations of the launch.  Asynchronous on `stream`. */
-int ts_calib_mfma(void *stream, const void *operands, void *result4, int iters, int softmax, int64_t *flops);
 
 /* Host only -- step a0.  Describes the work the planner makes of a batch, without touching a
  * GPU: how many decode split items, combine rows, prefill tiles and generic rows.

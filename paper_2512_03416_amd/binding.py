@@ -16,8 +16,8 @@ TS_VELOCITY_RESET, TS_VELOCITY_SYNC = 1, 2
 
 EXPORTS = ["ts_check_desc", "ts_cache_bytes", "ts_create", "ts_destroy", "ts_reserve", "ts_kv_append",
            "ts_mixed_paged_attention", "ts_token_velocity", "ts_last_error", "ts_set_option",
-           "ts_plan_describe", "ts_plan_export", "ts_kernel_times", "ts_calib_copy",
-           "ts_calib_read", "ts_calib_mfma"]
+           "ts_get_option", "ts_plan_describe", "ts_plan_export", "ts_kernel_times"]
+CALIB_EXPORTS = ["ts_calib_copy", "ts_calib_read", "ts_calib_mfma"]     # include/tokenscale_calib.h
 
 KERNEL_NAMES = ["append", "decode", "combine", "prefill", "rows", "mixed"]
 
@@ -98,6 +98,8 @@ def load_library():
     lib.ts_last_error.restype = ctypes.c_char_p
     lib.ts_set_option.argtypes = [vp, ctypes.c_char_p, ctypes.c_int64]
     lib.ts_set_option.restype = ctypes.c_int
+    lib.ts_get_option.argtypes = [vp, ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64)]
+    lib.ts_get_option.restype = ctypes.c_int
     lib.ts_plan_describe.argtypes = [ctypes.POINTER(Desc), i32p, i32p, ctypes.c_int, ctypes.c_int32,
                                      ctypes.POINTER(PlanInfo)]
     lib.ts_plan_describe.restype = ctypes.c_int
@@ -225,6 +227,13 @@ class Context:
 
     def set_option(self, name: str, value: int):
         self._check(self._lib.ts_set_option(self._h, name.encode(), int(value)))
+
+    def get_option(self, name: str) -> int:
+        v = ctypes.c_int64(0)
+        rc = self._lib.ts_get_option(self._h, name.encode(), ctypes.byref(v))
+        if rc != TS_OK:
+            raise TokenScaleError(rc, f"ts_get_option({name})")
+        return int(v.value)
 
     def kv_append(self, k_new, v_new, k_cache, v_cache, k_scale, v_scale, block_table, q_lens,
                   ctx_lens, stream=None):

@@ -15,7 +15,6 @@
 
 namespace ts {
 int check_desc_msg(const ts_attn_desc* d, std::string* err);
-void set_decode_nbuf(int n);
 }
 
 using namespace ts;
@@ -63,6 +62,10 @@ struct ts_ctx {
     hipStream_t last_stream = nullptr;
     bool have_work = false;
     bool validate_pages = false;       // debug: check the page ids of a batch before anything is launched
+    // launch shapes of this context's GPU, asked once per context (and again when the prefetch depth changes)
+    int dec_nbuf = 2;                  // KV tiles in flight per decode wave
+    int dec_slots = 0;                 // resident decode workgroups for dec_nbuf
+    int mixed_wgs = 0;                 // resident workgroups of the persistent kernel
     // optional per-kernel timing
     int timing = 0;                    // 0 = off, N = time the launches of every N-th pass
     uint64_t timing_pass = 0;
@@ -70,6 +73,7 @@ struct ts_ctx {
     struct Timed { int which; hipEvent_t a, b; };
     std::vector<Timed> timed;          // recorded, not yet read
     std::vector<hipEvent_t> ev_pool;   // spare events
+    int64_t n_alloc = 0;               // device / pinned allocations made so far
     uint64_t k_launches[TS_K_COUNT] = {};
     double k_ms[TS_K_COUNT] = {};
 };
@@ -114,6 +118,7 @@ int ensure_work(ts_ctx* c, size_t bytes)
     hipError_t e = hipMalloc((void**)&c->d_work, cap);
     if (e != hipSuccess) return fail(c, TS_ERR_NOMEM, "work-list scratch allocation failed");
     c->work_cap = cap;
+    c->n_alloc += 1;
     return TS_OK;
 }
 
@@ -130,6 +135,7 @@ int ensure_partials(ts_ctx* c, int64_t slots)
         hipMalloc((void**)&c->d_part_ml, (size_t)cap * Hq * 2 * sizeof(float)) != hipSuccess)
         return fail(c, TS_ERR_NOMEM, "split-K partial scratch allocation failed");
     c->part_cap = cap;
+    c->n_alloc += 2;
     return TS_OK;
 }
 
@@ -155,6 +161,7 @@ int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out)
             return fail(c, TS_ERR_HIP, "pinned staging memory is not visible to the GPU");
         }
         s.cap = cap;
+        c->n_alloc += 1;
     }
     *out = &s;
     return TS_OK;
@@ -389,6 +396,12 @@ extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
             rc = TS_ERR_NOMEM;
         }
     }
+    if (rc == TS_OK && desc_uses_mfma(c->desc)) {
+        // launch shapes of this GPU, asked here so that no later call has to
+        c->dec_slots = decode_resident_workgroups(c->desc.kv_dtype, c->dec_nbuf);
+        c->mixed_wgs = mixed_resident_workgroups(c->desc.kv_dtype);
+        if (c->mixed_wgs <= 0) rc = fail(c, TS_ERR_HIP, "occupancy query of the persistent kernel failed");
+    }
     if (rc != TS_OK) { g_create_error = c->err; ts_destroy(c); return rc; }
     *out = c;
     return TS_OK;
@@ -419,15 +432,20 @@ extern "C" int ts_reserve(ts_ctx* c, int64_t max_tokens, int64_t max_seqs, int64
     if (max_tokens < 0 || max_seqs < 0 || max_ctx_pages < 0)
         return fail(c, TS_ERR_INVALID_ARG, "negative size");
     DeviceGuard guard(c->device);
-    // worst case: every token a generic row or decode row, decode items of >= 8 pages each plus one
-    // per sequence, a prefill tile per 8 tokens.
-    const size_t items = (size_t)max_ctx_pages / 8 + (size_t)max_seqs + (size_t)max_tokens;
-    const size_t bytes = ((size_t)max_seqs + 1) * sizeof(SeqMeta) + items * (sizeof(DecItem) + sizeof(CmbItem)) +
-                         (size_t)max_tokens * (sizeof(RowItem) + sizeof(PfItem)) +
-                         (size_t)max_tokens * c->desc.num_kv_heads * 2 * (sizeof(PfSlot) + sizeof(QItem)) +
-                         items * c->desc.num_kv_heads * sizeof(QItem) +
-                         ((size_t)max_tokens / 8 + 2 * (size_t)max_seqs) * sizeof(AppTile) +
-                         (size_t)max_tokens * sizeof(AppRow) + 4096;
+    // Upper bounds of every work list for such a batch under the options in force now: a sequence of n
+    // pages gives at most n / L + 1 decode items (L = the decode_split_pages option, or the planner's own
+    // minimum of 32 pages), a chunk of q tokens at most q / tile + 1 tiles and q / 16 + 2 append pages; the
+    // die-aware launch order pads every die's list to the longest one.
+    const size_t T = (size_t)max_tokens, S = (size_t)max_seqs, P = (size_t)max_ctx_pages;
+    const size_t Hkv = (size_t)c->desc.num_kv_heads, xcds = (size_t)std::max(1, c->opt.xcds);
+    const size_t L = c->opt.split_pages > 0 ? (size_t)c->opt.split_pages : 32;
+    const size_t TT = (size_t)std::max<int32_t>(1, c->opt.tile_tokens > 0 ? c->opt.tile_tokens : prefill_tile_tokens(c->desc));
+    const size_t items = P / L + S;
+    const size_t tiles = T / TT + S;
+    const size_t bytes = (S + 1) * sizeof(SeqMeta) + items * (sizeof(DecItem) + sizeof(CmbItem)) + tiles * sizeof(PfItem) +
+                         tiles * Hkv * xcds * sizeof(PfSlot) + T * sizeof(RowItem) +
+                         (items + tiles) * Hkv * sizeof(QItem) + (xcds + 1) * sizeof(int32_t) +
+                         (T / kPage + 2 * S) * sizeof(AppTile) + T * sizeof(AppRow) + 16 * 16;
     int rc = ensure_work(c, bytes);
     if (rc != TS_OK) return rc;
     for (int i = 0; i < kRing; ++i) {
@@ -435,7 +453,7 @@ extern "C" int ts_reserve(ts_ctx* c, int64_t max_tokens, int64_t max_seqs, int64
         rc = acquire_slot(c, bytes, &s);
         if (rc != TS_OK) return rc;
     }
-    return ensure_partials(c, (int64_t)(max_ctx_pages / 8 + max_seqs));
+    return ensure_partials(c, (int64_t)items);
 }
 
 extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
@@ -453,7 +471,11 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
     }
     if (!strcmp(name, "decode_prefetch_tiles")) {
         if (value < 2 || value > 4) return fail(c, TS_ERR_INVALID_ARG, "decode_prefetch_tiles must be 2..4");
-        set_decode_nbuf((int)value);
+        if (c->dec_nbuf != (int)value) {
+            DeviceGuard guard(c->device);
+            c->dec_nbuf = (int)value;
+            if (desc_uses_mfma(c->desc)) c->dec_slots = decode_resident_workgroups(c->desc.kv_dtype, c->dec_nbuf);
+        }
         return TS_OK;
     }
     if (!strcmp(name, "mixed_persistent")) {
@@ -476,6 +498,21 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         return TS_OK;
     }
     return fail(c, TS_ERR_INVALID_ARG, std::string("unknown option: ") + name);
+}
+
+extern "C" int ts_get_option(const ts_ctx* c, const char* name, int64_t* value)
+{
+    if (!c || !name || !value) return TS_ERR_INVALID_ARG;
+    if (!strcmp(name, "decode_split_pages")) *value = c->opt.split_pages;
+    else if (!strcmp(name, "prefill_path")) *value = c->opt.prefill_generic ? 1 : 0;
+    else if (!strcmp(name, "decode_prefetch_tiles")) *value = c->dec_nbuf;
+    else if (!strcmp(name, "mixed_persistent")) *value = c->opt.mixed_persistent ? 1 : 0;
+    else if (!strcmp(name, "xcd_count")) *value = c->opt.xcds;
+    else if (!strcmp(name, "validate_block_table")) *value = c->validate_pages ? 1 : 0;
+    else if (!strcmp(name, "kernel_timing")) *value = c->timing;
+    else if (!strcmp(name, "scratch_allocations")) *value = c->n_alloc;
+    else return TS_ERR_INVALID_ARG;                         // (const context: the error text is left alone)
+    return TS_OK;
 }
 
 extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const void* v_new, void* k_cache,
@@ -539,11 +576,7 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     if (!(sm_scale == sm_scale)) return fail(c, TS_ERR_INVALID_ARG, "sm_scale is NaN");
     DeviceGuard guard(c->device);
     c->timing_now = c->timing > 0 && (c->timing_pass++ % (uint64_t)c->timing) == 0;
-    if (desc_uses_mfma(c->desc)) {
-        const int slots = decode_resident_workgroups(c->desc.kv_dtype);
-        if (slots > 0) c->opt.wg_slots = slots;
-
-    }
+    if (c->dec_slots > 0) c->opt.wg_slots = c->dec_slots;
     build_plan(c->desc, q_lens, ctx_lens, num_seqs, c->opt, &c->plan);
     const Plan& p = c->plan;
     if (p.info.total_tokens == 0) return TS_OK;
@@ -593,6 +626,7 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     a.queue = (const QItem*)(c->d_work + w.queue); a.q_off = (const int32_t*)(c->d_work + w.q_off);
     a.n_queue = (int32_t)p.queue.size(); a.n_xcd = p.q_off.empty() ? 0 : (int32_t)p.q_off.size() - 1;
     a.q_ctr = c->d_q_ctr;
+    a.dec_nbuf = c->dec_nbuf; a.mixed_wgs = c->mixed_wgs;
     a.part_o = c->d_part_o; a.part_ml = c->d_part_ml;
 
     hipError_t e;

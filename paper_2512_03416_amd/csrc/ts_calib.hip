@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include "tokenscale.h"
+#include "tokenscale_calib.h"
 #include "ts_device.h"
 
 namespace {

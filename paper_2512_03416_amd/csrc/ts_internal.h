@@ -160,6 +160,8 @@ struct AttnArgs {
     const QItem* queue; const int32_t* q_off; int32_t n_queue; int32_t n_xcd;
     int32_t* q_ctr;            // n_xcd queue heads + 1 finished-workgroup count, zero between launches
     const RowItem* rows; int32_t n_rows;
+    int32_t dec_nbuf;          // KV tiles in flight per decode wave (2..4)
+    int32_t mixed_wgs;         // workgroups of the persistent kernel that are resident on the GPU at once
     // split-K partials: o [slot][Hq][D] fp32 (unnormalised), ml [slot][Hq][2] = (max, sum) in log2 units
     float* part_o; float* part_ml;
 };
@@ -169,7 +171,10 @@ int launch_append(const AppendArgs& a, void* stream);
 int launch_rows(const AttnArgs& a, void* stream);
 int launch_decode(const AttnArgs& a, void* stream);
 int launch_combine(const AttnArgs& a, void* stream);
-int decode_resident_workgroups(int kv_dtype);   // on the current device, 0 if unknown
+// Resident workgroups of the decode / persistent kernel on the current device (0 if unknown).  The
+// caller keeps the answers per context: two contexts may sit on different GPUs.
+int decode_resident_workgroups(int kv_dtype, int nbuf);
+int mixed_resident_workgroups(int kv_dtype);
 int launch_prefill(const AttnArgs& a, void* stream);
 int launch_mixed(const AttnArgs& a, void* stream);
 

@@ -55,14 +55,11 @@ __global__ __launch_bounds__(128) void combine_kernel(AttnArgs a)
     ((uint16_t*)a.out)[((int64_t)it.row * Hq + h) * D + d] = (uint16_t)float_to_bf16_bits(o * vscale / L);
 }
 
-static int g_decode_nbuf = 2;
-void set_decode_nbuf(int n) { g_decode_nbuf = n; }
-
 template <typename KT>
 static int launch_decode_t(const AttnArgs& a, hipStream_t st)
 {
     dim3 grid((unsigned)a.n_dec * (unsigned)a.geo.Hkv), block(64 * kDecWaves);
-    switch (g_decode_nbuf) {
+    switch (a.dec_nbuf) {
     case 3: hipLaunchKernelGGL((decode_kernel<KT, 3>), grid, block, 0, st, a); break;
     case 4: hipLaunchKernelGGL((decode_kernel<KT, 4>), grid, block, 0, st, a); break;
     default: hipLaunchKernelGGL((decode_kernel<KT, 2>), grid, block, 0, st, a); break;
@@ -83,19 +80,13 @@ static int resident_t(int nbuf)
     return e == hipSuccess ? per_cu : 0;
 }
 
-int decode_resident_workgroups(int kv_dtype)
+int decode_resident_workgroups(int kv_dtype, int nbuf)
 {
-    static int cache[2][5] = {};
-    const int k = kv_dtype == TS_FP8_E4M3 ? 1 : 0;
-    int& slot = cache[k][g_decode_nbuf];
-    if (slot == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-            return 0;
-        slot = cus * (k ? resident_t<uint8_t>(g_decode_nbuf) : resident_t<uint16_t>(g_decode_nbuf));
-    }
-    return slot;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return 0;
+    return cus * (kv_dtype == TS_FP8_E4M3 ? resident_t<uint8_t>(nbuf) : resident_t<uint16_t>(nbuf));
 }
 
 int launch_decode(const AttnArgs& a, void* stream)

@@ -62,18 +62,26 @@ __global__ __launch_bounds__(kPfThreads) void mixed_kernel(AttnArgs a)
 }
 
 template <typename KT>
+static int resident_mixed_t()
+{
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mixed_kernel<KT, 2>, kPfThreads, 0) != hipSuccess)
+        return 0;
+    return cus * (per_cu > 0 ? per_cu : 1);
+}
+
+int mixed_resident_workgroups(int kv_dtype)
+{
+    return kv_dtype == TS_FP8_E4M3 ? resident_mixed_t<uint8_t>() : resident_mixed_t<uint16_t>();
+}
+
+template <typename KT>
 static int launch_mixed_t(const AttnArgs& a, hipStream_t st)
 {
-    static int wgs[2] = {0, 0};                                // resident workgroups, per element type
-    int& n = wgs[sizeof(KT) == 1 ? 1 : 0];
-    if (n == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mixed_kernel<KT, 2>, kPfThreads, 0) != hipSuccess)
-            return (int)hipErrorUnknown;
-        n = cus * (per_cu > 0 ? per_cu : 1);
-    }
+    const int n = a.mixed_wgs;                                 // resident workgroups on the context's GPU
+    if (n <= 0) return (int)hipErrorInvalidValue;
     const int grid = n < a.n_queue ? n : a.n_queue;
     hipLaunchKernelGGL((mixed_kernel<KT, 2>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
     return (int)hipGetLastError();

@@ -105,14 +105,14 @@ __device__ __forceinline__ void copy_2k_to_lds(uint32_t lds_addr, const void* ba
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %1, %2\n\t"
                  "global_load_lds_dwordx4 %1, %2 offset:1024\n"
-                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
 }
 template <int OFF>
 __device__ __forceinline__ void copy_1k_to_lds(uint32_t lds_addr, const void* base, uint32_t lane_off)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %1, %2 offset:%3\n"
-                 :: "s"(lds_addr), "v"(lane_off), "s"(base), "n"(OFF) : "memory");
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base), "n"(OFF) : "memory", "m0");
 }
 __device__ __forceinline__ int copy_k_lane_offset(int lane) { return (lane >> 4) * 256 + swap23(lane & 15) * 16; }
 __device__ __forceinline__ int copy_v_lane_offset(int lane) { return (lane & 31) * 32 + (lane >> 5) * 16; }

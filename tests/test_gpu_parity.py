@@ -526,6 +526,33 @@ def test_one_context_many_different_batches_in_a_row():
     ctx.close()
 
 
+def test_two_contexts_keep_their_own_options():
+    """Options are per context: one context with four tiles in flight per decode wave and forced splits,
+    one with the defaults, called in turns on one GPU; each reports its own settings and both match the
+    oracle."""
+    import paper_2512_03416_amd as ts
+    g = gpu()
+    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+    mk = lambda: make_batch(shape, [1, 1, 90, 1], [2500, 300, 150, 17], seed=72, value_mult=0.5)
+    b = g.to_dev(mk())
+    ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
+    c1, c2 = ts.Context(g.make_desc(b)), ts.Context(g.make_desc(b))
+    c1.set_option("decode_prefetch_tiles", 4)
+    c1.set_option("decode_split_pages", 16)
+    c1.set_option("mixed_persistent", 0)
+    assert c1.get_option("decode_prefetch_tiles") == 4 and c2.get_option("decode_prefetch_tiles") == 2
+    assert c1.get_option("decode_split_pages") == 16 and c2.get_option("decode_split_pages") == 0
+    assert c1.get_option("mixed_persistent") == 0 and c2.get_option("mixed_persistent") == 1
+    for _ in range(2):
+        for c in (c1, c2):
+            out, gk, gv = g.run_batch(b, ctx=c)
+            assert same_bytes(gk, rk) and same_bytes(gv, rv)
+            assert float(np.max(np.abs(out - ref))) <= TOL["bf16"]
+    assert c1.get_option("decode_prefetch_tiles") == 4 and c2.get_option("decode_prefetch_tiles") == 2
+    c1.close()
+    c2.close()
+
+
 def test_reserve_then_no_growth_and_kernel_timing_counts():
     """ts_reserve sizes the scratch for the largest batch to come (a pass within it matches the oracle);
     with kernel timing on every pass, ts_kernel_times counts one launch of each kernel the batch
@@ -540,13 +567,17 @@ def test_reserve_then_no_growth_and_kernel_timing_counts():
     with pytest.raises(ts.TokenScaleError) as e:
         ctx.reserve(-1, 4, 100)
     assert e.value.code == binding.TS_ERR_INVALID_ARG
-    ctx.reserve(4096, 64, 4096)
     ctx.set_option("decode_split_pages", 8)                  # split rows: decode, combine and prefill all run
     ctx.set_option("mixed_persistent", 0)
+    ctx.reserve(4096, 64, 4096)                              # (sized for the options in force)
+    n_alloc = ctx.get_option("scratch_allocations")
     ctx.set_option("kernel_timing", 1)
     ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
     for _ in range(3):
         out, gk, gv = g.run_batch(b, ctx=ctx)
+    assert ctx.get_option("scratch_allocations") == n_alloc  # nothing grew
+    with pytest.raises(ts.TokenScaleError):
+        ctx.get_option("no_such_option")
     assert same_bytes(gk, rk) and same_bytes(gv, rv)
     assert float(np.max(np.abs(out - ref))) <= TOL["bf16"]
     kt = ctx.kernel_times()

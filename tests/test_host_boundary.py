@@ -33,7 +33,17 @@ def test_library_exports_every_policy_symbol():
         assert hasattr(lib, name), name
     assert declared == set(policy.EXPORTS)
     headers = sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
-    assert headers == ["tokenscale.h", "tokenscale_policy.h"]      # every header is covered by a symbol test
+    assert headers == ["tokenscale.h", "tokenscale_calib.h", "tokenscale_policy.h"]   # each has a symbol test
+
+
+def test_library_exports_every_calibration_symbol():
+    hdr = open(os.path.join(ROOT, "include", "tokenscale_calib.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ts_[a-z_0-9]+)\s*\(", hdr))
+    lib = ctypes.CDLL(ts.library_path())
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(binding.CALIB_EXPORTS)
 
 
 def D(**kw):
