@@ -85,7 +85,7 @@ int ts_check_desc(const ts_attn_desc *desc);
 int64_t ts_cache_bytes(const ts_attn_desc *desc);
 
 /* Creates a context on GPU `device` (made current for the calling thread during the call).
- * Allocates a small initial scratch. */
+ * Allocates an initial scratch and the pinned staging ring (4 x 1 MiB) for the work lists. */
 int ts_create(const ts_attn_desc *desc, int device, ts_ctx **out);
 int ts_destroy(ts_ctx *ctx);
 
@@ -132,6 +132,30 @@ int ts_mixed_paged_attention(ts_ctx *ctx, void *stream,
                              const int32_t *q_lens, const int32_t *ctx_lens, int num_seqs,
                              float sm_scale,
                              void *out);
+
+/* The same pass for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels, same results as
+ * ts_mixed_paged_attention, but all device scratch of the call (work lists, split-K partial results,
+ * queue heads of the persistent launch) lives in a static device array of 8 MiB that the library
+ * holds on every GPU it runs on until the process ends, and the call makes no device, pinned-host or
+ * event allocation and frees nothing (the planner's host-side lists use the ordinary heap).
+ * Limits: the batch's work lists must fit 1 MiB - 4 KiB and its split decode rows
+ * 7 MiB / (Hq * (D + 2) * 4) partial results (220 for 64 query heads of 128 dims); beyond either the call fails
+ * with TS_ERR_UNSUPPORTED before anything is launched, and ts_last_error names the size.  The
+ * "kernel_timing" option is ignored, "validate_block_table" is refused (TS_ERR_UNSUPPORTED).
+ * The array is shared by every context and call on that GPU and keeps the last call's contents (the
+ * call itself puts back to zero what must start at zero): calls that overlap in time on one GPU,
+ * from any contexts or streams, race.  Calls on one context are ordered as for the other entry
+ * points. */
+int ts_mixed_paged_attention_noalloc(ts_ctx *ctx, void *stream,
+                                     const void *q,
+                                     const void *k_new, const void *v_new,
+                                     void *k_cache, void *v_cache,
+                                     const float *k_scale, const float *v_scale,
+                                     const int32_t *block_table,
+                                     const int32_t *q_lens, const int32_t *ctx_lens, int num_seqs,
+                                     float sm_scale,
+                                     void *out);
 
 /* Step a6 -- Token Velocity of this context (Sec. 3.2): tokens released per second, separately
  * for prefill chunks (rows of sequences with q_len > 1) and decode rows (q_len == 1), over the

@@ -15,7 +15,7 @@ TS_OK, TS_ERR_INVALID_ARG, TS_ERR_UNSUPPORTED, TS_ERR_HIP, TS_ERR_NOMEM = 0, -1,
 TS_VELOCITY_RESET, TS_VELOCITY_SYNC = 1, 2
 
 EXPORTS = ["ts_check_desc", "ts_cache_bytes", "ts_create", "ts_destroy", "ts_reserve", "ts_kv_append",
-           "ts_mixed_paged_attention", "ts_token_velocity", "ts_last_error", "ts_set_option",
+           "ts_mixed_paged_attention", "ts_mixed_paged_attention_noalloc", "ts_token_velocity", "ts_last_error", "ts_set_option",
            "ts_get_option", "ts_plan_describe", "ts_plan_export", "ts_kernel_times"]
 CALIB_EXPORTS = ["ts_calib_copy", "ts_calib_read", "ts_calib_mfma"]     # include/tokenscale_calib.h
 
@@ -92,6 +92,8 @@ def load_library():
     lib.ts_mixed_paged_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32p, i32p,
                                              ctypes.c_int, ctypes.c_float, vp]
     lib.ts_mixed_paged_attention.restype = ctypes.c_int
+    lib.ts_mixed_paged_attention_noalloc.argtypes = lib.ts_mixed_paged_attention.argtypes
+    lib.ts_mixed_paged_attention_noalloc.restype = ctypes.c_int
     lib.ts_token_velocity.argtypes = [vp, ctypes.POINTER(Velocity), ctypes.c_int]
     lib.ts_token_velocity.restype = ctypes.c_int
     lib.ts_last_error.argtypes = [vp]
@@ -244,9 +246,11 @@ class Context:
                                            _np_ptr(cl), len(ql)))
 
     def mixed_paged_attention(self, q, k_new, v_new, k_cache, v_cache, k_scale, v_scale, block_table,
-                              q_lens, ctx_lens, sm_scale: float, out, stream=None):
+                              q_lens, ctx_lens, sm_scale: float, out, stream=None, noalloc: bool = False):
+        """noalloc=True calls ts_mixed_paged_attention_noalloc (same arguments)."""
         ql, cl = _i32(q_lens), _i32(ctx_lens)
-        self._check(self._lib.ts_mixed_paged_attention(
+        fn = self._lib.ts_mixed_paged_attention_noalloc if noalloc else self._lib.ts_mixed_paged_attention
+        self._check(fn(
             self._h, self._stream(stream), _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new),
             _dev_ptr(k_cache), _dev_ptr(v_cache), _dev_ptr(k_scale), _dev_ptr(v_scale),
             _dev_ptr(block_table), _np_ptr(ql), _np_ptr(cl), len(ql), ctypes.c_float(sm_scale),

@@ -23,6 +23,39 @@ namespace {
 
 thread_local std::string g_create_error;
 
+// Scratch of the allocation-free entry point: device memory that exists from the moment the library is
+// loaded on a GPU until the process ends, one copy per GPU.  Layout (bytes):
+//   [0, 4 KiB)       queue heads of the persistent kernel, result words of the page-id check
+//   [4 KiB, 1 MiB)   device copy of the work lists
+//   [1 MiB, 8 MiB)   split-K partial results
+// In host code the array's name is only a handle: the address a kernel can use is asked for once per
+// device (static_scratch_of) and kept.
+constexpr size_t kStaticBytes = 8u << 20;
+constexpr size_t kStaticCtrBytes = 4096;
+constexpr size_t kStaticWorkOff = kStaticCtrBytes, kStaticWorkBytes = (1u << 20) - kStaticCtrBytes;
+constexpr size_t kStaticPartOff = 1u << 20, kStaticPartBytes = kStaticBytes - kStaticPartOff;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's copy of `scratch`.  `device` must be the calling thread's current device.
+hipError_t static_scratch_of(int device, unsigned char** out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = (unsigned char*)ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 constexpr int kRing = 4;
 
 struct HostSlot {
@@ -45,6 +78,8 @@ struct ts_ctx {
     char* d_work = nullptr;  size_t work_cap = 0;
     float* d_part_o = nullptr; float* d_part_ml = nullptr; int64_t part_cap = 0;
     int32_t* d_q_ctr = nullptr;      // queue heads of the persistent kernel (zero between launches)
+    unsigned char* d_static = nullptr;  // this GPU's copy of the static scratch array
+    bool static_call = false;        // the call in progress must not allocate (uses d_static)
     // pinned staging ring for the work lists
     HostSlot ring[kRing];
     int ring_pos = 0;
@@ -64,8 +99,8 @@ struct ts_ctx {
     bool validate_pages = false;       // debug: check the page ids of a batch before anything is launched
     // launch shapes of this context's GPU, asked once per context (and again when the prefetch depth changes)
     int dec_nbuf = 2;                  // KV tiles in flight per decode wave
-    int dec_slots = 0;                 // resident decode workgroups for dec_nbuf
-    int mixed_wgs = 0;                 // resident workgroups of the persistent kernel
+    int dec_slots = 0;                 // resident decode workgroups for dec_nbuf, 0 = not asked yet
+    int mixed_wgs = 0;                 // resident workgroups of the persistent kernel, 0 = not asked yet
     // optional per-kernel timing
     int timing = 0;                    // 0 = off, N = time the launches of every N-th pass
     uint64_t timing_pass = 0;
@@ -110,6 +145,12 @@ size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
 
 int ensure_work(ts_ctx* c, size_t bytes)
 {
+    if (c->static_call) {
+        if (bytes <= kStaticWorkBytes) return TS_OK;
+        return fail(c, TS_ERR_UNSUPPORTED, "batch too large for the allocation-free entry point: its work lists need " +
+                                               std::to_string(bytes) + " bytes, the static scratch holds " +
+                                               std::to_string(kStaticWorkBytes));
+    }
     if (bytes <= c->work_cap) return TS_OK;
     size_t cap = std::max<size_t>(bytes * 2, 1 << 16);
     TS_HIP(c, hipDeviceSynchronize());
@@ -122,8 +163,31 @@ int ensure_work(ts_ctx* c, size_t bytes)
     return TS_OK;
 }
 
+int64_t static_partial_slots(const ts_ctx* c)
+{
+    const size_t per = (size_t)c->desc.num_q_heads * ((size_t)c->desc.head_dim + 2) * sizeof(float);
+    return (int64_t)((kStaticPartBytes - 256) / per);
+}
+
+// Where the call in progress keeps its device-side scratch.
+char* work_base(const ts_ctx* c) { return c->static_call ? (char*)c->d_static + kStaticWorkOff : c->d_work; }
+int32_t* q_ctr_of(const ts_ctx* c) { return c->static_call ? (int32_t*)c->d_static : c->d_q_ctr; }
+float* part_o_of(const ts_ctx* c) { return c->static_call ? (float*)(c->d_static + kStaticPartOff) : c->d_part_o; }
+float* part_ml_of(const ts_ctx* c)
+{
+    if (!c->static_call) return c->d_part_ml;
+    const size_t o_bytes = (size_t)static_partial_slots(c) * c->desc.num_q_heads * c->desc.head_dim * sizeof(float);
+    return (float*)(c->d_static + kStaticPartOff + ((o_bytes + 255) & ~(size_t)255));
+}
+
 int ensure_partials(ts_ctx* c, int64_t slots)
 {
+    if (c->static_call) {
+        if (slots <= static_partial_slots(c)) return TS_OK;
+        return fail(c, TS_ERR_UNSUPPORTED, "batch too large for the allocation-free entry point: " + std::to_string(slots) +
+                                               " split-K partial results, the static scratch holds " +
+                                               std::to_string(static_partial_slots(c)));
+    }
     if (slots <= c->part_cap) return TS_OK;
     int64_t cap = std::max<int64_t>(slots * 2, 1024);
     TS_HIP(c, hipDeviceSynchronize());
@@ -140,18 +204,20 @@ int ensure_partials(ts_ctx* c, int64_t slots)
 }
 
 // Next pinned staging slot with at least `bytes`, free of any copy still in flight.
-int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out)
+int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out, bool exact = false)
 {
     HostSlot& s = c->ring[c->ring_pos];
     c->ring_pos = (c->ring_pos + 1) % kRing;
     if (s.pending) { TS_HIP(c, hipEventSynchronize(s.ev)); s.pending = false; }
     // (no system-scope fence: the event only orders GPU work against GPU work and against the host
     // overwriting a buffer the GPU has read)
+    if (c->static_call && (!s.ev || bytes > s.cap))         // (cannot happen: ts_create sized the ring for kStaticWorkBytes)
+        return fail(c, TS_ERR_UNSUPPORTED, "staging ring too small for the allocation-free entry point");
     if (!s.ev) TS_HIP(c, hipEventCreateWithFlags(&s.ev, hipEventDisableTiming | hipEventDisableSystemFence));
     if (bytes > s.cap) {
         if (s.ptr) TS_HIP(c, hipHostFree(s.ptr));
         s.ptr = s.dev_ptr = nullptr; s.cap = 0;
-        size_t cap = std::max<size_t>(bytes * 2, 1 << 16);
+        size_t cap = exact ? bytes : std::max<size_t>(bytes * 2, 1 << 16);
         // (coherent: the GPU reads it uncached over PCIe, so a slot that is filled again is never seen stale)
         if (hipHostMalloc(&s.ptr, cap, hipHostMallocCoherent) != hipSuccess)
             return fail(c, TS_ERR_NOMEM, "pinned staging allocation failed");
@@ -170,8 +236,12 @@ int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out)
 // Brings the work lists from the pinned staging buffer into device memory.  A kernel instead of a copy
 // command: between two kernels of a stream the GPU loses no time, around a copy command it idled
 // 10 + 5 us per call (a twentieth of a decode step).
-__global__ __launch_bounds__(256) void upload_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16)
+// zero / n_zero: words put back to zero by the same launch (the queue heads inside the static scratch, which
+// any earlier call on this GPU may have left in any state).
+__global__ __launch_bounds__(256) void upload_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16,
+                                                     int32_t* zero, int n_zero)
 {
+    if (blockIdx.x == 0 && (int)threadIdx.x < n_zero) zero[threadIdx.x] = 0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
@@ -241,12 +311,12 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w, UploadJob* defer
     const int blocks = (int)std::min<int64_t>(256, (n16 + 255) / 256);
     c->cur_slot = slot;                                    // its event is recorded by mark_work_done
     if (defer) {
-        *defer = UploadJob{(const uint4*)slot->dev_ptr, (uint4*)c->d_work, n16, blocks, (const char*)slot->dev_ptr};
+        *defer = UploadJob{(const uint4*)slot->dev_ptr, (uint4*)work_base(c), n16, blocks, (const char*)slot->dev_ptr};
         return TS_OK;
     }
     if (n16 > 0) {
-        hipLaunchKernelGGL(upload_kernel, dim3(blocks), dim3(256), 0, st, (const uint4*)slot->dev_ptr, (uint4*)c->d_work,
-                           n16);
+        hipLaunchKernelGGL(upload_kernel, dim3(blocks), dim3(256), 0, st, (const uint4*)slot->dev_ptr, (uint4*)work_base(c),
+                           n16, c->static_call ? q_ctr_of(c) : nullptr, c->static_call ? 128 : 0);
         TS_HIP(c, hipGetLastError());
     }
     return TS_OK;
@@ -257,9 +327,9 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w, UploadJob* defer
 int check_pages(ts_ctx* c, hipStream_t st, const WorkLayout& w, const int32_t* block_table, int num_seqs)
 {
     if (!c->validate_pages || num_seqs <= 0) return TS_OK;
-    int32_t* res = c->d_q_ctr + 120;                       // (the queue heads use the first 65 words)
+    int32_t* res = q_ctr_of(c) + 120;                      // (the queue heads use the first 65 words)
     TS_HIP(c, hipMemsetAsync(res, 0, 4 * sizeof(int32_t), st));
-    hipLaunchKernelGGL(check_pages_kernel, dim3((unsigned)num_seqs), dim3(256), 0, st, (const SeqMeta*)(c->d_work + w.seqs),
+    hipLaunchKernelGGL(check_pages_kernel, dim3((unsigned)num_seqs), dim3(256), 0, st, (const SeqMeta*)(work_base(c) + w.seqs),
                        block_table, c->desc.max_pages_per_seq, (int64_t)c->desc.num_pages, res);
     TS_HIP(c, hipGetLastError());
     int32_t host[4] = {0, 0, 0, 0};
@@ -401,6 +471,16 @@ extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
         c->dec_slots = decode_resident_workgroups(c->desc.kv_dtype, c->dec_nbuf);
         c->mixed_wgs = mixed_resident_workgroups(c->desc.kv_dtype);
         if (c->mixed_wgs <= 0) rc = fail(c, TS_ERR_HIP, "occupancy query of the persistent kernel failed");
+    }
+    if (rc == TS_OK) {
+        // the allocation-free entry point: this GPU's static scratch, and a staging ring that holds the
+        // largest work lists that scratch takes
+        const hipError_t se = static_scratch_of(device, &c->d_static);
+        if (se != hipSuccess) rc = hip_fail(c, se, "hipGetSymbolAddress(scratch)");
+        for (int i = 0; rc == TS_OK && i < kRing; ++i) {
+            HostSlot* s = nullptr;
+            rc = acquire_slot(c, kStaticWorkBytes, &s, true);
+        }
     }
     if (rc != TS_OK) { g_create_error = c->err; ts_destroy(c); return rc; }
     *out = c;
@@ -561,21 +641,25 @@ extern "C" int ts_kv_append(ts_ctx* c, void* stream, const void* k_new, const vo
     return mark_work_done(c, st);
 }
 
-extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, const void* k_new,
-                                        const void* v_new, void* k_cache, void* v_cache,
-                                        const float* k_scale, const float* v_scale,
-                                        const int32_t* block_table, const int32_t* q_lens,
-                                        const int32_t* ctx_lens, int num_seqs, float sm_scale, void* out)
+namespace {
+
+// The pass behind both entry points.  With c->static_call set, all device scratch lies inside the static
+// array and nothing on this path allocates (no growth, no new events, no per-kernel timing).
+int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+               const float* k_scale, const float* v_scale, const int32_t* block_table, const int32_t* q_lens,
+               const int32_t* ctx_lens, int num_seqs, float sm_scale, void* out)
 {
-    if (!c) return TS_ERR_INVALID_ARG;
     c->err.clear();
     int rc = check_common(c, k_cache, v_cache, k_scale, v_scale, block_table, q_lens, ctx_lens, num_seqs);
     if (rc != TS_OK) return rc;
     if ((k_new == nullptr) != (v_new == nullptr))
         return fail(c, TS_ERR_INVALID_ARG, "k_new and v_new must both be given or both be NULL");
     if (!(sm_scale == sm_scale)) return fail(c, TS_ERR_INVALID_ARG, "sm_scale is NaN");
+    if (c->static_call && c->validate_pages)
+        return fail(c, TS_ERR_UNSUPPORTED, "the validate_block_table option waits for the GPU and copies to the host: "
+                                           "not available in the allocation-free entry point");
     DeviceGuard guard(c->device);
-    c->timing_now = c->timing > 0 && (c->timing_pass++ % (uint64_t)c->timing) == 0;
+    c->timing_now = !c->static_call && c->timing > 0 && (c->timing_pass++ % (uint64_t)c->timing) == 0;
     if (c->dec_slots > 0) c->opt.wg_slots = c->dec_slots;
     build_plan(c->desc, q_lens, ctx_lens, num_seqs, c->opt, &c->plan);
     const Plan& p = c->plan;
@@ -585,8 +669,9 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     if (rc != TS_OK) return rc;
     const WorkLayout w = layout_of(p);
     hipStream_t st = (hipStream_t)stream;
-    // new tokens to append and no page check: the upload rides along in the first append launch
-    const bool ride = k_new && !c->validate_pages;
+    // new tokens to append and no page check: the upload rides along in the first append launch (not in the
+    // allocation-free call, whose upload launch also puts the shared queue heads back to zero)
+    const bool ride = k_new && !c->validate_pages && !c->static_call;
     UploadJob job;
     rc = upload_plan(c, st, w, ride ? &job : nullptr);
     if (rc != TS_OK) return rc;
@@ -595,15 +680,16 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     if (rc != TS_OK) return rc;
 
     const Geometry geo = geometry_of(c->desc);
+    const char* wb = work_base(c);
     if (k_new) {
         AppendArgs ap{};
         ap.geo = geo;
         ap.k_new = k_new; ap.v_new = v_new; ap.k_cache = k_cache; ap.v_cache = v_cache;
         ap.k_scale = k_scale; ap.v_scale = v_scale; ap.block_table = block_table;
-        ap.seqs = (const SeqMeta*)(c->d_work + w.seqs);
+        ap.seqs = (const SeqMeta*)(wb + w.seqs);
         ap.num_seqs = num_seqs; ap.total_tokens = (int32_t)p.info.total_tokens;
-        ap.apt = (const AppTile*)(c->d_work + w.apt); ap.n_apt = (int32_t)p.apt.size();
-        ap.apr = (const AppRow*)(c->d_work + w.apr); ap.n_apr = (int32_t)p.apr.size();
+        ap.apt = (const AppTile*)(wb + w.apt); ap.n_apt = (int32_t)p.apt.size();
+        ap.apr = (const AppRow*)(wb + w.apr); ap.n_apr = (int32_t)p.apr.size();
         if (ride) {
             ap.apr_host = (const AppRow*)(job.host_lists + w.apr);
             ap.apt_host = (const AppTile*)(job.host_lists + w.apt);
@@ -618,16 +704,16 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
     a.block_table = block_table;
     a.sm_scale = sm_scale > 0.0f ? sm_scale : 1.0f / sqrtf((float)c->desc.head_dim);
     a.out = out;
-    a.dec = (const DecItem*)(c->d_work + w.dec);   a.n_dec = (int32_t)p.dec.size();
-    a.cmb = (const CmbItem*)(c->d_work + w.cmb);   a.n_cmb = (int32_t)p.cmb.size();
-    a.pf = (const PfItem*)(c->d_work + w.pf);      a.n_pf = (int32_t)p.pf.size();
-    a.pfmap = (const PfSlot*)(c->d_work + w.pfmap); a.n_pfmap = (int32_t)p.pfmap.size();
-    a.rows = (const RowItem*)(c->d_work + w.rows); a.n_rows = (int32_t)p.rows.size();
-    a.queue = (const QItem*)(c->d_work + w.queue); a.q_off = (const int32_t*)(c->d_work + w.q_off);
+    a.dec = (const DecItem*)(wb + w.dec);   a.n_dec = (int32_t)p.dec.size();
+    a.cmb = (const CmbItem*)(wb + w.cmb);   a.n_cmb = (int32_t)p.cmb.size();
+    a.pf = (const PfItem*)(wb + w.pf);      a.n_pf = (int32_t)p.pf.size();
+    a.pfmap = (const PfSlot*)(wb + w.pfmap); a.n_pfmap = (int32_t)p.pfmap.size();
+    a.rows = (const RowItem*)(wb + w.rows); a.n_rows = (int32_t)p.rows.size();
+    a.queue = (const QItem*)(wb + w.queue); a.q_off = (const int32_t*)(wb + w.q_off);
     a.n_queue = (int32_t)p.queue.size(); a.n_xcd = p.q_off.empty() ? 0 : (int32_t)p.q_off.size() - 1;
-    a.q_ctr = c->d_q_ctr;
+    a.q_ctr = q_ctr_of(c);
     a.dec_nbuf = c->dec_nbuf; a.mixed_wgs = c->mixed_wgs;
-    a.part_o = c->d_part_o; a.part_ml = c->d_part_ml;
+    a.part_o = part_o_of(c); a.part_ml = part_ml_of(c);
 
     hipError_t e;
     // decode first: the serving loop's TPOT depends on these rows (Sec. 4.5.2)
@@ -658,6 +744,34 @@ extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, 
         c->passes += 1;
     }
     return TS_OK;
+}
+
+}  // namespace
+
+extern "C" int ts_mixed_paged_attention(ts_ctx* c, void* stream, const void* q, const void* k_new,
+                                        const void* v_new, void* k_cache, void* v_cache,
+                                        const float* k_scale, const float* v_scale,
+                                        const int32_t* block_table, const int32_t* q_lens,
+                                        const int32_t* ctx_lens, int num_seqs, float sm_scale, void* out)
+{
+    if (!c) return TS_ERR_INVALID_ARG;
+    c->static_call = false;
+    return mixed_pass(c, stream, q, k_new, v_new, k_cache, v_cache, k_scale, v_scale, block_table, q_lens, ctx_lens,
+                      num_seqs, sm_scale, out);
+}
+
+extern "C" int ts_mixed_paged_attention_noalloc(ts_ctx* c, void* stream, const void* q, const void* k_new,
+                                                const void* v_new, void* k_cache, void* v_cache,
+                                                const float* k_scale, const float* v_scale,
+                                                const int32_t* block_table, const int32_t* q_lens,
+                                                const int32_t* ctx_lens, int num_seqs, float sm_scale, void* out)
+{
+    if (!c) return TS_ERR_INVALID_ARG;
+    c->static_call = true;
+    const int rc = mixed_pass(c, stream, q, k_new, v_new, k_cache, v_cache, k_scale, v_scale, block_table, q_lens,
+                              ctx_lens, num_seqs, sm_scale, out);
+    c->static_call = false;
+    return rc;
 }
 
 extern "C" int ts_token_velocity(ts_ctx* c, ts_velocity* out, int flags)
