@@ -2,8 +2,10 @@
 """Benchmark of the mixed paged-attention pass on one MI355X.
 
 A step is one whole pass (KV append, decode split-K, combine, prefill tiles) over one synthetic
-batch that is already resident in HBM.  The default workload is the decode-only Llama-3-8B-like
-layer (32/8/128 bf16, 256 sequences, context U[512,4096]); `--workload` selects the others.
+batch that is already resident in HBM.  The default workload is the largest mixed batch (70B-like
+layer, 64/8/128, e4m3 KV cache: 512 decode rows next to 16 prefill chunks of 4096 tokens, 66 048 query tokens);
+the burst and the decode-only configurations are measured in the same run and reported under "extra";
+`--workload` selects another main workload.
 Prints one JSON line with tokens/s, the roofline of the dominant kernel (duration from HIP
 events recorded on the launch stream around every launch of the timed region) and the fp64 CPU
 oracle timed on a bounded sample of the same batch.
@@ -65,15 +67,10 @@ def algorithmic_work(batch):
                 prefill_bytes=pf_bytes, append_bytes=app_bytes)
 
 
-def cpu_baseline(batch, out_gpu, max_seqs: int, row_stride: int):
-    """Times the oracle (as it stands) on a bounded sample and checks the GPU rows against it."""
-    import numpy as np
+def _oracle_rows(sub, row_stride: int):
+    """Oracle on a sub-batch: KV append of its new tokens and attention for every row_stride-th row.
+    Returns (seconds, reference rows [T,Hq,D] with NaN where not computed)."""
     import oracle
-    import workloads as W
-    S = batch.num_seqs
-    step = max(1, S // max_seqs)
-    sample = list(range(0, S, step))[:max_seqs]
-    sub = W.to_cpu(W.select_sequences(batch, sample))
     sh = sub.shape
     args = (sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.q_dtype, sh.kv_dtype)
     kc = oracle.new_cache(sub.num_pages, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
@@ -90,16 +87,41 @@ def cpu_baseline(batch, out_gpu, max_seqs: int, row_stride: int):
     oracle.kv_append(*args, kn, vn, kc, vc, ks, vs, sub.block_table, sub.q_lens, sub.ctx_lens, sub.num_pages)
     ref = oracle.mixed_paged_attention(*args, q_raw, kc, vc, ks, vs, sub.block_table, sub.q_lens,
                                        sub.ctx_lens, sub.sm_scale, sub.num_pages, row_stride=row_stride)
-    dt = time.perf_counter() - t0
-    done = ~np.isnan(ref[:, 0, 0])
-    n_rows = int(done.sum())
-    q_off = np.concatenate([[0], np.cumsum(batch.q_lens)])
-    got = np.concatenate([out_gpu[q_off[s]:q_off[s + 1]] for s in sample])
-    err = float(np.max(np.abs(got[done] - ref[done]))) if n_rows else 0.0
-    return dict(value=n_rows / dt, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
-                sample=f"{n_rows} query rows ({len(sample)} of {S} sequences, every {row_stride} row(s)), "
-                       f"{dt:.1f} s of fp64 CPU work incl. their KV append",
-                max_abs_err_vs_gpu=err)
+    return time.perf_counter() - t0, ref
+
+
+def cpu_baseline(batch, out_gpu, max_decode: int, max_chunks: int, chunk_stride: int):
+    """Times the oracle (as it stands) on a bounded sample of the batch -- every row of up to max_decode
+    decode sequences, and every chunk_stride-th row of up to max_chunks prefill chunks -- and checks the GPU
+    rows against it."""
+    import numpy as np
+    import oracle
+    import workloads as W
+    ql = batch.q_lens
+    q_off = np.concatenate([[0], np.cumsum(ql)])
+
+    def pick(idx, n):
+        idx = list(idx)
+        return idx[:: max(1, len(idx) // n)][:n] if n > 0 else []
+
+    legs = [(pick(np.nonzero(ql == 1)[0], max_decode), 1), (pick(np.nonzero(ql > 1)[0], max_chunks), chunk_stride)]
+    n_rows, dt, err, parts = 0, 0.0, 0.0, []
+    for sample, stride in legs:
+        if not sample:
+            continue
+        sub = W.to_cpu(W.select_sequences(batch, sample))
+        t, ref = _oracle_rows(sub, stride)
+        done = ~np.isnan(ref[:, 0, 0])
+        got = np.concatenate([out_gpu[q_off[s]:q_off[s + 1]] for s in sample])
+        if done.any():
+            err = max(err, float(np.max(np.abs(got[done] - ref[done]))))
+        n_rows += int(done.sum())
+        dt += t
+        kind = "decode sequences, every row" if stride == 1 and ql[sample[0]] == 1 else f"prefill chunks, every {stride}. row"
+        parts.append(f"{int(done.sum())} rows of {len(sample)} {kind}")
+    return dict(value=n_rows / dt if dt > 0 else 0.0, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"{n_rows} query rows ({'; '.join(parts)}) of {batch.name}: {dt:.1f} s of fp64 CPU work "
+                       f"incl. their KV append", max_abs_err_vs_gpu=err)
 
 
 def recorded_traffic(kernel: str, workload: str):
@@ -164,37 +186,70 @@ def calibrate(nbytes: int = 2 << 30):
     return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences in the oracle sample (0 = auto)")
-    ap.add_argument("--calibrate", action="store_true", help="also time the plain copy/read kernels")
-    ap.add_argument("--split-pages", type=int, default=0)
-    ap.add_argument("--prefetch-tiles", type=int, default=0)
-    ap.add_argument("--xcd-count", type=int, default=0)
-    ap.add_argument("--no-persistent", action="store_true",
-                    help="mixed batches: decode kernel then prefill kernel instead of the persistent launch")
-    ap.add_argument("--time-every", type=int, default=4,
-                    help="record HIP events around the kernels of every N-th step of the timed region")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
+CPU_SAMPLE = {   # workload -> (decode sequences, prefill chunks, chunk row stride) of the oracle's bounded sample
+    "cfg1": (8, 8, 1), "cfg2": (256, 0, 1), "cfg3": (0, 8, 8), "cfg4": (64, 4, 16), "cfg5": (48, 16, 64),
+}
 
+
+def roofline_of(work, ktimes, batch_name):
+    """Roofline block of the kernel that takes the most time, from the algorithmic work of the batch and
+    the kernel's mean duration (HIP events on the launch stream)."""
+    tot = {k: v[0] * v[1] for k, v in ktimes.items()}
+    dominant = max(("decode", "prefill", "rows", "mixed"), key=lambda k: tot.get(k, 0.0))
+    n, ms = ktimes[dominant]
+    sec = ms * 1e-3
+    all_bytes = work["decode_bytes"] + work["prefill_bytes"]
+    common = dict(kernel=dominant + "_kernel", kernel_ms=ms, kernel_launches_timed=n)
+    if dominant == "decode":
+        ach = work["decode_bytes"] / sec / 1e9
+        return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
+                    traffic=recorded_traffic("decode_kernel", batch_name), algorithmic_bytes=work["decode_bytes"], **common)
+    if dominant == "prefill":
+        ach = work["prefill_flops"] / sec / 1e12
+        return dict(bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=ach / PEAK_BF16_TFLOPS,
+                    traffic=recorded_traffic("prefill_kernel", batch_name), algorithmic_flops=work["prefill_flops"],
+                    algorithmic_bytes=work["prefill_bytes"], **common)
+    if dominant == "mixed":
+        # the persistent kernel runs both kinds at once: its floor is the higher of the two, and it is priced
+        # against the peak of that bound (frac = floor time / kernel time)
+        t_hbm = all_bytes / (PEAK_HBM_GBS * 1e9)
+        t_mfma = work["prefill_flops"] / (PEAK_BF16_TFLOPS * 1e12)
+        extra = dict(algorithmic_flops=work["prefill_flops"], algorithmic_bytes=all_bytes,
+                     floor_ms=max(t_hbm, t_mfma) * 1e3, floor_hbm_ms=t_hbm * 1e3, floor_mfma_ms=t_mfma * 1e3,
+                     traffic=recorded_traffic("mixed_kernel", batch_name), **common)
+        if t_mfma >= t_hbm:
+            ach = work["prefill_flops"] / sec / 1e12
+            return dict(bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=ach / PEAK_BF16_TFLOPS, **extra)
+        ach = all_bytes / sec / 1e9
+        return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS, **extra)
+    ach = all_bytes / sec / 1e9
+    return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS, traffic=None,
+                algorithmic_bytes=all_bytes, **common)
+
+
+def per_class_of(work, ktimes):
+    """The two classes of a mixed batch priced separately, from a run with one launch per class."""
+    out = {}
+    if ktimes.get("decode", (0, 0))[0]:
+        ach = work["decode_bytes"] / (ktimes["decode"][1] * 1e-3) / 1e9
+        out["decode"] = dict(kernel="decode_kernel", bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s",
+                             frac=ach / PEAK_HBM_GBS, kernel_ms=ktimes["decode"][1], algorithmic_bytes=work["decode_bytes"])
+    if ktimes.get("prefill", (0, 0))[0]:
+        ach = work["prefill_flops"] / (ktimes["prefill"][1] * 1e-3) / 1e12
+        out["prefill"] = dict(kernel="prefill_kernel", bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                              frac=ach / PEAK_BF16_TFLOPS, kernel_ms=ktimes["prefill"][1],
+                              algorithmic_flops=work["prefill_flops"])
+    return out
+
+
+def run_workload(name, args, with_cpu: bool):
+    """All legs of one workload: the timed region (whole pass, kernels bracketed by HIP events), for a mixed
+    batch a second region with one launch per class, and the oracle on a bounded sample."""
     import numpy as np
     import torch
     import paper_2512_03416_amd as ts
-    if not torch.cuda.is_available():
-        raise SystemExit("bench.py needs a GPU")
-    ts.load_library()
-    torch.cuda.set_device(0)
-
     t_setup = time.perf_counter()
-    batch = build_workload(args.workload, "cuda")
+    batch = build_workload(name, "cuda")
     sh = batch.shape
     desc = ts.Desc.make(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.q_dtype, sh.kv_dtype,
                         batch.num_pages, batch.max_pages_per_seq)
@@ -227,82 +282,43 @@ def main():
         ctx.mixed_paged_attention(batch.q, batch.k_new, batch.v_new, kc, vc, batch.k_scale, batch.v_scale, bt,
                                   batch.q_lens, batch.ctx_lens, batch.sm_scale, out)
 
+    def region(steps, timing):
+        """`steps` passes bracketed by synchronisations; returns (seconds, kernel times)."""
+        ctx.set_option("kernel_timing", timing)
+        ctx.kernel_times(reset=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        kt = ctx.kernel_times()
+        ctx.set_option("kernel_timing", 0)
+        return dt, kt
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-
     # reference loop without per-kernel events
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_plain = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    # timed region: HIP events on the launch stream around every kernel launch
-    ctx.set_option("kernel_timing", args.time_every)
-    ctx.kernel_times(reset=True)
+    ms_plain = region(args.steps, 0)[0] * 1e3 / args.steps
+    # timed region: HIP events on the launch stream around the kernel launches of every N-th step
     ctx.token_velocity(reset=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    elapsed, ktimes = region(args.steps, args.time_every)
     vel = ctx.token_velocity(sync=True)
-    ktimes = ctx.kernel_times()
-    ctx.set_option("kernel_timing", 0)
     ms_step = elapsed * 1e3 / args.steps
     T = batch.total_q
-    value = T * args.steps / elapsed
-    log(f"[bench] {ms_step:.4f} ms/step with kernel events on every {args.time_every}. step, {ms_plain:.4f} "
-        f"ms/step without; kernels: " +
+    log(f"[bench] {batch.name}: {ms_step:.4f} ms/step with kernel events on every {args.time_every}. step, "
+        f"{ms_plain:.4f} ms/step without; kernels: " +
         ", ".join(f"{k} {v[1] * 1e3:.1f} us x{v[0]}" for k, v in ktimes.items() if v[0]))
     log(f"[bench] token velocity counters: prefill {vel.prefill_tok_per_s:.0f} tok/s, decode "
         f"{vel.decode_tok_per_s:.0f} tok/s over {vel.window_s:.3f} s ({vel.passes} passes)")
-
     work = algorithmic_work(batch)
-    tot = {k: v[0] * v[1] for k, v in ktimes.items()}
-    dominant = max(("decode", "prefill", "rows", "mixed"), key=lambda k: tot.get(k, 0.0))
-    dom_ms = ktimes[dominant][1]
-    if dominant == "decode":
-        ach = work["decode_bytes"] / (dom_ms * 1e-3) / 1e9
-        roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
-                    traffic=recorded_traffic("decode_kernel", batch.name), kernel="decode_kernel",
-                    kernel_ms=dom_ms, kernel_launches_timed=ktimes[dominant][0],
-                    algorithmic_bytes=work["decode_bytes"])
-    elif dominant == "prefill":
-        ach = work["prefill_flops"] / (dom_ms * 1e-3) / 1e12
-        roof = dict(bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=ach / PEAK_BF16_TFLOPS, traffic=None, kernel="prefill_kernel", kernel_ms=dom_ms,
-                    algorithmic_flops=work["prefill_flops"])
-    elif dominant == "mixed":
-        # the persistent kernel runs both kinds: price it against whichever floor is higher
-        t_hbm = (work["decode_bytes"] + work["prefill_bytes"]) / (PEAK_HBM_GBS * 1e9)
-        t_mfma = work["prefill_flops"] / (PEAK_BF16_TFLOPS * 1e12)
-        if t_mfma >= t_hbm:
-            ach = work["prefill_flops"] / (dom_ms * 1e-3) / 1e12
-            roof = dict(bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=ach / PEAK_BF16_TFLOPS, traffic=None, kernel="mixed_kernel", kernel_ms=dom_ms,
-                        algorithmic_flops=work["prefill_flops"],
-                        algorithmic_bytes=work["decode_bytes"] + work["prefill_bytes"])
-        else:
-            ach = (work["decode_bytes"] + work["prefill_bytes"]) / (dom_ms * 1e-3) / 1e9
-            roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
-                        traffic=None, kernel="mixed_kernel", kernel_ms=dom_ms,
-                        algorithmic_flops=work["prefill_flops"],
-                        algorithmic_bytes=work["decode_bytes"] + work["prefill_bytes"])
-    else:
-        bytes_all = work["decode_bytes"] + work["prefill_bytes"]
-        ach = bytes_all / (dom_ms * 1e-3) / 1e9
-        roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
-                    traffic=None, kernel="rows_kernel", kernel_ms=dom_ms, algorithmic_bytes=bytes_all)
-
-    result = {
-        "metric": "mixed-batch tokens/s (decode+prefill) on 1 MI355X",
-        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if sh.q_dtype == "bf16" else "f32", "data": "synthetic",
+    roof = roofline_of(work, ktimes, batch.name)
+    res = {
+        "value": T * args.steps / elapsed, "ms_per_step": ms_step,
+        "dtype": ("bf16" if sh.q_dtype == "bf16" else "f32") + (" (e4m3 KV cache)" if sh.kv_dtype == "fp8" else ""),
         "config": {"workload": batch.name, "num_seqs": batch.num_seqs, "query_tokens": T,
+                   "decode_rows": int((batch.q_lens == 1).sum()), "prefill_tokens": int(batch.q_lens[batch.q_lens > 1].sum()),
                    "heads": f"{sh.num_q_heads}q/{sh.num_kv_heads}kv/d{sh.head_dim}", "kv_dtype": sh.kv_dtype,
                    "page_size": 16, "ctx_tokens": int(batch.ctx_lens.sum()), "pool_pages": batch.num_pages,
                    "decode_split_pages": int(info.split_pages)},
@@ -310,17 +326,83 @@ def main():
         "ms_per_step_without_kernel_events": ms_plain,
         "kernels_us": {k: round(v[1] * 1e3, 2) for k, v in ktimes.items() if v[0]},
     }
+    if roof["kernel"] == "mixed_kernel" and not args.no_persistent:
+        # the same batch with one launch per class: what each class reaches on its own
+        ctx.set_option("mixed_persistent", 0)
+        for _ in range(max(2, args.warmup // 3)):
+            step()
+        n_sep = max(4, args.steps // 2)
+        dt_sep, kt_sep = region(n_sep, max(1, args.time_every // 2))
+        ctx.set_option("mixed_persistent", 1)
+        roof["per_class"] = per_class_of(work, kt_sep)
+        roof["ms_per_step_separate_launches"] = dt_sep * 1e3 / n_sep
+        log(f"[bench] {batch.name}, one launch per class: {dt_sep * 1e3 / n_sep:.4f} ms/step; kernels: " +
+            ", ".join(f"{k} {v[1] * 1e3:.1f} us x{v[0]}" for k, v in kt_sep.items() if v[0]))
+        step()                                               # `out` as the persistent launch writes it
+        torch.cuda.synchronize()
+    if with_cpu:
+        out_host = out.double().cpu().numpy()
+        n_dec, n_chunks, stride = CPU_SAMPLE[name]
+        if args.cpu_seqs:
+            n_dec = min(n_dec, args.cpu_seqs)
+        res["cpu_baseline"] = cpu_baseline(batch, out_host, n_dec, n_chunks, stride)
+        log(f"[bench] oracle: {res['cpu_baseline']}")
+    ctx.close()
+    del kc, vc, out, batch
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
+                    help="the workload the line's value is measured on (default: the largest mixed batch)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the extra workloads reported next to the main one")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=0, help="cap on the decode sequences in the oracle sample")
+    ap.add_argument("--calibrate", action="store_true", help="also time the plain copy/read kernels")
+    ap.add_argument("--split-pages", type=int, default=0)
+    ap.add_argument("--prefetch-tiles", type=int, default=0)
+    ap.add_argument("--xcd-count", type=int, default=0)
+    ap.add_argument("--no-persistent", action="store_true",
+                    help="mixed batches: decode kernel then prefill kernel instead of the persistent launch")
+    ap.add_argument("--time-every", type=int, default=4,
+                    help="record HIP events around the kernels of every N-th step of the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_03416_amd as ts
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    ts.load_library()
+    torch.cuda.set_device(0)
+
+    main_res = run_workload(args.workload, args, with_cpu=not args.no_cpu_baseline)
+    result = {
+        "metric": "mixed-batch tokens/s (decode+prefill) on 1 MI355X",
+        "value": main_res.pop("value"), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": main_res.pop("dtype"), "data": "synthetic",
+    }
+    result.update(main_res)
+    if args.workload == "cfg5" and not args.no_extra:
+        # the burst configuration and the decode-only configuration, same procedure, for context
+        result["extra"] = {}
+        for w in ("cfg4", "cfg2"):
+            r = run_workload(w, args, with_cpu=False)
+            result["extra"][r["config"]["workload"]] = dict(
+                tokens_per_s=r["value"], ms_per_step=r["ms_per_step"], query_tokens=r["config"]["query_tokens"],
+                kernels_us=r["kernels_us"], roofline=r["roofline"])
     if args.calibrate:
         result["calibration"] = calibrate()
         log(f"[bench] calibration: {result['calibration']}")
-    if not args.no_cpu_baseline:
-        out_host = out.double().cpu().numpy()
-        n = args.cpu_seqs or {"cfg2": 256, "cfg4": 132, "cfg5": 64, "cfg3": 8, "cfg1": 8}[args.workload]
-        stride = {"cfg4": 16, "cfg5": 256, "cfg3": 8}.get(args.workload, 1)
-        result["cpu_baseline"] = cpu_baseline(batch, out_host, n, stride)
-        log(f"[bench] oracle: {result['cpu_baseline']}")
     print(json.dumps(result), flush=True)
-    ctx.close()
 
 
 if __name__ == "__main__":
