@@ -261,7 +261,7 @@ def run_workload(name, args, with_cpu: bool):
     if args.xcd_count:
         ctx.set_option("xcd_count", args.xcd_count)
     if args.no_persistent:
-        ctx.set_option("mixed_persistent", 0)
+        ctx.set_option("mixed_mode", 0)
     nbytes = ts.cache_bytes(desc)
     kc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
     vc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
@@ -328,12 +328,12 @@ def run_workload(name, args, with_cpu: bool):
     }
     if roof["kernel"] == "mixed_kernel" and not args.no_persistent:
         # the same batch with one launch per class: what each class reaches on its own
-        ctx.set_option("mixed_persistent", 0)
+        ctx.set_option("mixed_mode", 0)
         for _ in range(max(2, args.warmup // 3)):
             step()
         n_sep = max(4, args.steps // 2)
         dt_sep, kt_sep = region(n_sep, max(1, args.time_every // 2))
-        ctx.set_option("mixed_persistent", 1)
+        ctx.set_option("mixed_mode", 2)
         roof["per_class"] = per_class_of(work, kt_sep)
         roof["ms_per_step_separate_launches"] = dt_sep * 1e3 / n_sep
         log(f"[bench] {batch.name}, one launch per class: {dt_sep * 1e3 / n_sep:.4f} ms/step; kernels: " +

@@ -59,6 +59,8 @@ typedef struct ts_ctx ts_ctx;
 
 typedef enum { TS_F32 = 0, TS_BF16 = 1, TS_FP8_E4M3 = 2 } ts_dtype;
 
+enum { TS_MIXED_SEPARATE = 0, TS_MIXED_ONE_KERNEL = 1, TS_MIXED_CORESIDENT = 2 };   /* option "mixed_mode" */
+
 enum {
     TS_OK = 0,
     TS_ERR_INVALID_ARG = -1,  /* null pointer, bad length, bad descriptor                  */
@@ -182,8 +184,14 @@ const char *ts_last_error(const ts_ctx *ctx);
  *   "decode_split_pages"  longest page range of one decode item (0 = choose from the batch)
  *   "prefill_path"        0 = MFMA tiles where supported, 1 = force the generic row kernel
  *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave
- *   "mixed_persistent"    1 (default) = decode items and prefill tiles of a mixed batch share one
- *                         persistent launch; 0 = decode kernel, then prefill kernel
+ *   "mixed_mode"          how a batch that holds decode rows and prefill chunks is launched:
+ *                         2 (default, TS_MIXED_CORESIDENT) = the prefill tiles run in resident workgroups,
+ *                         one per CU, that leave room on every CU for one decode workgroup, and the decode
+ *                         items run next to them as a grid of their own on an internal side stream (forked
+ *                         from and joined to the caller's stream with events); batches too small to gain
+ *                         from it take mode 1 by themselves;
+ *                         1 (TS_MIXED_ONE_KERNEL) = decode items and prefill tiles share the workgroups of one
+ *                         persistent launch;  0 (TS_MIXED_SEPARATE) = decode kernel, then prefill kernel
  *   "xcd_count"           accelerator dies the prefill launch order is laid out for (default 8)
  *   "kernel_timing"       N > 0 = record HIP events around the launches of every N-th call
  *                         (see ts_kernel_times), 0 = off
@@ -226,6 +234,8 @@ typedef struct {
     int32_t tile_tokens;        /* query tokens per prefill tile                               */
     int64_t partial_slots;      /* split-K partial results held in scratch                     */
     int64_t ctx_pages;          /* sum over sequences of ceil(ctx_len/16)                      */
+    int32_t mixed_mode;         /* TS_MIXED_* the batch is launched with (SEPARATE if one kind only) */
+    int32_t reserved;
 } ts_plan_info;
 
 int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
@@ -238,16 +248,18 @@ int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int3
  *   TS_LIST_PREFILL (seq, row0, q_len, prefix, tok_begin, tok_count, ctx_len, 0)
  *   TS_LIST_PFMAP   (prefill tile or -1, kv_head)       launch order, workgroup i -> die i % 8
  *   TS_LIST_ROWS    (row, seq, n_keys, 0)
- *   TS_LIST_QUEUE   (kind 0 decode / 1 prefill, item, kv_head, 0)   per-die queues, concatenated
+ *   TS_LIST_QUEUE   (kind 0 decode / 1 prefill, item, kv_head, 0)   per-die queues, concatenated (mode 1: both
+ *                   kinds interleaved; mode 2: the tiles only)
  *   TS_LIST_QOFF    (offset)                                        n_dies + 1 offsets into the queue
  *   TS_LIST_APPEND  (seq, page_index, slot_lo, slot_hi, row_of_slot_0, 0, 0, 0)   page-wise append work
  *   TS_LIST_APPEND_ROWS (row, seq, pos, 0)                          tokens appended one by one
- * wg_slots = 0 uses the default number of resident decode workgroups. */
+ * wg_slots = 0 uses the default number of resident decode workgroups; mixed_mode = TS_MIXED_* as for the
+ * option of that name, or -1 for the default. */
 enum { TS_LIST_DECODE = 0, TS_LIST_COMBINE = 1, TS_LIST_PREFILL = 2, TS_LIST_PFMAP = 3, TS_LIST_ROWS = 4,
        TS_LIST_QUEUE = 5, TS_LIST_QOFF = 6, TS_LIST_APPEND = 7,
        TS_LIST_APPEND_ROWS = 8 };
 int64_t ts_plan_export(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
-                       int num_seqs, int32_t split_pages, int32_t wg_slots, int which,
+                       int num_seqs, int32_t split_pages, int32_t wg_slots, int32_t mixed_mode, int which,
                        int32_t *out, int64_t capacity);
 
 #ifdef __cplusplus

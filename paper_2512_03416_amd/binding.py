@@ -57,7 +57,7 @@ class PlanInfo(ctypes.Structure):
                 ("n_combine_rows", ctypes.c_int32), ("n_prefill_tiles", ctypes.c_int32),
                 ("n_generic_rows", ctypes.c_int32), ("split_pages", ctypes.c_int32),
                 ("tile_tokens", ctypes.c_int32), ("partial_slots", ctypes.c_int64),
-                ("ctx_pages", ctypes.c_int64)]
+                ("ctx_pages", ctypes.c_int64), ("mixed_mode", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 _lib = None
@@ -106,7 +106,7 @@ def load_library():
                                      ctypes.POINTER(PlanInfo)]
     lib.ts_plan_describe.restype = ctypes.c_int
     lib.ts_plan_export.argtypes = [ctypes.POINTER(Desc), i32p, i32p, ctypes.c_int, ctypes.c_int32,
-                                   ctypes.c_int32, ctypes.c_int, i32p, ctypes.c_int64]
+                                   ctypes.c_int32, ctypes.c_int32, ctypes.c_int, i32p, ctypes.c_int64]
     lib.ts_plan_export.restype = ctypes.c_int64
     lib.ts_kernel_times.argtypes = [vp, ctypes.POINTER(KernelStats), ctypes.c_int]
     lib.ts_kernel_times.restype = ctypes.c_int
@@ -164,19 +164,20 @@ PLAN_LISTS = {"decode": (0, 8), "combine": (1, 4), "prefill": (2, 8), "pfmap": (
               "append_rows": (8, 4)}
 
 
-def plan_export(desc: Desc, q_lens, ctx_lens, which: str, split_pages: int = 0, wg_slots: int = 0) -> np.ndarray:
+def plan_export(desc: Desc, q_lens, ctx_lens, which: str, split_pages: int = 0, wg_slots: int = 0,
+                mixed_mode: int = -1) -> np.ndarray:
     """One of the planner's work lists as an int32 array [records, words] (see tokenscale.h)."""
     ql, cl = _i32(q_lens), _i32(ctx_lens)
     lib = load_library()
     code, words = PLAN_LISTS[which]
-    n = lib.ts_plan_export(ctypes.byref(desc), _np_ptr(ql), _np_ptr(cl), len(ql), split_pages, wg_slots, code,
-                           ctypes.c_void_p(0), 0)
+    n = lib.ts_plan_export(ctypes.byref(desc), _np_ptr(ql), _np_ptr(cl), len(ql), split_pages, wg_slots, mixed_mode,
+                           code, ctypes.c_void_p(0), 0)
     if n < 0:
         raise TokenScaleError(int(n), "ts_plan_export")
     out = np.zeros((int(n), words), dtype=np.int32)
     if n:
-        lib.ts_plan_export(ctypes.byref(desc), _np_ptr(ql), _np_ptr(cl), len(ql), split_pages, wg_slots, code,
-                           _np_ptr(out), int(n) * words)
+        lib.ts_plan_export(ctypes.byref(desc), _np_ptr(ql), _np_ptr(cl), len(ql), split_pages, wg_slots, mixed_mode,
+                           code, _np_ptr(out), int(n) * words)
     return out
 
 

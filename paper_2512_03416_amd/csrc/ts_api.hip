@@ -96,6 +96,10 @@ struct ts_ctx {
     hipEvent_t last_event = nullptr;   // event of the most recent call
     hipStream_t last_stream = nullptr;
     bool have_work = false;
+    // Co-resident launch of a mixed batch: the decode grid runs on this internal stream (default priority),
+    // forked from the caller's stream behind the append and joined to it again with these two events.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     bool validate_pages = false;       // debug: check the page ids of a batch before anything is launched
     // launch shapes of this context's GPU, asked once per context (and again when the prefetch depth changes)
     int dec_nbuf = 2;                  // KV tiles in flight per decode wave
@@ -472,6 +476,12 @@ extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
         c->mixed_wgs = mixed_resident_workgroups(c->desc.kv_dtype);
         if (c->mixed_wgs <= 0) rc = fail(c, TS_ERR_HIP, "occupancy query of the persistent kernel failed");
     }
+    if (rc == TS_OK && desc_uses_mfma(c->desc)) {
+        if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming | hipEventDisableSystemFence) != hipSuccess ||
+            hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming | hipEventDisableSystemFence) != hipSuccess)
+            rc = fail(c, TS_ERR_HIP, "side stream / event creation failed");
+    }
     if (rc == TS_OK) {
         // the allocation-free entry point: this GPU's static scratch, and a staging ring that holds the
         // largest work lists that scratch takes
@@ -496,6 +506,9 @@ extern "C" int ts_destroy(ts_ctx* c)
     if (c->d_part_o) (void)hipFree(c->d_part_o);
     if (c->d_part_ml) (void)hipFree(c->d_part_ml);
     if (c->d_q_ctr) (void)hipFree(c->d_q_ctr);
+    if (c->side) (void)hipStreamDestroy(c->side);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     for (HostSlot& s : c->ring) {
         if (s.ptr) (void)hipHostFree(s.ptr);
         if (s.ev) (void)hipEventDestroy(s.ev);
@@ -558,8 +571,9 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         }
         return TS_OK;
     }
-    if (!strcmp(name, "mixed_persistent")) {
-        c->opt.mixed_persistent = value != 0;
+    if (!strcmp(name, "mixed_mode")) {
+        if (value < TS_MIXED_SEPARATE || value > TS_MIXED_CORESIDENT) return fail(c, TS_ERR_INVALID_ARG, "mixed_mode must be 0, 1 or 2");
+        c->opt.mixed_mode = (int32_t)value;
         return TS_OK;
     }
     if (!strcmp(name, "xcd_count")) {
@@ -586,7 +600,7 @@ extern "C" int ts_get_option(const ts_ctx* c, const char* name, int64_t* value)
     if (!strcmp(name, "decode_split_pages")) *value = c->opt.split_pages;
     else if (!strcmp(name, "prefill_path")) *value = c->opt.prefill_generic ? 1 : 0;
     else if (!strcmp(name, "decode_prefetch_tiles")) *value = c->dec_nbuf;
-    else if (!strcmp(name, "mixed_persistent")) *value = c->opt.mixed_persistent ? 1 : 0;
+    else if (!strcmp(name, "mixed_mode")) *value = c->opt.mixed_mode;
     else if (!strcmp(name, "xcd_count")) *value = c->opt.xcds;
     else if (!strcmp(name, "validate_block_table")) *value = c->validate_pages ? 1 : 0;
     else if (!strcmp(name, "kernel_timing")) *value = c->timing;
@@ -712,12 +726,30 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
     a.queue = (const QItem*)(wb + w.queue); a.q_off = (const int32_t*)(wb + w.q_off);
     a.n_queue = (int32_t)p.queue.size(); a.n_xcd = p.q_off.empty() ? 0 : (int32_t)p.q_off.size() - 1;
     a.q_ctr = q_ctr_of(c);
-    a.dec_nbuf = c->dec_nbuf; a.mixed_wgs = c->mixed_wgs;
+    a.dec_nbuf = c->dec_nbuf; a.mixed_wgs = c->mixed_wgs; a.n_cu = c->opt.n_cu;
     a.part_o = part_o_of(c); a.part_ml = part_ml_of(c);
 
     hipError_t e;
     // decode first: the serving loop's TPOT depends on these rows (Sec. 4.5.2)
-    if (a.n_queue > 0) {
+    if (a.n_queue > 0 && p.info.mixed_mode == TS_MIXED_CORESIDENT) {
+        // mixed batch, co-resident: the prefill tiles go to resident workgroups on this stream, the decode items
+        // (and the merge of split rows) to a grid of their own on the side stream, which starts behind everything
+        // this stream holds so far (the append) and which this stream waits for again before the call's end
+        // is marked.  The prefill launch comes first so that its workgroups take their places on the CUs.
+        // Timed as one unit (TS_K_MIXED): events between the two launches would serialise them.
+        e = (hipError_t)timed_launch(c, TS_K_MIXED, true, st, [&] {
+            hipError_t r = hipEventRecord(c->ev_fork, st);
+            if (r == hipSuccess) r = (hipError_t)launch_prefill_resident(a, stream);
+            if (r == hipSuccess) r = hipStreamWaitEvent(c->side, c->ev_fork, 0);
+            if (r == hipSuccess) r = (hipError_t)launch_decode(a, (void*)c->side);
+            if (r == hipSuccess) r = (hipError_t)launch_combine(a, (void*)c->side);
+            // (the join is made even after a failed launch: the side stream must not run on unordered)
+            const hipError_t j1 = hipEventRecord(c->ev_join, c->side);
+            const hipError_t j2 = j1 == hipSuccess ? hipStreamWaitEvent(st, c->ev_join, 0) : j1;
+            return (int)(r != hipSuccess ? r : j2);
+        });
+        if (e != hipSuccess) return hip_fail(c, e, "co-resident launch");
+    } else if (a.n_queue > 0) {
         // mixed batch: decode items and prefill tiles share the CUs in one persistent launch
         e = (hipError_t)timed_launch(c, TS_K_MIXED, true, st, [&] { return launch_mixed(a, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "mixed launch");

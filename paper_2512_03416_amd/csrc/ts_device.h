@@ -32,6 +32,34 @@ __device__ __forceinline__ const T TS_CONSTANT* as_constant(const T* p)
 #pragma clang diagnostic pop
 }
 
+// An opaque copy of a value: whatever is derived from the copy is worked out where it is used.  The
+// optimiser otherwise moves lane-index arithmetic and masks of rarely taken paths to the top of a kernel
+// and keeps them in registers across its main loops.
+__device__ __forceinline__ int opaque(int v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+__device__ __forceinline__ int opaque_uniform(int v)
+{
+    asm volatile("" : "+s"(v));
+    return v;
+}
+
+// Lanes l and l ^ 32 of a wave exchange through one register swap between the halves of the wave (no lane
+// index register, no trip through the LDS crossbar): both results of the swap hold, in every lane, one
+// of the two values of the lane pair.
+__device__ __forceinline__ float pair32_max(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair32_sum(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // bf16 bits <-> float
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
 

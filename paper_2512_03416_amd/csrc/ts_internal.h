@@ -101,7 +101,7 @@ struct PlanOptions {
     int32_t wg_slots = 768;     // decode workgroups resident at once (256 CUs x 3)
     int32_t n_cu = 256;         // compute units of the GPU
     int32_t xcds = 8;           // accelerator dies; workgroup i is dispatched to die i % xcds
-    bool mixed_persistent = true; // decode items and prefill tiles in one persistent launch
+    int32_t mixed_mode = TS_MIXED_CORESIDENT;   // how a batch with decode rows and prefill chunks is launched
     bool generic_only = false;  // every row through the generic kernel
     bool prefill_generic = false;
     int32_t tile_tokens = 0;    // query tokens per prefill tile
@@ -162,6 +162,7 @@ struct AttnArgs {
     const RowItem* rows; int32_t n_rows;
     int32_t dec_nbuf;          // KV tiles in flight per decode wave (2..4)
     int32_t mixed_wgs;         // workgroups of the persistent kernel that are resident on the GPU at once
+    int32_t n_cu;              // compute units of the GPU
     // split-K partials: o [slot][Hq][D] fp32 (unnormalised), ml [slot][Hq][2] = (max, sum) in log2 units
     float* part_o; float* part_ml;
 };
@@ -177,5 +178,6 @@ int decode_resident_workgroups(int kv_dtype, int nbuf);
 int mixed_resident_workgroups(int kv_dtype);
 int launch_prefill(const AttnArgs& a, void* stream);
 int launch_mixed(const AttnArgs& a, void* stream);
+int launch_prefill_resident(const AttnArgs& a, void* stream);
 
 }  // namespace ts

@@ -12,6 +12,17 @@ __global__ __launch_bounds__(64 * kDecWaves) void decode_kernel(AttnArgs a)
     decode_item<KT, NBUF, kDecWaves>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
 }
 
+// The default form, two KV tiles in flight per wave, held to 128 vector registers per lane (the attribute
+// counts in units of two here): one such workgroup then fits on a CU next to a resident prefill workgroup
+// (see prefill_resident_kernel), and four fit on a CU of their own.  A single workgroup of four waves per CU
+// already keeps enough loads in flight for the bf16 scan to run at its full rate.
+template <typename KT>
+__global__ __launch_bounds__(64 * kDecWaves) __attribute__((amdgpu_num_vgpr(64))) void decode_kernel_lean(AttnArgs a)
+{
+    __shared__ DecMerge<kDecWaves> mg;
+    decode_item<KT, 2, kDecWaves>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
+}
+
 // Merge of a row's splits, in split order:  M = max m_i, out = sum o_i 2^(m_i-M) / sum l_i 2^(m_i-M).
 // The partials of up to eight splits are requested together and then added one after the other: the
 // sums keep their order, and a row of ten splits waits for four loads instead of thirty.
@@ -62,7 +73,7 @@ static int launch_decode_t(const AttnArgs& a, hipStream_t st)
     switch (a.dec_nbuf) {
     case 3: hipLaunchKernelGGL((decode_kernel<KT, 3>), grid, block, 0, st, a); break;
     case 4: hipLaunchKernelGGL((decode_kernel<KT, 4>), grid, block, 0, st, a); break;
-    default: hipLaunchKernelGGL((decode_kernel<KT, 2>), grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL((decode_kernel_lean<KT>), grid, block, 0, st, a); break;
     }
     return (int)hipGetLastError();
 }
@@ -75,7 +86,7 @@ static int resident_t(int nbuf)
     switch (nbuf) {
     case 3: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 3>, 64 * kDecWaves, 0); break;
     case 4: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 4>, 64 * kDecWaves, 0); break;
-    default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 2>, 64 * kDecWaves, 0); break;
+    default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel_lean<KT>, 64 * kDecWaves, 0); break;
     }
     return e == hipSuccess ? per_cu : 0;
 }

@@ -24,10 +24,11 @@ union MixedLds {
     PfLds lds;
 };
 
-template <typename KT, int NBUF>
-__global__ __launch_bounds__(kPfThreads) void mixed_kernel(AttnArgs a)
+// The queue loop of a resident workgroup.  WITH_DECODE: the queues hold both kinds (one persistent kernel);
+// without it they hold prefill tiles only and LDS is the tile ring alone.
+template <typename KT, int NBUF, bool WITH_DECODE, typename LDS>
+__device__ __forceinline__ void drain_queues(const AttnArgs& a, LDS& sh)
 {
-    __shared__ MixedLds sh;
     int& s_idx = *reinterpret_cast<int*>(&sh);             // LDS is idle between two items
     const int tid = threadIdx.x;
     const int n_xcd = a.n_xcd;
@@ -46,8 +47,14 @@ __global__ __launch_bounds__(kPfThreads) void mixed_kernel(AttnArgs a)
         }
         const int32_t TS_CONSTANT* q = as_constant((const int32_t*)(a.queue + begin + idx));
         const int kind = q[0], item = q[1], g = q[2];
-        if (kind == 0) decode_item<KT, NBUF, kPfWaves>(a, item, g, sh.mg);
-        else prefill_tile<KT>(a, item, g, sh.lds);
+        int t = tid;
+        asm volatile("" : "+v"(t));                            // (see prefill_tile)
+        if constexpr (WITH_DECODE) {
+            if (kind == 0) decode_item<KT, NBUF, kPfWaves>(a, item, g, sh.mg);
+            else prefill_tile<KT>(a, item, g, sh.lds, t);
+        } else {
+            prefill_tile<KT>(a, item, g, sh, t);
+        }
         __syncthreads();                                       // LDS is reused by the next item
     }
     // last workgroup out resets the counters
@@ -59,6 +66,26 @@ __global__ __launch_bounds__(kPfThreads) void mixed_kernel(AttnArgs a)
                 __hip_atomic_store(a.q_ctr + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+}
+
+template <typename KT, int NBUF>
+__global__ __launch_bounds__(kPfThreads) void mixed_kernel(AttnArgs a)
+{
+    __shared__ MixedLds sh;
+    drain_queues<KT, NBUF, true>(a, sh);
+}
+
+// Co-resident form: one of these workgroups per CU stays for the whole launch and works through the prefill
+// tiles; it is held to 192 vector registers per lane (two waves per SIMD: 384 of 512) and uses 128 of the
+// 160 KB of LDS, so that every CU keeps room for one 4-wave decode workgroup of 128 registers per lane and
+// 25 KB -- the decode grid that the host launches next to it on a second stream.  The HBM-bound scan then
+// runs in the shadow of the MFMA-bound tiles on the same CU instead of taking turns with them.
+// (The register attribute counts in units of two on this architecture: 96 means 192.)
+template <typename KT>
+__global__ __launch_bounds__(kPfThreads) __attribute__((amdgpu_num_vgpr(96))) void prefill_resident_kernel(AttnArgs a)
+{
+    __shared__ PfLds lds;
+    drain_queues<KT, 2, false>(a, lds);
 }
 
 template <typename KT>
@@ -84,6 +111,18 @@ static int launch_mixed_t(const AttnArgs& a, hipStream_t st)
     if (n <= 0) return (int)hipErrorInvalidValue;
     const int grid = n < a.n_queue ? n : a.n_queue;
     hipLaunchKernelGGL((mixed_kernel<KT, 2>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
+    return (int)hipGetLastError();
+}
+
+int launch_prefill_resident(const AttnArgs& a, void* stream)
+{
+    if (a.n_queue <= 0) return (int)hipSuccess;
+    if (a.geo.D != 128 || a.geo.q_dtype != TS_BF16 || a.n_xcd <= 0 || a.n_xcd > 64 || a.n_cu <= 0) return (int)hipErrorInvalidValue;
+    const int grid = a.n_cu < a.n_queue ? a.n_cu : a.n_queue;   // (128 KB of LDS: one per CU)
+    hipStream_t st = (hipStream_t)stream;
+    if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_resident_kernel<uint16_t>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
+    else if (a.geo.kv_dtype == TS_FP8_E4M3) hipLaunchKernelGGL((prefill_resident_kernel<uint8_t>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
+    else return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
 }
 

@@ -3,14 +3,15 @@
 
 namespace ts {
 
+// (held to 192 vector registers per lane like the resident form: the attribute counts in units of two)
 template <typename KT>
-__global__ __launch_bounds__(kPfThreads) void prefill_kernel(AttnArgs a)
+__global__ __launch_bounds__(kPfThreads) __attribute__((amdgpu_num_vgpr(96))) void prefill_kernel(AttnArgs a)
 {
     __shared__ PfLds lds;
     const int32_t TS_CONSTANT* slot = as_constant((const int32_t*)(a.pfmap + blockIdx.x));
     const int item_idx = slot[0], g = slot[1];
     if (item_idx < 0) return;                               // padding of the die-aware launch order
-    prefill_tile<KT>(a, item_idx, g, lds);
+    prefill_tile<KT>(a, item_idx, g, lds, threadIdx.x);
 }
 
 int launch_prefill(const AttnArgs& a, void* stream)

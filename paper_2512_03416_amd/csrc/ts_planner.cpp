@@ -100,7 +100,8 @@ int validate_batch(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* 
 static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int64_t n_rows, int Hkv,
                                 int32_t wg_slots, int32_t n_cu, bool filled_by_prefill)
 {
-    const int64_t slots = std::max<int32_t>(1, filled_by_prefill ? wg_slots / 3 : wg_slots);
+    // (next to resident prefill tiles a CU has room for one decode workgroup)
+    const int64_t slots = std::max<int32_t>(1, filled_by_prefill ? n_cu : wg_slots);
     int64_t L = std::max<int64_t>(32, (decode_tiles + slots - 1) / slots);
     if (!filled_by_prefill && n_rows * Hkv < n_cu && decode_pages > 0) {
         const int64_t want_items = (n_cu + Hkv - 1) / Hkv;             // per KV head
@@ -115,7 +116,7 @@ static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int6
 // are launched next to each other: they walk the stream's pages almost in step, and the pages are
 // fetched from HBM about once instead of once per tile.  Streams are spread over the dies by
 // decreasing work (greedy), longest tiles of a stream first.
-static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds, bool build_queue)
+static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds, int mixed_mode)
 {
     p.pfmap.clear();
     p.queue.clear();
@@ -156,7 +157,17 @@ static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds, bool build_queue)
     p.pfmap.assign(longest * xcds, PfSlot{-1, 0});
     for (int x = 0; x < xcds; ++x)
         for (size_t k = 0; k < per[x].size(); ++k) p.pfmap[k * xcds + x] = per[x][k];
-    if (!build_queue || p.dec.empty()) return;
+    if (mixed_mode == TS_MIXED_SEPARATE || p.dec.empty()) return;
+    if (mixed_mode == TS_MIXED_CORESIDENT) {
+        // The tiles alone, die by die in the launch order above, for the resident prefill workgroups; the
+        // decode items run as a grid of their own next to them.
+        p.q_off.assign(xcds + 1, 0);
+        for (int x = 0; x < xcds; ++x) {
+            for (const PfSlot& t : per[x]) p.queue.push_back(QItem{1, t.item, t.head_kv, 0});
+            p.q_off[x + 1] = (int32_t)p.queue.size();
+        }
+        return;
+    }
 
     // Mixed batch: one queue per die for the persistent kernel.  Decode items (HBM-bound) and
     // prefill tiles (MFMA-bound) are interleaved by their share of their own kind's total cost, so
@@ -236,7 +247,15 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     if (mfma && !opt.prefill_generic)
         for (int s = 0; s < num_seqs; ++s)
             if (p.seqs[s].q_len > 1) tile_heads += (int64_t)((p.seqs[s].q_len + TT - 1) / TT) * Hkv;
-    const bool filled_by_prefill = opt.mixed_persistent && tile_heads >= opt.wg_slots / 3;
+    // How a batch with both kinds of rows is launched.  Co-resident by default; the fork and join of the
+    // two launches cost a few microseconds, so a batch whose tiles cannot occupy half of the CUs, or that has
+    // hardly any decode pages to hide behind them, goes through the single persistent kernel instead.
+    int mixed_mode = opt.mixed_mode;
+    if (mixed_mode == TS_MIXED_CORESIDENT && (tile_heads * 2 < opt.n_cu || decode_tiles < 4 * (int64_t)opt.n_cu))
+        mixed_mode = TS_MIXED_ONE_KERNEL;
+    if (!mfma || p.info.decode_tokens == 0 || tile_heads == 0) mixed_mode = TS_MIXED_SEPARATE;
+    p.info.mixed_mode = mixed_mode;
+    const bool filled_by_prefill = mixed_mode != TS_MIXED_SEPARATE && tile_heads >= opt.n_cu;
     const int32_t L = opt.split_pages > 0
                           ? opt.split_pages
                           : auto_split_pages(decode_tiles, decode_pages, p.info.decode_tokens, Hkv, opt.wg_slots,
@@ -277,7 +296,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     std::stable_sort(p.pf.begin(), p.pf.end(), [](const PfItem& a, const PfItem& b) {
         return (a.prefix + a.tok_begin + a.tok_count) > (b.prefix + b.tok_begin + b.tok_count);
     });
-    map_prefill_to_xcds(p, Hkv, std::max(1, opt.xcds), opt.mixed_persistent);
+    map_prefill_to_xcds(p, Hkv, std::max(1, opt.xcds), mixed_mode);
     std::stable_sort(p.rows.begin(), p.rows.end(),
                      [](const RowItem& a, const RowItem& b) { return a.n_keys > b.n_keys; });
     p.info.n_decode_items = (int32_t)p.dec.size();
@@ -323,19 +342,21 @@ extern "C" int ts_plan_describe(const ts_attn_desc* desc, const int32_t* q_lens,
 }
 
 extern "C" int64_t ts_plan_export(const ts_attn_desc* desc, const int32_t* q_lens, const int32_t* ctx_lens,
-                                  int num_seqs, int32_t split_pages, int32_t wg_slots, int which,
+                                  int num_seqs, int32_t split_pages, int32_t wg_slots, int32_t mixed_mode, int which,
                                   int32_t* out, int64_t capacity)
 {
     std::string err;
     int rc = ts::check_desc_impl(desc, &err);
     if (rc != TS_OK) return rc;
     if (split_pages < 0 || wg_slots < 0 || capacity < 0 || (capacity > 0 && !out)) return TS_ERR_INVALID_ARG;
+    if (mixed_mode < -1 || mixed_mode > TS_MIXED_CORESIDENT) return TS_ERR_INVALID_ARG;
     rc = ts::validate_batch(*desc, q_lens, ctx_lens, num_seqs, &err);
     if (rc != TS_OK) return rc;
     ts::Plan plan;
     ts::PlanOptions opt;
     opt.split_pages = split_pages;
     if (wg_slots > 0) opt.wg_slots = wg_slots;
+    if (mixed_mode >= 0) opt.mixed_mode = mixed_mode;
     ts::build_plan(*desc, q_lens, ctx_lens, num_seqs, opt, &plan);
     const void* src = nullptr;
     int64_t n = 0, words = 0;

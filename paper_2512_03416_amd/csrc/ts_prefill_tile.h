@@ -71,6 +71,16 @@ __device__ __forceinline__ uint4 keep_first8(uint4 v, int n)
 constexpr int kPfWaves = 8;                                // 512 threads, 256 query rows per tile
 constexpr int kPfThreads = 64 * kPfWaves;
 constexpr int kPfRing = 4;                                 // stages resident in LDS
+// MFMA slots between the LDS read of an operand and its use (2..4).  Every slot of lookahead keeps four more
+// registers per lane busy; the fp8 form, which also holds a prefetched stage in registers, takes two slots so
+// that it fits the 192 registers of the co-resident launch.
+#ifndef TS_PF_LOOKAHEAD
+#define TS_PF_LOOKAHEAD 4
+#endif
+#ifndef TS_PF_LOOKAHEAD_FP8
+#define TS_PF_LOOKAHEAD_FP8 2
+#endif
+template <typename KT> constexpr int kPfLookahead = sizeof(KT) == 1 ? TS_PF_LOOKAHEAD_FP8 : TS_PF_LOOKAHEAD;
 
 // LDS image of a stage (bf16 in both cases): per page the 256 16-byte pieces of the cache tile,
 // reordered.
@@ -175,12 +185,17 @@ __device__ __forceinline__ void stage_store(const StageFp8& st, unsigned char* l
 
 // One causal tile for KV head g, executed by a workgroup of kPfThreads threads.  All threads must call
 // it; it ends with a workgroup barrier, so lds may be reused right after it returns.
+// tid: the thread's index in the workgroup (a caller that runs tiles in a loop passes an opaque copy, so
+// that the many lane offsets derived from it are worked out per tile instead of being kept in registers
+// across the loop).
 template <typename KT>
-__device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, int g, PfLds& lds)
+__device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, int g, PfLds& lds, int tid)
 {
     constexpr int D = 128, KS = 8, DB = 4, kHalf = 32;     // KS: 16-dim steps of K Q^T, DB: 32-dim blocks of O^T
-    const PfItem it = a.pf[item_idx];
-    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, h = lane >> 5,
+    // (through the constant address space: the tile's description is wave-uniform and belongs in scalar registers)
+    const int32_t TS_CONSTANT* itp = as_constant((const int32_t*)(a.pf + item_idx));
+    const PfItem it{itp[0], itp[1], itp[2], itp[3], itp[4], itp[5], itp[6], 0};
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, h = lane >> 5,
               n = lane & 31;
     const int Hq = a.geo.Hq, G = a.geo.G;
 
@@ -257,7 +272,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // New reference maximum of the row; returns the factor that rescales everything accumulated so
     // far.  The weight sum is rescaled here, the caller rescales acc.
     auto raise = [&](float lmax) {
-        const float full = fmaxf(lmax, __shfl_xor(lmax, 32, 64));
+        const float full = pair32_max(lmax);                 // the row's other half sits in lane ^ 32
         const float m_new = fmaxf(m_ref, full);
         const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
         l_part *= alpha;
@@ -316,7 +331,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         if (q == 2) copy_1k_to_lds<0>(cp_lds_v, cp_v, cp_v_src);
         if (q == 3) copy_1k_to_lds<1024>(cp_lds_v, cp_v, cp_v_src);
     };
-    bf16x8 vpre[2], kpre[2];
+    bf16x8 vpre[3], kpre[2];
     auto fast_iter = [&](auto kin_tag, auto kout_tag, auto dma_tag, int hs, bool masked, const f32x16& s1, f32x16& s2,
                          const bf16x8 (&pop0)[2], bf16x8 (&pop1)[2]) {
         constexpr bool KIN = decltype(kin_tag)::value, KOUT = decltype(kout_tag)::value, DMA = decltype(dma_tag)::value;
@@ -337,16 +352,16 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         const float l_before = l_part;
         bf16x8 kop[KS], vop[2 * DB];
         uint32_t w[8];
-        vop[0] = vpre[0];
-        vop[1] = vpre[1];
+        constexpr int LA = kPfLookahead<KT>;
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (KIN) {
-            kop[0] = kpre[0];
-            kop[1] = kpre[1];
-        } else {
-            vop[2] = v_at(lv, 2);
-            kop[0] = lds16(lk);
-            kop[1] = lds16(lk + 512);
+        // operands of the first LA slots: read during the previous iteration (V always, K only where the
+        // stage was already published: KIN), else here
+#pragma unroll
+        for (int p = 0; p < LA; ++p) {
+            const int op = KIN ? kWarm[p] : kCold[p];
+            if (op < 8) vop[op] = vpre[op];
+            else if constexpr (KIN) kop[op - 8] = kpre[op - 8];
+            else kop[op - 8] = lds16(lk + (op - 8) * 512);
         }
         // The weight arithmetic is spread over the slots such that no instruction uses a result of its
         // own slot: slot j scales score j+1, takes the exponential of score j, adds weight j-1 to the
@@ -369,19 +384,16 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
                 }
                 s2 = mfma(kop[op - 8], qb[op - 8], s2);
             }
-            // read the operand of the MFMA four slots on (the first ones came with the iteration)
-            if (j + 4 < 16) {
-                const int nx = KIN ? kWarm[j + 4] : kCold[j + 4];
-                if (nx < 8) { if (nx >= (KIN ? 2 : 3)) vop[nx] = v_at(lv, nx); }
-                else if (nx - 8 >= 2) kop[nx - 8] = lds16(lk + (nx - 8) * 512);
+            // read the operand of the MFMA LA slots on; the last LA slots read the first operands of the next
+            // iteration (its K operands only if their stage is already published: KOUT)
+            if (j + LA < 16) {
+                const int nx = KIN ? kWarm[j + LA] : kCold[j + LA];
+                if (nx < 8) vop[nx] = v_at(lv, nx);
+                else kop[nx - 8] = lds16(lk + (nx - 8) * 512);
             } else {
-                // the last four slots read the first operands of the next iteration
-                if (j == 12) vpre[0] = v_at(lvn, 0);
-                if (j == 13) vpre[1] = v_at(lvn, 1);
-                if constexpr (KOUT) {
-                    if (j == 14) kpre[0] = lds16(lkn);
-                    if (j == 15) kpre[1] = lds16(lkn + 512);
-                }
+                const int nx = KOUT ? kWarm[j + LA - 16] : kCold[j + LA - 16];
+                if (nx < 8) vpre[nx] = v_at(lvn, nx);
+                else if constexpr (KOUT) kpre[nx - 8] = lds16(lkn + (nx - 8) * 512);
             }
             if (j >= 1) {
                 l_part += (j & 1) ? p_a : p_b;             // weight j-1
@@ -456,8 +468,12 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             cp_v = (const char*)a.v_cache + off;
         } else {
             if (i + 2 < n_stage) {
-                stage_store(st, lds.k[(i + 2) % kPfRing], lds.v[(i + 2) % kPfRing], (i + 2) * kStageTok, it.ctx_len, tid);
-                if (i + 3 < n_stage) stage_fetch(st, a, pid_next, g, tid);
+                // (the thread index goes through an opaque copy: the LDS and cache offsets derived from it are
+                // then worked out here, once per body, instead of occupying six registers for the whole tile)
+                int t = tid;
+                asm volatile("" : "+v"(t));
+                stage_store(st, lds.k[(i + 2) % kPfRing], lds.v[(i + 2) % kPfRing], (i + 2) * kStageTok, it.ctx_len, t);
+                if (i + 3 < n_stage) stage_fetch(st, a, pid_next, g, t);
             }
         }
     };
@@ -474,7 +490,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         __syncthreads();
         if constexpr (kCopy) {
             if (i + 2 == clear_stage) {                    // tile-uniform, at most once per tile
-                clear_v_tail(lds.v[clear_stage % kPfRing], clear_stage, it.ctx_len, tid);
+                clear_v_tail(lds.v[clear_stage % kPfRing], clear_stage, it.ctx_len, opaque(tid));
                 __syncthreads();
             }
         }
@@ -499,7 +515,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     __syncthreads();
     if constexpr (kCopy) {
         if (clear_stage == 0 || clear_stage == 1) {
-            clear_v_tail(lds.v[clear_stage], clear_stage, it.ctx_len, tid);
+            clear_v_tail(lds.v[clear_stage], clear_stage, it.ctx_len, opaque(tid));
             __syncthreads();
         }
     }
@@ -527,8 +543,12 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     constexpr std::true_type yes{};
     constexpr std::false_type no{};
     constexpr std::bool_constant<kCopy> dma{};
-    vpre[0] = lds16(vptr(0));                              // V operands of the first iteration
-    vpre[1] = lds16(vptr(0) + 1024);
+    {                                                      // V operands of the first slots of the first iteration
+        constexpr int kColdHead[4] = {0, 1, 2, 8};
+#pragma unroll
+        for (int p = 0; p < kPfLookahead<KT>; ++p)
+            if (kColdHead[p] < 8) vpre[kColdHead[p]] = lds16(vptr(0) + kColdHead[p] * 1024);
+    }
     for (; i < n_plain; ++i) {
         top(i);
         fast_iter(no, yes, dma, 2 * i, false, sA, sB, popA, popB);
@@ -553,10 +573,14 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // a lane holds 4-dim pieces of its row (8 bytes each), written directly they would reach memory
     // as 16 stores of 32 scattered 16-byte runs per wave; staged in LDS (row stride 272 bytes), 16 lanes
     // store one whole 256-byte row as 16-byte pieces and an instruction covers 4 rows.
+    // (Lane indices are derived afresh from an opaque copy of the thread index: nothing of this stage then
+    // occupies a register during the loops above.)
     constexpr int kOutStride = 272;
-    unsigned char* ob = (unsigned char*)&lds + wave * (32 * kOutStride);
+    const int tid_o = opaque(tid), wave_o = __builtin_amdgcn_readfirstlane(tid_o >> 6), lane_o = tid_o & 63,
+              h_o = lane_o >> 5, n_o = lane_o & 31;
+    unsigned char* ob = (unsigned char*)&lds + wave_o * (32 * kOutStride);
     const float vscale = (sizeof(KT) == 1) ? a.v_scale[g] : 1.0f;
-    const float l_row = l_part + __shfl_xor(l_part, 32, 64);
+    const float l_row = pair32_sum(l_part);
     const float inv = vscale / l_row;
 #pragma unroll
     for (int b = 0; b < DB; ++b)
@@ -565,20 +589,20 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             uint2 w;
             w.x = pack2(acc[b][4 * j] * inv, acc[b][4 * j + 1] * inv);
             w.y = pack2(acc[b][4 * j + 2] * inv, acc[b][4 * j + 3] * inv);
-            *(uint2*)(ob + n * kOutStride + 64 * b + 16 * j + 8 * h) = w;
+            *(uint2*)(ob + n_o * kOutStride + 64 * b + 16 * j + 8 * h_o) = w;
         }
     __builtin_amdgcn_wave_barrier();                       // (the rows are read back by other lanes of this wave)
-    const float inv_g = 1.0f / (float)G;
+    const float inv_g = 1.0f / (float)opaque_uniform(G);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int r = 4 * i + (lane >> 4);                 // row of the wave, 16 lanes per row
-        const int rho_r = 32 * wave + r;
+        const int r = 4 * i + (lane_o >> 4);               // row of the wave, 16 lanes per row
+        const int rho_r = 32 * wave_o + r;
         const int t_r = (int)(((float)rho_r + 0.5f) * inv_g);      // rho_r / G (exact for rho_r < 256, G <= 16)
         const int hd_r = rho_r - t_r * G;
-        const uint4 v = *(const uint4*)(ob + r * kOutStride + (lane & 15) * 16);
+        const uint4 v = *(const uint4*)(ob + r * kOutStride + (lane_o & 15) * 16);
         if (t_r < it.tok_count) {
             uint16_t* o = (uint16_t*)a.out + ((int64_t)(it.row0 + it.tok_begin + t_r) * Hq + g * G + hd_r) * D;
-            *(uint4*)(o + (lane & 15) * 8) = v;
+            *(uint4*)(o + (lane_o & 15) * 8) = v;
         }
     }
     __syncthreads();                                       // LDS may be reused by the caller

@@ -117,7 +117,7 @@ def test_prefill_pipeline_boundaries(kv, heads):
     pre = [0, 1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 159, 160, 191, 192, 193, 255, 257]
     q = [2 + (7 * i) % 70 for i in range(len(pre))]
     b = make_batch(shape, q, [a + c for a, c in zip(q, pre)], seed=43, pool_rule=1.2, value_mult=0.5)
-    check(b, options={"mixed_persistent": 0})
+    check(b, options={"mixed_mode": 0})
 
 
 def test_prefill_maximum_rises_late():
@@ -131,7 +131,7 @@ def test_prefill_maximum_rises_late():
     pos_new = torch.cat([1200 + torch.arange(300), 330 + torch.arange(70)]).float()
     b.k_prefix = (b.k_prefix.float() * (1.0 + pos_pre / 60.0)[:, None, None]).to(b.k_prefix.dtype)
     b.k_new = (b.k_new.float() * (1.0 + pos_new / 60.0)[:, None, None]).to(b.k_new.dtype)
-    check(b, options={"mixed_persistent": 0})
+    check(b, options={"mixed_mode": 0})
 
 
 @pytest.mark.parametrize("kv", ["bf16", "fp8"])
@@ -147,20 +147,24 @@ def test_mixed_batch_one_pass(kv):
     assert e1 == e2
 
 
-@pytest.mark.parametrize("persistent", [1, 0])
-def test_mixed_batch_persistent_and_separate_launches(persistent):
-    shape = AttnShape(32, 8, 128, "bf16", "bf16")
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+@pytest.mark.parametrize("persistent", [2, 1, 0])
+def test_mixed_batch_persistent_and_separate_launches(persistent, kv):
+    """The three ways of launching a mixed batch: co-resident (resident prefill workgroups, decode grid on
+    the side stream), one persistent kernel, one launch per class."""
+    import paper_2512_03416_amd as ts
+    shape = AttnShape(32, 8, 128, "bf16", kv)
     q = [1] * 40 + [300, 129, 1000] + [1] * 17
     rng = np.random.default_rng(5)
     c = list(rng.integers(1, 3000, size=40)) + [300 + 77, 129, 1000 + 640] + list(rng.integers(1, 600, size=17))
     b = make_batch(shape, q, c, seed=44, pool_rule=1.25, value_mult=0.5)
-    check(b, options={"mixed_persistent": persistent})
-    # a second pass on the same context must find the queue counters reset
-    import paper_2512_03416_amd as ts
     g = gpu()
+    assert ts.plan_describe(g.make_desc(b), b.q_lens, b.ctx_lens).mixed_mode == 2      # large enough for the default
+    check(b, options={"mixed_mode": persistent})
+    # a second pass on the same context must find the queue counters reset
     b = g.to_dev(make_batch(shape, q, c, seed=44, pool_rule=1.25, value_mult=0.5))
     ctx = ts.Context(g.make_desc(b))
-    ctx.set_option("mixed_persistent", persistent)
+    ctx.set_option("mixed_mode", persistent)
     outs = []
     for _ in range(3):
         o, _, _ = g.run_batch(b, ctx=ctx)
@@ -485,7 +489,7 @@ def test_seeded_random_batches(seed):
         c.append(ql + pre)
     if sum(q) == 0:
         q[0], c[0] = 1, c[0] + 1
-    opts = {"mixed_persistent": int(rng.integers(0, 2))}
+    opts = {"mixed_mode": int(rng.integers(0, 3))}
     if rng.integers(0, 2):
         opts["decode_split_pages"] = int(rng.choice([8, 13, 40]))
     b = make_batch(shape, q, c, seed=2000 + seed, pool_rule=1.3, value_mult=0.5)
@@ -539,10 +543,10 @@ def test_two_contexts_keep_their_own_options():
     c1, c2 = ts.Context(g.make_desc(b)), ts.Context(g.make_desc(b))
     c1.set_option("decode_prefetch_tiles", 4)
     c1.set_option("decode_split_pages", 16)
-    c1.set_option("mixed_persistent", 0)
+    c1.set_option("mixed_mode", 0)
     assert c1.get_option("decode_prefetch_tiles") == 4 and c2.get_option("decode_prefetch_tiles") == 2
     assert c1.get_option("decode_split_pages") == 16 and c2.get_option("decode_split_pages") == 0
-    assert c1.get_option("mixed_persistent") == 0 and c2.get_option("mixed_persistent") == 1
+    assert c1.get_option("mixed_mode") == 0 and c2.get_option("mixed_mode") == 2
     for _ in range(2):
         for c in (c1, c2):
             out, gk, gv = g.run_batch(b, ctx=c)
@@ -568,7 +572,7 @@ def test_reserve_then_no_growth_and_kernel_timing_counts():
         ctx.reserve(-1, 4, 100)
     assert e.value.code == binding.TS_ERR_INVALID_ARG
     ctx.set_option("decode_split_pages", 8)                  # split rows: decode, combine and prefill all run
-    ctx.set_option("mixed_persistent", 0)
+    ctx.set_option("mixed_mode", 0)
     ctx.reserve(4096, 64, 4096)                              # (sized for the options in force)
     n_alloc = ctx.get_option("scratch_allocations")
     ctx.set_option("kernel_timing", 1)

@@ -132,7 +132,10 @@ def test_config2_decode_full_size_sampled():
 
 
 def test_config4_burst_full_size_sampled():
+    import gpu_harness as g
+    import paper_2512_03416_amd as ts
     b = W.config4(device="cuda")
+    assert ts.plan_describe(g.make_desc(b), b.q_lens, b.ctx_lens).mixed_mode == 2      # co-resident launch
     dec = np.random.default_rng(8).choice(128, size=6, replace=False).tolist()
     # every 7th row of the sample, two chunks included, plus whole query tiles (64 tokens x 4 heads) of one
     # chunk: one in the middle with its neighbours' edges, and the chunk's last
@@ -142,6 +145,9 @@ def test_config4_burst_full_size_sampled():
 def test_config5_fp8_full_size_sampled():
     b = W.config5(device="cuda")
     assert b.shape.kv_dtype == "fp8" and b.num_seqs == 528
+    import gpu_harness as g
+    import paper_2512_03416_amd as ts
+    assert ts.plan_describe(g.make_desc(b), b.q_lens, b.ctx_lens).mixed_mode == 2      # co-resident launch
     dec = np.random.default_rng(9).choice(512, size=5, replace=False).tolist()
     longest = int(np.argmax(b.ctx_lens[:512]))
     # two chunks, every 61st row of the sample, plus two whole query tiles (32 tokens x 8 heads) and the edges around them

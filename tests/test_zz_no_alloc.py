@@ -27,7 +27,7 @@ def _pass(ctx, b, noalloc):
     return raw(out), raw(kc), raw(vc)
 
 
-@pytest.mark.parametrize("kv,persistent", [("bf16", 1), ("fp8", 1), ("bf16", 0)])
+@pytest.mark.parametrize("kv,persistent", [("bf16", 2), ("bf16", 1), ("fp8", 1), ("bf16", 0)])
 def test_noalloc_entry_point_matches_the_ordinary_one(kv, persistent):
     """Two calls in a row through ts_mixed_paged_attention_noalloc, the second with a smaller batch: outputs
     and caches byte-equal to ts_mixed_paged_attention's (same kernels, other scratch), which in turn is
@@ -38,13 +38,13 @@ def test_noalloc_entry_point_matches_the_ordinary_one(kv, persistent):
     import paper_2512_03416_amd as ts
     from paper_2512_03416_amd import binding
     shape = AttnShape(32, 8, 128, "bf16", kv)
-    big = dict(q=[1, 1, 1, 300, 1, 130, 1], c=[3000, 555, 40, 420, 64, 135, 1])
+    big = dict(q=[1, 1, 1, 300, 1, 130, 1, 700], c=[3000, 555, 40, 420, 64, 135, 1, 900])
     small = dict(q=[1, 70], c=[900, 70])
     tol = 2e-2 if kv == "bf16" else 6e-2
     b0 = g.to_dev(make_batch(shape, big["q"], big["c"], seed=91, value_mult=0.5))
     ctx = ts.Context(g.make_desc(b0))
     ctx.set_option("decode_split_pages", 8)                   # split rows: partial results and their merge are in play
-    ctx.set_option("mixed_persistent", persistent)
+    ctx.set_option("mixed_mode", persistent)
     for i, spec in enumerate((big, small)):
         print(f"[case] noalloc kv={kv} persistent={persistent} call {i}: q_lens={spec['q']}", flush=True)
         b = g.to_dev(make_batch(shape, spec["q"], spec["c"], seed=91 + i, value_mult=0.5, num_pages=b0.num_pages))
@@ -63,7 +63,7 @@ def test_noalloc_entry_point_matches_the_ordinary_one(kv, persistent):
     # a second context shares the GPU's static scratch: same answer again
     ctx2 = ts.Context(g.make_desc(b0))
     ctx2.set_option("decode_split_pages", 8)
-    ctx2.set_option("mixed_persistent", persistent)
+    ctx2.set_option("mixed_mode", persistent)
     again = _pass(ctx2, b, noalloc=True)
     assert again[0].tobytes() == got[0].tobytes()
     ctx2.close()
