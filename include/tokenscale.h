@@ -192,6 +192,11 @@ const char *ts_last_error(const ts_ctx *ctx);
  *                         from it take mode 1 by themselves;
  *                         1 (TS_MIXED_ONE_KERNEL) = decode items and prefill tiles share the workgroups of one
  *                         persistent launch;  0 (TS_MIXED_SEPARATE) = decode kernel, then prefill kernel
+ *   "prefill_widen_pages" fp8 caches: every tile of a prefill chunk reads the chunk's whole prefix, so the pages
+ *                         of the chunks' sequences are widened from e4m3 to bf16 once per pass, into scratch of
+ *                         8 KiB * num_kv_heads per page, and the tiles read that copy; a batch whose chunk
+ *                         sequences hold more pages than this value (default 16384; 0 = never widen) has its
+ *                         tiles widen the cache themselves.  Results are identical either way
  *   "xcd_count"           accelerator dies the prefill launch order is laid out for (default 8)
  *   "kernel_timing"       N > 0 = record HIP events around the launches of every N-th call
  *                         (see ts_kernel_times), 0 = off
@@ -236,6 +241,7 @@ typedef struct {
     int64_t ctx_pages;          /* sum over sequences of ceil(ctx_len/16)                      */
     int32_t mixed_mode;         /* TS_MIXED_* the batch is launched with (SEPARATE if one kind only) */
     int32_t reserved;
+    int64_t widened_pages;      /* fp8 caches: pages widened to bf16 before the prefill tiles run   */
 } ts_plan_info;
 
 int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
@@ -253,11 +259,12 @@ int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int3
  *   TS_LIST_QOFF    (offset)                                        n_dies + 1 offsets into the queue
  *   TS_LIST_APPEND  (seq, page_index, slot_lo, slot_hi, row_of_slot_0, 0, 0, 0)   page-wise append work
  *   TS_LIST_APPEND_ROWS (row, seq, pos, 0)                          tokens appended one by one
+ *   TS_LIST_WIDEN   (seq, page_index)                               fp8 caches: pages widened to bf16 per pass
  * wg_slots = 0 uses the default number of resident decode workgroups; mixed_mode = TS_MIXED_* as for the
  * option of that name, or -1 for the default. */
 enum { TS_LIST_DECODE = 0, TS_LIST_COMBINE = 1, TS_LIST_PREFILL = 2, TS_LIST_PFMAP = 3, TS_LIST_ROWS = 4,
        TS_LIST_QUEUE = 5, TS_LIST_QOFF = 6, TS_LIST_APPEND = 7,
-       TS_LIST_APPEND_ROWS = 8 };
+       TS_LIST_APPEND_ROWS = 8, TS_LIST_WIDEN = 9 };
 int64_t ts_plan_export(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
                        int num_seqs, int32_t split_pages, int32_t wg_slots, int32_t mixed_mode, int which,
                        int32_t *out, int64_t capacity);

@@ -78,6 +78,7 @@ struct ts_ctx {
     char* d_work = nullptr;  size_t work_cap = 0;
     float* d_part_o = nullptr; float* d_part_ml = nullptr; int64_t part_cap = 0;
     int32_t* d_q_ctr = nullptr;      // queue heads of the persistent kernel (zero between launches)
+    char* d_wide_k = nullptr; char* d_wide_v = nullptr; int64_t wide_cap = 0;   // fp8 caches: widened pages (capacity in pages)
     unsigned char* d_static = nullptr;  // this GPU's copy of the static scratch array
     bool static_call = false;        // the call in progress must not allocate (uses d_static)
     // pinned staging ring for the work lists
@@ -207,6 +208,24 @@ int ensure_partials(ts_ctx* c, int64_t slots)
     return TS_OK;
 }
 
+// fp8 caches: scratch for the bf16 copies of `pages` pages (K and V).
+int ensure_wide(ts_ctx* c, int64_t pages)
+{
+    if (pages <= c->wide_cap) return TS_OK;
+    const size_t page_bytes = (size_t)c->desc.num_kv_heads * kPage * c->desc.head_dim * 2;
+    TS_HIP(c, hipDeviceSynchronize());
+    if (c->d_wide_k) TS_HIP(c, hipFree(c->d_wide_k));
+    if (c->d_wide_v) TS_HIP(c, hipFree(c->d_wide_v));
+    c->d_wide_k = c->d_wide_v = nullptr; c->wide_cap = 0;
+    const int64_t cap = std::min<int64_t>(std::max<int64_t>(pages + pages / 2, 256), std::max<int64_t>(pages, c->opt.widen_pages));
+    if (hipMalloc((void**)&c->d_wide_k, (size_t)cap * page_bytes) != hipSuccess ||
+        hipMalloc((void**)&c->d_wide_v, (size_t)cap * page_bytes) != hipSuccess)
+        return fail(c, TS_ERR_NOMEM, "scratch for the widened fp8 pages could not be allocated");
+    c->wide_cap = cap;
+    c->n_alloc += 2;
+    return TS_OK;
+}
+
 // Next pinned staging slot with at least `bytes`, free of any copy still in flight.
 int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out, bool exact = false)
 {
@@ -266,7 +285,7 @@ __global__ __launch_bounds__(256) void check_pages_kernel(const SeqMeta* __restr
 }
 
 struct WorkLayout {
-    size_t seqs, dec, cmb, pf, pfmap, rows, queue, q_off, apt, apr, total;
+    size_t seqs, dec, cmb, pf, pfmap, rows, queue, q_off, apt, apr, wide, wide_base, total;
 };
 
 WorkLayout layout_of(const Plan& p)
@@ -283,6 +302,8 @@ WorkLayout layout_of(const Plan& p)
     w.q_off = o; o = align16(o + p.q_off.size() * sizeof(int32_t));
     w.apt = o; o = align16(o + p.apt.size() * sizeof(AppTile));
     w.apr = o; o = align16(o + p.apr.size() * sizeof(AppRow));
+    w.wide = o; o = align16(o + p.wide.size() * sizeof(WideItem));
+    w.wide_base = o; o = align16(o + p.wide_base.size() * sizeof(int32_t));
     w.total = o;
     return w;
 }
@@ -311,6 +332,8 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w, UploadJob* defer
     if (!p.q_off.empty()) memcpy(h + w.q_off, p.q_off.data(), p.q_off.size() * sizeof(int32_t));
     if (!p.apt.empty()) memcpy(h + w.apt, p.apt.data(), p.apt.size() * sizeof(AppTile));
     if (!p.apr.empty()) memcpy(h + w.apr, p.apr.data(), p.apr.size() * sizeof(AppRow));
+    if (!p.wide.empty()) memcpy(h + w.wide, p.wide.data(), p.wide.size() * sizeof(WideItem));
+    if (!p.wide_base.empty()) memcpy(h + w.wide_base, p.wide_base.data(), p.wide_base.size() * sizeof(int32_t));
     const int64_t n16 = (int64_t)(w.total / 16);           // (every list starts at a multiple of 16)
     const int blocks = (int)std::min<int64_t>(256, (n16 + 255) / 256);
     c->cur_slot = slot;                                    // its event is recorded by mark_work_done
@@ -506,6 +529,8 @@ extern "C" int ts_destroy(ts_ctx* c)
     if (c->d_part_o) (void)hipFree(c->d_part_o);
     if (c->d_part_ml) (void)hipFree(c->d_part_ml);
     if (c->d_q_ctr) (void)hipFree(c->d_q_ctr);
+    if (c->d_wide_k) (void)hipFree(c->d_wide_k);
+    if (c->d_wide_v) (void)hipFree(c->d_wide_v);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
@@ -538,9 +563,14 @@ extern "C" int ts_reserve(ts_ctx* c, int64_t max_tokens, int64_t max_seqs, int64
     const size_t bytes = (S + 1) * sizeof(SeqMeta) + items * (sizeof(DecItem) + sizeof(CmbItem)) + tiles * sizeof(PfItem) +
                          tiles * Hkv * xcds * sizeof(PfSlot) + T * sizeof(RowItem) +
                          (items + tiles) * Hkv * sizeof(QItem) + (xcds + 1) * sizeof(int32_t) +
-                         (T / kPage + 2 * S) * sizeof(AppTile) + T * sizeof(AppRow) + 16 * 16;
+                         (T / kPage + 2 * S) * sizeof(AppTile) + T * sizeof(AppRow) +
+                         (size_t)std::min<int64_t>((int64_t)P, c->opt.widen_pages) * sizeof(WideItem) + S * sizeof(int32_t) + 16 * 16;
     int rc = ensure_work(c, bytes);
     if (rc != TS_OK) return rc;
+    if (c->desc.kv_dtype == TS_FP8_E4M3 && desc_uses_mfma(c->desc) && c->opt.widen_pages > 0) {
+        rc = ensure_wide(c, std::min<int64_t>((int64_t)P, c->opt.widen_pages));
+        if (rc != TS_OK) return rc;
+    }
     for (int i = 0; i < kRing; ++i) {
         HostSlot* s = nullptr;
         rc = acquire_slot(c, bytes, &s);
@@ -576,6 +606,11 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         c->opt.mixed_mode = (int32_t)value;
         return TS_OK;
     }
+    if (!strcmp(name, "prefill_widen_pages")) {
+        if (value < 0 || value > ((int64_t)1 << 24)) return fail(c, TS_ERR_INVALID_ARG, "prefill_widen_pages out of range");
+        c->opt.widen_pages = value;
+        return TS_OK;
+    }
     if (!strcmp(name, "xcd_count")) {
         if (value < 1 || value > 64) return fail(c, TS_ERR_INVALID_ARG, "xcd_count must be 1..64");
         c->opt.xcds = (int32_t)value;
@@ -602,6 +637,7 @@ extern "C" int ts_get_option(const ts_ctx* c, const char* name, int64_t* value)
     else if (!strcmp(name, "decode_prefetch_tiles")) *value = c->dec_nbuf;
     else if (!strcmp(name, "mixed_mode")) *value = c->opt.mixed_mode;
     else if (!strcmp(name, "xcd_count")) *value = c->opt.xcds;
+    else if (!strcmp(name, "prefill_widen_pages")) *value = c->opt.widen_pages;
     else if (!strcmp(name, "validate_block_table")) *value = c->validate_pages ? 1 : 0;
     else if (!strcmp(name, "kernel_timing")) *value = c->timing;
     else if (!strcmp(name, "scratch_allocations")) *value = c->n_alloc;
@@ -675,12 +711,20 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
     DeviceGuard guard(c->device);
     c->timing_now = !c->static_call && c->timing > 0 && (c->timing_pass++ % (uint64_t)c->timing) == 0;
     if (c->dec_slots > 0) c->opt.wg_slots = c->dec_slots;
-    build_plan(c->desc, q_lens, ctx_lens, num_seqs, c->opt, &c->plan);
+    {
+        PlanOptions opt = c->opt;
+        if (c->static_call) opt.widen_pages = 0;           // (no scratch for widened pages: the tiles widen themselves)
+        build_plan(c->desc, q_lens, ctx_lens, num_seqs, opt, &c->plan);
+    }
     const Plan& p = c->plan;
     if (p.info.total_tokens == 0) return TS_OK;
     if (!q || !out) return fail(c, TS_ERR_INVALID_ARG, "q / out is NULL");
     rc = ensure_partials(c, p.info.partial_slots);
     if (rc != TS_OK) return rc;
+    if (!p.wide.empty()) {
+        rc = ensure_wide(c, (int64_t)p.wide.size());
+        if (rc != TS_OK) return rc;
+    }
     const WorkLayout w = layout_of(p);
     hipStream_t st = (hipStream_t)stream;
     // new tokens to append and no page check: the upload rides along in the first append launch (not in the
@@ -728,8 +772,16 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
     a.q_ctr = q_ctr_of(c);
     a.dec_nbuf = c->dec_nbuf; a.mixed_wgs = c->mixed_wgs; a.n_cu = c->opt.n_cu;
     a.part_o = part_o_of(c); a.part_ml = part_ml_of(c);
+    if (!p.wide.empty()) {
+        a.wide = (const WideItem*)(wb + w.wide); a.n_wide = (int32_t)p.wide.size();
+        a.wide_base = (const int32_t*)(wb + w.wide_base);
+        a.wide_k = c->d_wide_k; a.wide_v = c->d_wide_v;
+    }
 
     hipError_t e;
+    // fp8 cache: bf16 copies of the pages the prefill tiles read (behind the append: the chunk's own tokens are among them)
+    e = (hipError_t)timed_launch(c, TS_K_PREFILL, false, st, [&] { return launch_widen(a, c->d_wide_k, c->d_wide_v, stream); });
+    if (e != hipSuccess) return hip_fail(c, e, "widen launch");
     // decode first: the serving loop's TPOT depends on these rows (Sec. 4.5.2)
     if (a.n_queue > 0 && p.info.mixed_mode == TS_MIXED_CORESIDENT) {
         // mixed batch, co-resident: the prefill tiles go to resident workgroups on this stream, the decode items

@@ -75,6 +75,11 @@ struct AppRow {           // one new token that is appended on its own
     int32_t pad;
 };
 
+struct WideItem {         // one page of a prefill chunk's sequence that is widened from e4m3 to bf16 before the tiles run
+    int32_t seq;
+    int32_t page_idx;     // index into the sequence's page list; the widened copy is page number = index in this list
+};
+
 struct RowItem {          // one query row for the generic kernel
     int32_t row;
     int32_t seq;
@@ -93,6 +98,8 @@ struct Plan {
     std::vector<QItem> queue;        // mixed batches: per-die queues, concatenated
     std::vector<int32_t> q_off;      // xcds + 1 offsets into queue
     std::vector<RowItem> rows;
+    std::vector<WideItem> wide;      // fp8 caches: pages to widen, in the order of their widened copies
+    std::vector<int32_t> wide_base;  // per sequence: number of its first widened page, -1 = not widened
     ts_plan_info info{};
 };
 
@@ -105,6 +112,7 @@ struct PlanOptions {
     bool generic_only = false;  // every row through the generic kernel
     bool prefill_generic = false;
     int32_t tile_tokens = 0;    // query tokens per prefill tile
+    int64_t widen_pages = 16384; // fp8 caches: most pages of prefill sequences that are widened to bf16 per pass (0 = never)
 };
 
 // Which kernels serve a descriptor.
@@ -160,6 +168,11 @@ struct AttnArgs {
     const QItem* queue; const int32_t* q_off; int32_t n_queue; int32_t n_xcd;
     int32_t* q_ctr;            // n_xcd queue heads + 1 finished-workgroup count, zero between launches
     const RowItem* rows; int32_t n_rows;
+    // fp8 caches: bf16 copies of the prefill sequences' pages (tiles [page][kv head], bf16 operand order), made
+    // once per pass; wide_base[seq] = number of the sequence's first widened page.  NULL = the tiles read the
+    // fp8 cache and widen it themselves.
+    const void* wide_k; const void* wide_v; const int32_t* wide_base;
+    const WideItem* wide; int32_t n_wide;
     int32_t dec_nbuf;          // KV tiles in flight per decode wave (2..4)
     int32_t mixed_wgs;         // workgroups of the persistent kernel that are resident on the GPU at once
     int32_t n_cu;              // compute units of the GPU
@@ -176,6 +189,7 @@ int launch_combine(const AttnArgs& a, void* stream);
 // caller keeps the answers per context: two contexts may sit on different GPUs.
 int decode_resident_workgroups(int kv_dtype, int nbuf);
 int mixed_resident_workgroups(int kv_dtype);
+int launch_widen(const AttnArgs& a, void* wide_k, void* wide_v, void* stream);
 int launch_prefill(const AttnArgs& a, void* stream);
 int launch_mixed(const AttnArgs& a, void* stream);
 int launch_prefill_resident(const AttnArgs& a, void* stream);

@@ -26,7 +26,9 @@ union MixedLds {
 
 // The queue loop of a resident workgroup.  WITH_DECODE: the queues hold both kinds (one persistent kernel);
 // without it they hold prefill tiles only and LDS is the tile ring alone.
-template <typename KT, int NBUF, bool WITH_DECODE, typename LDS>
+// KT: element type the decode items read (the cache's); PKT: element type the prefill tiles read (the cache's,
+// or bf16 when the pages of an e4m3 cache were widened before the launch).
+template <typename KT, typename PKT, bool WIDE, int NBUF, bool WITH_DECODE, typename LDS>
 __device__ __forceinline__ void drain_queues(const AttnArgs& a, LDS& sh)
 {
     int& s_idx = *reinterpret_cast<int*>(&sh);             // LDS is idle between two items
@@ -51,9 +53,9 @@ __device__ __forceinline__ void drain_queues(const AttnArgs& a, LDS& sh)
         asm volatile("" : "+v"(t));                            // (see prefill_tile)
         if constexpr (WITH_DECODE) {
             if (kind == 0) decode_item<KT, NBUF, kPfWaves>(a, item, g, sh.mg);
-            else prefill_tile<KT>(a, item, g, sh.lds, t);
+            else prefill_tile<PKT, WIDE>(a, item, g, sh.lds, t);
         } else {
-            prefill_tile<KT>(a, item, g, sh, t);
+            prefill_tile<PKT, WIDE>(a, item, g, sh, t);
         }
         __syncthreads();                                       // LDS is reused by the next item
     }
@@ -68,11 +70,11 @@ __device__ __forceinline__ void drain_queues(const AttnArgs& a, LDS& sh)
     }
 }
 
-template <typename KT, int NBUF>
+template <typename KT, typename PKT, bool WIDE, int NBUF>
 __global__ __launch_bounds__(kPfThreads) void mixed_kernel(AttnArgs a)
 {
     __shared__ MixedLds sh;
-    drain_queues<KT, NBUF, true>(a, sh);
+    drain_queues<KT, PKT, WIDE, NBUF, true>(a, sh);
 }
 
 // Co-resident form: one of these workgroups per CU stays for the whole launch and works through the prefill
@@ -81,11 +83,11 @@ __global__ __launch_bounds__(kPfThreads) void mixed_kernel(AttnArgs a)
 // 25 KB -- the decode grid that the host launches next to it on a second stream.  The HBM-bound scan then
 // runs in the shadow of the MFMA-bound tiles on the same CU instead of taking turns with them.
 // (The register attribute counts in units of two on this architecture: 96 means 192.)
-template <typename KT>
+template <typename KT, bool WIDE>
 __global__ __launch_bounds__(kPfThreads) __attribute__((amdgpu_num_vgpr(96))) void prefill_resident_kernel(AttnArgs a)
 {
     __shared__ PfLds lds;
-    drain_queues<KT, 2, false>(a, lds);
+    drain_queues<KT, KT, WIDE, 2, false>(a, lds);
 }
 
 template <typename KT>
@@ -94,7 +96,7 @@ static int resident_mixed_t()
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mixed_kernel<KT, 2>, kPfThreads, 0) != hipSuccess)
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mixed_kernel<KT, KT, false, 2>, kPfThreads, 0) != hipSuccess)
         return 0;
     return cus * (per_cu > 0 ? per_cu : 1);
 }
@@ -104,13 +106,13 @@ int mixed_resident_workgroups(int kv_dtype)
     return kv_dtype == TS_FP8_E4M3 ? resident_mixed_t<uint8_t>() : resident_mixed_t<uint16_t>();
 }
 
-template <typename KT>
+template <typename KT, typename PKT, bool WIDE>
 static int launch_mixed_t(const AttnArgs& a, hipStream_t st)
 {
     const int n = a.mixed_wgs;                                 // resident workgroups on the context's GPU
     if (n <= 0) return (int)hipErrorInvalidValue;
     const int grid = n < a.n_queue ? n : a.n_queue;
-    hipLaunchKernelGGL((mixed_kernel<KT, 2>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
+    hipLaunchKernelGGL((mixed_kernel<KT, PKT, WIDE, 2>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
     return (int)hipGetLastError();
 }
 
@@ -120,8 +122,10 @@ int launch_prefill_resident(const AttnArgs& a, void* stream)
     if (a.geo.D != 128 || a.geo.q_dtype != TS_BF16 || a.n_xcd <= 0 || a.n_xcd > 64 || a.n_cu <= 0) return (int)hipErrorInvalidValue;
     const int grid = a.n_cu < a.n_queue ? a.n_cu : a.n_queue;   // (128 KB of LDS: one per CU)
     hipStream_t st = (hipStream_t)stream;
-    if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_resident_kernel<uint16_t>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
-    else if (a.geo.kv_dtype == TS_FP8_E4M3) hipLaunchKernelGGL((prefill_resident_kernel<uint8_t>), dim3((unsigned)grid), dim3(kPfThreads), 0, st, a);
+    const dim3 g3((unsigned)grid), b3(kPfThreads);
+    if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_resident_kernel<uint16_t, false>), g3, b3, 0, st, a);
+    else if (a.geo.kv_dtype == TS_FP8_E4M3 && a.wide_base) hipLaunchKernelGGL((prefill_resident_kernel<uint16_t, true>), g3, b3, 0, st, a);
+    else if (a.geo.kv_dtype == TS_FP8_E4M3) hipLaunchKernelGGL((prefill_resident_kernel<uint8_t, false>), g3, b3, 0, st, a);
     else return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
 }
@@ -131,8 +135,9 @@ int launch_mixed(const AttnArgs& a, void* stream)
     if (a.n_queue <= 0) return (int)hipSuccess;
     if (a.geo.D != 128 || a.geo.q_dtype != TS_BF16 || a.n_xcd <= 0 || a.n_xcd > 64) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    if (a.geo.kv_dtype == TS_BF16) return launch_mixed_t<uint16_t>(a, st);
-    if (a.geo.kv_dtype == TS_FP8_E4M3) return launch_mixed_t<uint8_t>(a, st);
+    if (a.geo.kv_dtype == TS_BF16) return launch_mixed_t<uint16_t, uint16_t, false>(a, st);
+    if (a.geo.kv_dtype == TS_FP8_E4M3 && a.wide_base) return launch_mixed_t<uint8_t, uint16_t, true>(a, st);
+    if (a.geo.kv_dtype == TS_FP8_E4M3) return launch_mixed_t<uint8_t, uint8_t, false>(a, st);
     return (int)hipErrorInvalidValue;
 }
 

@@ -4,14 +4,51 @@
 namespace ts {
 
 // (held to 192 vector registers per lane like the resident form: the attribute counts in units of two)
-template <typename KT>
+template <typename KT, bool WIDE>
 __global__ __launch_bounds__(kPfThreads) __attribute__((amdgpu_num_vgpr(96))) void prefill_kernel(AttnArgs a)
 {
     __shared__ PfLds lds;
     const int32_t TS_CONSTANT* slot = as_constant((const int32_t*)(a.pfmap + blockIdx.x));
     const int item_idx = slot[0], g = slot[1];
     if (item_idx < 0) return;                               // padding of the die-aware launch order
-    prefill_tile<KT>(a, item_idx, g, lds, threadIdx.x);
+    prefill_tile<KT, WIDE>(a, item_idx, g, lds, threadIdx.x);
+}
+
+// fp8 caches: bf16 copies of the pages the prefill tiles will read, one workgroup per (page, KV head).  The
+// copies keep the tile order of a bf16 cache -- K as 16-byte chunks of 8 dims [D/8][16 slots][8], V
+// token-fastest [D][16 slots] -- so the tile kernel copies them into LDS exactly like bf16 cache pages.  Every
+// e4m3 value is a bf16 value: the conversion is exact, and pages are copied whole (slots past the end of the
+// sequence hold whatever the cache holds; the tile kernel masks them as it does for a bf16 cache).
+__global__ __launch_bounds__(256) void widen_kernel(AttnArgs a, uint16_t* __restrict__ wk, uint16_t* __restrict__ wv)
+{
+    const int Hkv = a.geo.Hkv;
+    const int item = blockIdx.x / Hkv, g = blockIdx.x % Hkv;
+    const int32_t TS_CONSTANT* w = as_constant((const int32_t*)(a.wide + item));
+    const int seq = w[0], pidx = w[1];
+    const int64_t page = as_constant(a.block_table)[(int64_t)seq * a.geo.max_pages + pidx];
+    const uint8_t* ks = (const uint8_t*)a.k_cache + (page * Hkv + g) * 2048;
+    const uint8_t* vs = (const uint8_t*)a.v_cache + (page * Hkv + g) * 2048;
+    uint16_t* kd = wk + ((int64_t)item * Hkv + g) * 2048;
+    uint16_t* vd = wv + ((int64_t)item * Hkv + g) * 2048;
+    const int t = threadIdx.x;
+    // thread t takes 8 consecutive bytes of each tile.  K: bytes of chunk (c16 = t / 32, slot = (t / 2) % 16),
+    // dims 16 c16 + 8 (t % 2) .. + 7 -> bf16 chunk (2 c16 + t % 2, slot).  V: elements 8 t .. 8 t + 7 keep their place.
+    const uint2 kb = *(const uint2*)(ks + t * 8);
+    const uint2 vb = *(const uint2*)(vs + t * 8);
+    const int c16 = t >> 5, slot = (t >> 1) & 15, half = t & 1;
+    const uint2 k0 = fp8x4_bf16x4(kb.x), k1 = fp8x4_bf16x4(kb.y);
+    const uint2 v0 = fp8x4_bf16x4(vb.x), v1 = fp8x4_bf16x4(vb.y);
+    *(uint4*)(kd + ((2 * c16 + half) * 16 + slot) * 8) = make_uint4(k0.x, k0.y, k1.x, k1.y);
+    *(uint4*)(vd + t * 8) = make_uint4(v0.x, v0.y, v1.x, v1.y);
+}
+
+int launch_widen(const AttnArgs& a, void* wide_k, void* wide_v, void* stream)
+{
+    if (a.n_wide <= 0) return (int)hipSuccess;
+    if (a.geo.D != 128 || a.geo.kv_dtype != TS_FP8_E4M3 || !wide_k || !wide_v) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(widen_kernel, dim3((unsigned)a.n_wide * (unsigned)a.geo.Hkv), dim3(256), 0, (hipStream_t)stream, a,
+                       (uint16_t*)wide_k, (uint16_t*)wide_v);
+    return (int)hipGetLastError();
 }
 
 int launch_prefill(const AttnArgs& a, void* stream)
@@ -20,8 +57,10 @@ int launch_prefill(const AttnArgs& a, void* stream)
     if (a.geo.D != 128 || a.geo.q_dtype != TS_BF16) return (int)hipErrorInvalidValue;
     dim3 grid((unsigned)a.n_pfmap), block(kPfThreads);
     hipStream_t st = (hipStream_t)stream;
-    if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_kernel<uint16_t>), grid, block, 0, st, a);
-    else if (a.geo.kv_dtype == TS_FP8_E4M3) hipLaunchKernelGGL((prefill_kernel<uint8_t>), grid, block, 0, st, a);
+    // (an fp8 cache whose pages were widened beforehand is read through the bf16 form)
+    if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_kernel<uint16_t, false>), grid, block, 0, st, a);
+    else if (a.geo.kv_dtype == TS_FP8_E4M3 && a.wide_base) hipLaunchKernelGGL((prefill_kernel<uint16_t, true>), grid, block, 0, st, a);
+    else if (a.geo.kv_dtype == TS_FP8_E4M3) hipLaunchKernelGGL((prefill_kernel<uint8_t, false>), grid, block, 0, st, a);
     else return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
 }

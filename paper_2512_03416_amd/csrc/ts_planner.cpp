@@ -289,6 +289,24 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
                 p.rows.push_back(RowItem{m.q_off + i, s, m.prefix + i + 1, 0});
         }
     }
+    // fp8 caches: the pages of the chunks' sequences are widened to bf16 once per pass (every tile of a chunk
+    // reads the whole prefix: widening inside the tiles repeats the conversion once per tile and costs the tile
+    // kernel 8 % of its time), provided they fit the scratch the option allows
+    if (d.kv_dtype == TS_FP8_E4M3 && !p.pf.empty() && opt.widen_pages > 0) {
+        int64_t need = 0;
+        for (int s = 0; s < num_seqs; ++s)
+            if (p.seqs[s].q_len > 1) need += (p.seqs[s].ctx_len + kPage - 1) / kPage;
+        if (need <= opt.widen_pages) {
+            p.wide_base.assign((size_t)num_seqs, -1);
+            for (int s = 0; s < num_seqs; ++s) {
+                if (p.seqs[s].q_len <= 1) continue;
+                p.wide_base[s] = (int32_t)p.wide.size();
+                const int32_t n_pages = (p.seqs[s].ctx_len + kPage - 1) / kPage;
+                for (int32_t j = 0; j < n_pages; ++j) p.wide.push_back(WideItem{s, j});
+            }
+        }
+    }
+    p.info.widened_pages = (int64_t)p.wide.size();
     // longest first (stable, so equal lengths keep batch order and runs stay reproducible)
     std::stable_sort(p.dec.begin(), p.dec.end(), [](const DecItem& a, const DecItem& b) {
         return (a.page_end - a.page_begin) > (b.page_end - b.page_begin);
@@ -370,6 +388,7 @@ extern "C" int64_t ts_plan_export(const ts_attn_desc* desc, const int32_t* q_len
     case TS_LIST_QOFF:    src = plan.q_off.data(); n = (int64_t)plan.q_off.size(); words = 1; break;
     case TS_LIST_APPEND:  src = plan.apt.data();   n = (int64_t)plan.apt.size();   words = sizeof(ts::AppTile) / 4; break;
     case TS_LIST_APPEND_ROWS: src = plan.apr.data(); n = (int64_t)plan.apr.size(); words = sizeof(ts::AppRow) / 4; break;
+    case TS_LIST_WIDEN:   src = plan.wide.data();  n = (int64_t)plan.wide.size();  words = sizeof(ts::WideItem) / 4; break;
     default: return TS_ERR_INVALID_ARG;
     }
     const int64_t fit = words ? std::min<int64_t>(n, capacity / words) : 0;

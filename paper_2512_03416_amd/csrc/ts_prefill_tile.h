@@ -73,14 +73,18 @@ constexpr int kPfThreads = 64 * kPfWaves;
 constexpr int kPfRing = 4;                                 // stages resident in LDS
 // MFMA slots between the LDS read of an operand and its use (2..4).  Every slot of lookahead keeps four more
 // registers per lane busy; the fp8 form, which also holds a prefetched stage in registers, takes two slots so
-// that it fits the 192 registers of the co-resident launch.
+// that it fits the 192 registers of the co-resident launch, the form that reads widened pages three.
 #ifndef TS_PF_LOOKAHEAD
 #define TS_PF_LOOKAHEAD 4
 #endif
 #ifndef TS_PF_LOOKAHEAD_FP8
 #define TS_PF_LOOKAHEAD_FP8 2
 #endif
-template <typename KT> constexpr int kPfLookahead = sizeof(KT) == 1 ? TS_PF_LOOKAHEAD_FP8 : TS_PF_LOOKAHEAD;
+#ifndef TS_PF_LOOKAHEAD_WIDE
+#define TS_PF_LOOKAHEAD_WIDE 3
+#endif
+template <typename KT, bool WIDE> constexpr int kPfLookahead =
+    sizeof(KT) == 1 ? TS_PF_LOOKAHEAD_FP8 : (WIDE ? TS_PF_LOOKAHEAD_WIDE : TS_PF_LOOKAHEAD);
 
 // LDS image of a stage (bf16 in both cases): per page the 256 16-byte pieces of the cache tile,
 // reordered.
@@ -126,15 +130,15 @@ __device__ __forceinline__ void copy_1k_to_lds(uint32_t lds_addr, const void* ba
 }
 __device__ __forceinline__ int copy_k_lane_offset(int lane) { return (lane >> 4) * 256 + swap23(lane & 15) * 16; }
 __device__ __forceinline__ int copy_v_lane_offset(int lane) { return (lane & 31) * 32 + (lane >> 5) * 16; }
-__device__ __forceinline__ void stage_copy_bf16(const AttnArgs& a, int stage, int page_id, int g, int wave, int lane,
-                                                PfLds& lds)
+__device__ __forceinline__ void stage_copy_bf16(const char* kbase, const char* vbase, int Hkv, int stage, int page_id, int g,
+                                                int wave, int lane, PfLds& lds)
 {
-    const int64_t off = ((int64_t)page_id * a.geo.Hkv + g) * 4096 + (wave & 1) * 2048;   // (page_id: of page 4 stage + wave / 2)
+    const int64_t off = ((int64_t)page_id * Hkv + g) * 4096 + (wave & 1) * 2048;   // (page_id: of page 4 stage + wave / 2)
     const int slot = stage % kPfRing;
     // K: LDS piece [c0 + lane / 16][lane % 16] takes cache piece (c0 + lane / 16, swap23(lane % 16))
     // V: LDS piece [b0][lane / 32][lane % 32] takes cache piece (dim 32 b0 + lane % 32, half lane / 32)
-    copy_2k_to_lds(lds_address(lds.k[slot]) + wave * 2048, (const char*)a.k_cache + off, copy_k_lane_offset(lane));
-    copy_2k_to_lds(lds_address(lds.v[slot]) + wave * 2048, (const char*)a.v_cache + off, copy_v_lane_offset(lane));
+    copy_2k_to_lds(lds_address(lds.k[slot]) + wave * 2048, kbase + off, copy_k_lane_offset(lane));
+    copy_2k_to_lds(lds_address(lds.v[slot]) + wave * 2048, vbase + off, copy_v_lane_offset(lane));
 }
 constexpr int kCopiesPerStage = 4;                         // vmcnt units one stage_copy_bf16 adds per wave
 template <int N> __device__ __forceinline__ void pf_wait_copies()
@@ -188,7 +192,8 @@ __device__ __forceinline__ void stage_store(const StageFp8& st, unsigned char* l
 // tid: the thread's index in the workgroup (a caller that runs tiles in a loop passes an opaque copy, so
 // that the many lane offsets derived from it are worked out per tile instead of being kept in registers
 // across the loop).
-template <typename KT>
+// WIDE: KT is bf16 and the pages are the widened copies of an e4m3 cache.
+template <typename KT, bool WIDE>
 __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, int g, PfLds& lds, int tid)
 {
     constexpr int D = 128, KS = 8, DB = 4, kHalf = 32;     // KS: 16-dim steps of K Q^T, DB: 32-dim blocks of O^T
@@ -211,13 +216,23 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
 #pragma unroll
         for (int s = 0; s < KS; ++s) qb[s] = u4_bf16x8(*(const uint4*)(qrow + 16 * s));
     }
-    const float kscale = (sizeof(KT) == 1) ? a.k_scale[g] : 1.0f;
-    const float c = a.sm_scale * kscale * kLog2e;
+    // KT is the element type the tile reads: e4m3 straight from the cache, or bf16 -- the cache itself, or the
+    // copy of an e4m3 cache that was widened before the launch (then the scales still apply and the pages of
+    // the sequence are numbered consecutively from wide_base[seq] instead of going through the block table)
+    static_assert(!WIDE || sizeof(KT) == 2, "widened pages are bf16");
+    constexpr bool fp8_cache = sizeof(KT) == 1 || WIDE;
+    constexpr bool widened = WIDE;
+    // (the scale of the exponent is wave-uniform: kept in a scalar register, it costs no vector register)
+    const float kscale = fp8_cache ? as_constant(a.k_scale)[g] : 1.0f;
+    const float c = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.sm_scale * kscale * kLog2e)));
     const int qpos = it.prefix + it.tok_begin + tok;
     const int wave_min_q = it.prefix + it.tok_begin + min((32 * wave) / G, it.tok_count - 1);
     const int kv_hi = it.prefix + it.tok_begin + it.tok_count;     // keys [0, kv_hi) matter to this tile
     const int last_page = (it.ctx_len - 1) / kPage;
     const int32_t TS_CONSTANT* bt = as_constant(a.block_table) + (int64_t)it.seq * a.geo.max_pages;
+    const int wbase = widened ? as_constant(a.wide_base)[it.seq] : 0;
+    const char* const kbase = (const char*)(widened ? a.wide_k : a.k_cache);
+    const char* const vbase = (const char*)(widened ? a.wide_v : a.v_cache);
     // Half-stages [0, hend) hold keys that some row of the tile sees; every wave works through all of
     // them (a wave whose rows all come earlier multiplies one or two fully masked half-stages: that
     // keeps the eight waves in the same loop).  Half-stages [0, hfull) need no causal mask in this wave.
@@ -352,7 +367,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         const float l_before = l_part;
         bf16x8 kop[KS], vop[2 * DB];
         uint32_t w[8];
-        constexpr int LA = kPfLookahead<KT>;
+        constexpr int LA = kPfLookahead<KT, WIDE>;
         __builtin_amdgcn_sched_barrier(0);
         // operands of the first LA slots: read during the previous iteration (V always, K only where the
         // stage was already published: KIN), else here
@@ -454,7 +469,10 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // dependent load would hold up every wave of the workgroup right after the barrier, when no wave
     // has anything else to issue; so the id that top(i+1) needs is requested between the two iterations
     // of body i, where the wait for it falls into a phase in which the other wave of the SIMD has work.
-    auto page_id = [&](int stage) { return bt[min(stage * 4 + (wave >> 1), last_page)]; };
+    auto page_id = [&](int stage) {
+        const int j = min(stage * 4 + (wave >> 1), last_page);
+        return widened ? wbase + j : bt[j];
+    };
     int32_t pid_next;                                      // page id top(i) needs: that of stage i + 3
     // top(i), bf16: a steady body always copies "stage i+3" into the ring slot of stage i-1, whose last
     // reader finished before the barrier that ended body i-1; beyond the last stage that is the last
@@ -464,8 +482,8 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
             const int64_t off = ((int64_t)pid_next * a.geo.Hkv + g) * 4096 + (wave & 1) * 2048;
             cp_lds_k = lds_address(lds.k[(i + 3) % kPfRing]) + wave * 2048;
             cp_lds_v = lds_address(lds.v[(i + 3) % kPfRing]) + wave * 2048;
-            cp_k = (const char*)a.k_cache + off;
-            cp_v = (const char*)a.v_cache + off;
+            cp_k = kbase + off;
+            cp_v = vbase + off;
         } else {
             if (i + 2 < n_stage) {
                 // (the thread index goes through an opaque copy: the LDS and cache offsets derived from it are
@@ -498,9 +516,9 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     if constexpr (kCopy) {
         const int32_t p0 = page_id(0), p1 = page_id(1), p2 = page_id(2);
         pid_next = page_id(3);
-        stage_copy_bf16(a, 0, p0, g, wave, lane, lds);
-        if (n_stage > 1) stage_copy_bf16(a, 1, p1, g, wave, lane, lds);
-        if (n_stage > 2) { stage_copy_bf16(a, 2, p2, g, wave, lane, lds); pf_wait_copies<kCopiesPerStage>(); }
+        stage_copy_bf16(kbase, vbase, a.geo.Hkv, 0, p0, g, wave, lane, lds);
+        if (n_stage > 1) stage_copy_bf16(kbase, vbase, a.geo.Hkv, 1, p1, g, wave, lane, lds);
+        if (n_stage > 2) { stage_copy_bf16(kbase, vbase, a.geo.Hkv, 2, p2, g, wave, lane, lds); pf_wait_copies<kCopiesPerStage>(); }
         else pf_wait_copies<0>();
     } else {
         const int32_t p0 = page_id(0), p1 = page_id(1), p2 = page_id(2);
@@ -546,7 +564,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     {                                                      // V operands of the first slots of the first iteration
         constexpr int kColdHead[4] = {0, 1, 2, 8};
 #pragma unroll
-        for (int p = 0; p < kPfLookahead<KT>; ++p)
+        for (int p = 0; p < kPfLookahead<KT, WIDE>; ++p)
             if (kColdHead[p] < 8) vpre[kColdHead[p]] = lds16(vptr(0) + kColdHead[p] * 1024);
     }
     for (; i < n_plain; ++i) {
@@ -579,7 +597,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     const int tid_o = opaque(tid), wave_o = __builtin_amdgcn_readfirstlane(tid_o >> 6), lane_o = tid_o & 63,
               h_o = lane_o >> 5, n_o = lane_o & 31;
     unsigned char* ob = (unsigned char*)&lds + wave_o * (32 * kOutStride);
-    const float vscale = (sizeof(KT) == 1) ? a.v_scale[g] : 1.0f;
+    const float vscale = fp8_cache ? as_constant(a.v_scale)[g] : 1.0f;
     const float l_row = pair32_sum(l_part);
     const float inv = vscale / l_row;
 #pragma unroll

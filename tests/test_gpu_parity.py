@@ -173,6 +173,39 @@ def test_mixed_batch_persistent_and_separate_launches(persistent, kv):
     ctx.close()
 
 
+@pytest.mark.parametrize("mode", [2, 1, 0])
+def test_fp8_prefill_widened_pages_and_in_tile_widening_agree(mode):
+    """fp8 cache: the prefill tiles read bf16 copies of the chunk sequences' pages made once per pass (default)
+    or widen the cache themselves (option 0, or more pages than the option allows); both must match the oracle
+    and each other bit for bit (the conversion is exact), in every launch mode, with ragged page tails."""
+    import paper_2512_03416_amd as ts
+    shape = AttnShape(32, 8, 128, "bf16", "fp8")
+    q = [1] * 30 + [333, 1000, 64, 2] + [1] * 9
+    rng = np.random.default_rng(6)
+    c = list(rng.integers(1, 2500, size=30)) + [333 + 1111, 1000, 64 + 15, 2 + 640] + list(rng.integers(1, 900, size=9))
+    mk = lambda: make_batch(shape, q, c, seed=45, pool_rule=1.25, value_mult=1.0)
+    g = gpu()
+    b = mk()
+    info = ts.plan_describe(g.make_desc(b), b.q_lens, b.ctx_lens)
+    chunk_pages = sum(-(-cl // 16) for ql, cl in zip(q, c) if ql > 1)
+    assert info.widened_pages == chunk_pages and info.mixed_mode == 2
+    wide = binding_export(g.make_desc(b), b, "widen")
+    assert len(wide) == chunk_pages and sorted(set(wide[:, 0].tolist())) == [30, 31, 32, 33]
+    ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
+    outs = []
+    for pages in (16384, 0, chunk_pages - 1):
+        out, gk, gv = g.run_batch(mk(), options={"mixed_mode": mode, "prefill_widen_pages": pages})
+        assert same_bytes(gk, rk) and same_bytes(gv, rv)
+        assert float(np.max(np.abs(out - ref))) <= TOL["fp8"]
+        outs.append(out)
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[1], outs[2])
+
+
+def binding_export(desc, b, which):
+    from paper_2512_03416_amd import binding
+    return binding.plan_export(desc, b.q_lens, b.ctx_lens, which)
+
+
 def test_prefill_generic_path_agrees():
     shape = AttnShape(8, 2, 128, "bf16", "bf16")
     b = make_batch(shape, [150, 1], [190, 50], seed=43, value_mult=0.5)
