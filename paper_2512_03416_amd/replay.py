@@ -12,6 +12,13 @@ queue length, TTFT of the requests whose first token came out in that second.
     python -m paper_2512_03416_amd.replay --seconds 20 --step-at 10 --rps 1,10
 
 No traces, weights or datasets: K/V/Q contents are random, only the batch structure is replayed.
+
+Scheduling rules (readings where the paper is silent): a request becomes the prefill task when a table row
+and pages for its input + output are free, in arrival order, the head of the queue is never overtaken; the
+iteration that finishes a prefill releases the request's first token, and the request joins the decode batch
+from the next iteration on; a request is done after out_len tokens (the first one counts).  `replay` can be
+given the time of a pass as a function of the batch (instead of measuring it), which makes the schedule a
+function of the arrival list alone, and a callback that sees every pass.
 """
 from __future__ import annotations
 
@@ -68,11 +75,14 @@ class Decoder:
         self.desc = ts.Desc.make(hq, hkv, 128, "bf16", kv, self.num_pages, self.max_pages)
         self.ctx = ts.Context(self.desc)
         nbytes = ts.cache_bytes(self.desc)
-        self.kc = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
-        self.vc = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        self.kc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+        self.vc = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
         gen = torch.Generator(device="cuda")
         gen.manual_seed(seed)
-        T = chunk_size
+        # a pass carries the decode batch (at most max_resident rows) plus a chunk that fills what the chunk size
+        # leaves: never more than max(chunk_size, max_resident) rows
+        T = max(chunk_size, max_resident)
+        self.rows = T
         self.q = (torch.randn(T, hq, 128, generator=gen, device="cuda") * 0.5).to(torch.bfloat16)
         self.k = (torch.randn(T, hkv, 128, generator=gen, device="cuda") * 0.5).to(torch.bfloat16)
         self.v = (torch.randn(T, hkv, 128, generator=gen, device="cuda") * 0.5).to(torch.bfloat16)
@@ -101,6 +111,8 @@ class Decoder:
         """One attention pass over the given sequences; returns its wall time in seconds."""
         torch = self.torch
         T = int(sum(q_lens))
+        if T > self.rows:
+            raise ValueError(f"a pass of {T} rows exceeds the {self.rows} rows of the buffers")
         ctx_lens = [r.cached + n for r, n in zip(seqs, q_lens)]
         bt = torch.from_numpy(self.table[[r.row for r in seqs]]).cuda()
         torch.cuda.synchronize()
@@ -110,12 +122,17 @@ class Decoder:
                                        self.out[:T])
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        self.last = dict(bt=bt, q_lens=np.asarray(q_lens, np.int32), ctx_lens=np.asarray(ctx_lens, np.int32), T=T)
         for r, n in zip(seqs, q_lens):
             r.cached += n
         return dt
 
 
-def replay(args) -> dict:
+def replay(args, time_fn=None, on_pass=None, record=False) -> dict:
+    """time_fn(q_lens, ctx_lens) -> seconds: the time charged for a pass instead of the measured one.
+    on_pass(iteration, decoder): called after every pass (decoder.last describes it).
+    record: the result also lists every iteration's (request ids, q_lens, ctx_lens) and the first-token and
+    completion times by request id."""
     rng = np.random.default_rng(args.seed)
     rps_before, rps_after = (float(x) for x in args.rps.split(","))
     hq, hkv = (int(x) for x in args.heads.split(","))
@@ -130,6 +147,7 @@ def replay(args) -> dict:
     win = [dict(t=i, arrivals=0, prefill_tokens=0, decode_tokens=0, first_tokens=0, ttft_sum=0.0, queue=0,
                 iterations=0, pass_ms_sum=0.0) for i in range(n_windows)]
     iterations = pf_rows = dec_rows = 0
+    log = []
     while now < args.seconds + args.drain:
         while nxt < len(reqs) and reqs[nxt].arrival <= now:
             queue.append(reqs[nxt])
@@ -140,7 +158,7 @@ def replay(args) -> dict:
         seqs, q_lens = list(decoding), [1] * len(decoding)
         n_pf = 0
         if task is not None:
-            n_pf = min(task.in_len - task.cached, args.chunk_size - len(decoding))
+            n_pf = max(0, min(task.in_len - task.cached, args.chunk_size - len(decoding)))   # decode rows come first
             if n_pf > 0:
                 seqs.append(task)
                 q_lens.append(n_pf)
@@ -149,6 +167,12 @@ def replay(args) -> dict:
             now = max(now + 1e-3, nxt_t)                   # idle until the next arrival
             continue
         dt = dec.run(seqs, q_lens)
+        if time_fn is not None:
+            dt = float(time_fn(list(q_lens), [int(x) for x in dec.last["ctx_lens"]]))
+        if record:
+            log.append((tuple(r.rid for r in seqs), tuple(q_lens), tuple(int(x) for x in dec.last["ctx_lens"])))
+        if on_pass is not None:
+            on_pass(iterations, dec)
         iterations += 1
         pf_rows += n_pf if n_pf > 1 else 0                 # the library counts a one-token chunk as a decode row
         dec_rows += len(decoding) + (1 if n_pf == 1 else 0)
@@ -195,11 +219,17 @@ def replay(args) -> dict:
                   prefill_tokens_submitted=pf_rows, decode_tokens_submitted=dec_rows,
                   kernel_prefill_tok_per_s=vel.prefill_tok_per_s, kernel_decode_tok_per_s=vel.decode_tok_per_s,
                   series=series)
+    if record:
+        result["iteration_log"] = log
+        result["first_token_at"] = {r.rid: r.first_token_at for r in reqs if r.first_token_at is not None}
+        result["done_at"] = {r.rid: r.done_at for r in reqs if r.done_at is not None}
+        result["arrivals"] = [(r.arrival, r.in_len, r.out_len) for r in reqs]
+        result["num_pages"], result["max_pages_per_seq"] = dec.num_pages, dec.max_pages
     dec.ctx.close()
     return result
 
 
-def main(argv=None):
+def main(argv=None, **replay_kwargs):
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--heads", default="32,8")
     ap.add_argument("--kv", default="bf16", choices=["bf16", "fp8"])
@@ -220,13 +250,13 @@ def main(argv=None):
     import torch
     if not torch.cuda.is_available():
         raise SystemExit("the replay measures on a GPU")
-    res = replay(args)
+    res = replay(args, **replay_kwargs)
     for s in res["series"]:
         ttft = f"{s['mean_ttft_s'] * 1e3:7.0f} ms" if s["mean_ttft_s"] is not None else "      -   "
         print(f"[replay] t={s['t']:3d}s arrivals {s['arrivals']:3d}  prefill {s['prefill_tok_per_s']:7d} tok/s  decode "
               f"{s['decode_tok_per_s']:6d} tok/s  queue {s['queue']:3d}  TTFT {ttft}  pass "
               f"{(s['mean_pass_ms'] or 0):6.3f} ms", file=sys.stderr)
-    print(json.dumps(res))
+    print(json.dumps({k: v for k, v in res.items() if k not in ("iteration_log", "first_token_at", "done_at", "arrivals")}))
     return res
 
 

@@ -483,6 +483,59 @@ def test_burst_replay_accounts_for_every_token():
     assert res["completed"] >= res["first_tokens"] - 40 and res["completed"] > 0
 
 
+REPLAY_ARGS = ["--heads", "8,2", "--seconds", "3", "--step-at", "1", "--rps", "2,12", "--drain", "2",
+               "--in-median", "120", "--in-max", "600", "--out-median", "12", "--out-max", "40",
+               "--layers", "2", "--other-ms", "4"]
+
+
+@pytest.mark.parametrize("chunk,resident", [(256, 64), (24, 48)])
+def test_burst_replay_against_the_scheduler_oracle_and_the_attention_oracle(chunk, resident):
+    """The replay with a given pass time (1 us per query token + 20 us) forms exactly the batches of the
+    scheduler oracle, iteration by iteration, with the same first-token and completion times; a CPU mirror of
+    the cache follows every pass through the oracle's append, and every 9th pass is recomputed by the attention
+    oracle: outputs within the bf16 bar, the cache pages of every sequence of the pass byte-equal.
+    (24, 48): the chunk size is below the number of resident requests, so the decode batch alone can exceed it.)"""
+    from oracle import replay as orp
+    from paper_2512_03416_amd import replay
+    time_fn = lambda q, c: 1e-6 * sum(q) + 20e-6
+    Hq, Hkv, D = 8, 2, 128
+    state = dict(kc=None, vc=None, checked=0, worst=0.0)
+
+    def on_pass(i, dec):
+        if state["kc"] is None:
+            state["kc"] = oracle.new_cache(dec.num_pages, Hkv, D, "bf16")
+            state["vc"] = oracle.new_cache(dec.num_pages, Hkv, D, "bf16")
+        last = dec.last
+        T, bt = last["T"], last["bt"].cpu().numpy()
+        args = (Hq, Hkv, D, "bf16", "bf16")
+        oracle.kv_append(*args, oracle.raw(dec.k[:T]), oracle.raw(dec.v[:T]), state["kc"], state["vc"], None, None, bt,
+                         last["q_lens"], last["ctx_lens"], dec.num_pages)
+        if i % 9:
+            return
+        ref = oracle.mixed_paged_attention(*args, oracle.raw(dec.q[:T]), state["kc"], state["vc"], None, None, bt,
+                                           last["q_lens"], last["ctx_lens"], 1.0 / np.sqrt(D), dec.num_pages)
+        out = dec.out[:T].double().cpu().numpy()
+        state["worst"] = max(state["worst"], float(np.max(np.abs(out - ref))))
+        page_elems = Hkv * 16 * D
+        ids = np.unique(np.concatenate([bt[s, :-(-int(c) // 16)] for s, c in enumerate(last["ctx_lens"])]))
+        gk = dec.kc.view(torch.int16).view(-1, page_elems)[torch.from_numpy(ids.astype(np.int64)).cuda()].cpu().numpy()
+        gv = dec.vc.view(torch.int16).view(-1, page_elems)[torch.from_numpy(ids.astype(np.int64)).cuda()].cpu().numpy()
+        assert np.array_equal(gk.view(np.uint16), state["kc"].reshape(-1, page_elems)[ids]), f"K pages differ at pass {i}"
+        assert np.array_equal(gv.view(np.uint16), state["vc"].reshape(-1, page_elems)[ids]), f"V pages differ at pass {i}"
+        state["checked"] += 1
+
+    res = replay.main(REPLAY_ARGS + ["--chunk-size", str(chunk), "--max-resident", str(resident)],
+                      time_fn=time_fn, on_pass=on_pass, record=True)
+    its, first, done = orp.schedule(res["arrivals"], chunk_size=chunk, max_resident=resident,
+                                    num_pages=res["num_pages"], max_pages_per_seq=res["max_pages_per_seq"],
+                                    pass_time=time_fn, layers=2, other_s=4e-3, horizon_s=5.0)
+    assert len(its) > 50 and res["iteration_log"] == its
+    assert res["first_token_at"] == first and res["done_at"] == done
+    assert state["checked"] >= 6 and state["worst"] <= TOL["bf16"]
+    print(f"       {len(its)} iterations equal to the scheduler oracle, {state['checked']} passes recomputed, "
+          f"max abs err {state['worst']:.3e}", flush=True)
+
+
 def test_mfma_calibration_stream_runs_and_counts_its_work():
     """The calibration launch returns, leaves the result word alone and reports
     CUs x 8 waves x iters x 16 MFMAs x 32768 flop."""
