@@ -192,6 +192,10 @@ const char *ts_last_error(const ts_ctx *ctx);
  *                         from it take mode 1 by themselves;
  *                         1 (TS_MIXED_ONE_KERNEL) = decode items and prefill tiles share the workgroups of one
  *                         persistent launch;  0 (TS_MIXED_SEPARATE) = decode kernel, then prefill kernel
+ *   "prefill_split_min_keys"  a batch whose prefill tiles cannot give every CU a workgroup (a short chunk over a
+ *                         long prefix) has its tiles cut along the keys, below their first query position, into
+ *                         parts of at least this many keys (multiple of 64, default 1024; 0 = never); the
+ *                         parts' partial results are merged in part order by a small launch
  *   "prefill_widen_pages" fp8 caches: every tile of a prefill chunk reads the chunk's whole prefix, so the pages
  *                         of the chunks' sequences are widened from e4m3 to bf16 once per pass, into scratch of
  *                         8 KiB * num_kv_heads per page, and the tiles read that copy; a batch whose chunk
@@ -242,6 +246,7 @@ typedef struct {
     int32_t mixed_mode;         /* TS_MIXED_* the batch is launched with (SEPARATE if one kind only) */
     int32_t reserved;
     int64_t widened_pages;      /* fp8 caches: pages widened to bf16 before the prefill tiles run   */
+    int64_t prefill_parts;      /* partial results of prefill tiles cut along the keys (0 = none cut) */
 } ts_plan_info;
 
 int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
@@ -251,7 +256,9 @@ int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int3
  * int32 words); returns the number of records, or a negative error.  Lists and record layouts:
  *   TS_LIST_DECODE  (row, seq, n_keys, page_begin, page_end, partial_slot or -1, 0, 0)
  *   TS_LIST_COMBINE (row, partial_begin, n_split, 0)
- *   TS_LIST_PREFILL (seq, row0, q_len, prefix, tok_begin, tok_count, ctx_len, 0)
+ *   TS_LIST_PREFILL (seq, row0, q_len, prefix, tok_begin, tok_count, ctx_len, part or -1, kv_begin, kv_end, 0, 0)
+ *                   one causal tile, or one part [kv_begin, kv_end) of a tile cut along the keys
+ *   TS_LIST_PFCOMBINE (prefill item of the tile, first part, parts, 0)   cut tiles to merge
  *   TS_LIST_PFMAP   (prefill tile or -1, kv_head)       launch order, workgroup i -> die i % 8
  *   TS_LIST_ROWS    (row, seq, n_keys, 0)
  *   TS_LIST_QUEUE   (kind 0 decode / 1 prefill, item, kv_head, 0)   per-die queues, concatenated (mode 1: both
@@ -264,7 +271,7 @@ int ts_plan_describe(const ts_attn_desc *desc, const int32_t *q_lens, const int3
  * option of that name, or -1 for the default. */
 enum { TS_LIST_DECODE = 0, TS_LIST_COMBINE = 1, TS_LIST_PREFILL = 2, TS_LIST_PFMAP = 3, TS_LIST_ROWS = 4,
        TS_LIST_QUEUE = 5, TS_LIST_QOFF = 6, TS_LIST_APPEND = 7,
-       TS_LIST_APPEND_ROWS = 8, TS_LIST_WIDEN = 9 };
+       TS_LIST_APPEND_ROWS = 8, TS_LIST_WIDEN = 9, TS_LIST_PFCOMBINE = 10 };
 int64_t ts_plan_export(const ts_attn_desc *desc, const int32_t *q_lens, const int32_t *ctx_lens,
                        int num_seqs, int32_t split_pages, int32_t wg_slots, int32_t mixed_mode, int which,
                        int32_t *out, int64_t capacity);

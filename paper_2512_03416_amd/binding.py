@@ -58,7 +58,7 @@ class PlanInfo(ctypes.Structure):
                 ("n_generic_rows", ctypes.c_int32), ("split_pages", ctypes.c_int32),
                 ("tile_tokens", ctypes.c_int32), ("partial_slots", ctypes.c_int64),
                 ("ctx_pages", ctypes.c_int64), ("mixed_mode", ctypes.c_int32), ("reserved", ctypes.c_int32),
-                ("widened_pages", ctypes.c_int64)]
+                ("widened_pages", ctypes.c_int64), ("prefill_parts", ctypes.c_int64)]
 
 
 _lib = None
@@ -160,9 +160,9 @@ def plan_describe(desc: Desc, q_lens, ctx_lens, split_pages: int = 0) -> PlanInf
     return info
 
 
-PLAN_LISTS = {"decode": (0, 8), "combine": (1, 4), "prefill": (2, 8), "pfmap": (3, 2), "rows": (4, 4),
+PLAN_LISTS = {"decode": (0, 8), "combine": (1, 4), "prefill": (2, 12), "pfmap": (3, 2), "rows": (4, 4),
               "queue": (5, 4), "qoff": (6, 1), "append": (7, 8),
-              "append_rows": (8, 4), "widen": (9, 2)}
+              "append_rows": (8, 4), "widen": (9, 2), "pfcombine": (10, 4)}
 
 
 def plan_export(desc: Desc, q_lens, ctx_lens, which: str, split_pages: int = 0, wg_slots: int = 0,

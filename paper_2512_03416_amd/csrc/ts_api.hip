@@ -78,6 +78,7 @@ struct ts_ctx {
     char* d_work = nullptr;  size_t work_cap = 0;
     float* d_part_o = nullptr; float* d_part_ml = nullptr; int64_t part_cap = 0;
     int32_t* d_q_ctr = nullptr;      // queue heads of the persistent kernel (zero between launches)
+    float* d_pf_part_o = nullptr; float* d_pf_part_ml = nullptr; int64_t pf_part_cap = 0;   // partial results of cut prefill tiles
     char* d_wide_k = nullptr; char* d_wide_v = nullptr; int64_t wide_cap = 0;   // fp8 caches: widened pages (capacity in pages)
     unsigned char* d_static = nullptr;  // this GPU's copy of the static scratch array
     bool static_call = false;        // the call in progress must not allocate (uses d_static)
@@ -208,6 +209,24 @@ int ensure_partials(ts_ctx* c, int64_t slots)
     return TS_OK;
 }
 
+// Partial results of prefill tiles cut along the keys: `parts` results of 256 rows for every KV head.
+int ensure_pf_parts(ts_ctx* c, int64_t parts)
+{
+    if (parts <= c->pf_part_cap) return TS_OK;
+    const size_t rows = (size_t)c->desc.num_kv_heads * kPfPartRows;
+    const int64_t cap = std::max<int64_t>(parts * 2, 64);
+    TS_HIP(c, hipDeviceSynchronize());
+    if (c->d_pf_part_o) TS_HIP(c, hipFree(c->d_pf_part_o));
+    if (c->d_pf_part_ml) TS_HIP(c, hipFree(c->d_pf_part_ml));
+    c->d_pf_part_o = c->d_pf_part_ml = nullptr; c->pf_part_cap = 0;
+    if (hipMalloc((void**)&c->d_pf_part_o, (size_t)cap * rows * c->desc.head_dim * sizeof(float)) != hipSuccess ||
+        hipMalloc((void**)&c->d_pf_part_ml, (size_t)cap * rows * 2 * sizeof(float)) != hipSuccess)
+        return fail(c, TS_ERR_NOMEM, "scratch for the partial results of cut prefill tiles could not be allocated");
+    c->pf_part_cap = cap;
+    c->n_alloc += 2;
+    return TS_OK;
+}
+
 // fp8 caches: scratch for the bf16 copies of `pages` pages (K and V).
 int ensure_wide(ts_ctx* c, int64_t pages)
 {
@@ -285,7 +304,7 @@ __global__ __launch_bounds__(256) void check_pages_kernel(const SeqMeta* __restr
 }
 
 struct WorkLayout {
-    size_t seqs, dec, cmb, pf, pfmap, rows, queue, q_off, apt, apr, wide, wide_base, total;
+    size_t seqs, dec, cmb, pf, pfcmb, pfmap, rows, queue, q_off, apt, apr, wide, wide_base, total;
 };
 
 WorkLayout layout_of(const Plan& p)
@@ -296,6 +315,7 @@ WorkLayout layout_of(const Plan& p)
     w.dec = o;  o = align16(o + p.dec.size() * sizeof(DecItem));
     w.cmb = o;  o = align16(o + p.cmb.size() * sizeof(CmbItem));
     w.pf = o;   o = align16(o + p.pf.size() * sizeof(PfItem));
+    w.pfcmb = o; o = align16(o + p.pfcmb.size() * sizeof(PfCmb));
     w.pfmap = o; o = align16(o + p.pfmap.size() * sizeof(PfSlot));
     w.rows = o; o = align16(o + p.rows.size() * sizeof(RowItem));
     w.queue = o; o = align16(o + p.queue.size() * sizeof(QItem));
@@ -326,6 +346,7 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w, UploadJob* defer
     if (!p.dec.empty()) memcpy(h + w.dec, p.dec.data(), p.dec.size() * sizeof(DecItem));
     if (!p.cmb.empty()) memcpy(h + w.cmb, p.cmb.data(), p.cmb.size() * sizeof(CmbItem));
     if (!p.pf.empty()) memcpy(h + w.pf, p.pf.data(), p.pf.size() * sizeof(PfItem));
+    if (!p.pfcmb.empty()) memcpy(h + w.pfcmb, p.pfcmb.data(), p.pfcmb.size() * sizeof(PfCmb));
     if (!p.pfmap.empty()) memcpy(h + w.pfmap, p.pfmap.data(), p.pfmap.size() * sizeof(PfSlot));
     if (!p.rows.empty()) memcpy(h + w.rows, p.rows.data(), p.rows.size() * sizeof(RowItem));
     if (!p.queue.empty()) memcpy(h + w.queue, p.queue.data(), p.queue.size() * sizeof(QItem));
@@ -529,6 +550,8 @@ extern "C" int ts_destroy(ts_ctx* c)
     if (c->d_part_o) (void)hipFree(c->d_part_o);
     if (c->d_part_ml) (void)hipFree(c->d_part_ml);
     if (c->d_q_ctr) (void)hipFree(c->d_q_ctr);
+    if (c->d_pf_part_o) (void)hipFree(c->d_pf_part_o);
+    if (c->d_pf_part_ml) (void)hipFree(c->d_pf_part_ml);
     if (c->d_wide_k) (void)hipFree(c->d_wide_k);
     if (c->d_wide_v) (void)hipFree(c->d_wide_v);
     if (c->side) (void)hipStreamDestroy(c->side);
@@ -559,14 +582,18 @@ extern "C" int ts_reserve(ts_ctx* c, int64_t max_tokens, int64_t max_seqs, int64
     const size_t L = c->opt.split_pages > 0 ? (size_t)c->opt.split_pages : 32;
     const size_t TT = (size_t)std::max<int32_t>(1, c->opt.tile_tokens > 0 ? c->opt.tile_tokens : prefill_tile_tokens(c->desc));
     const size_t items = P / L + S;
-    const size_t tiles = T / TT + S;
-    const size_t bytes = (S + 1) * sizeof(SeqMeta) + items * (sizeof(DecItem) + sizeof(CmbItem)) + tiles * sizeof(PfItem) +
+    const size_t tiles = T / TT + S + (size_t)c->opt.n_cu;      // (cutting tiles along the keys adds at most one item per CU)
+    const size_t bytes = (S + 1) * sizeof(SeqMeta) + items * (sizeof(DecItem) + sizeof(CmbItem)) + tiles * (sizeof(PfItem) + sizeof(PfCmb)) +
                          tiles * Hkv * xcds * sizeof(PfSlot) + T * sizeof(RowItem) +
                          (items + tiles) * Hkv * sizeof(QItem) + (xcds + 1) * sizeof(int32_t) +
                          (T / kPage + 2 * S) * sizeof(AppTile) + T * sizeof(AppRow) +
                          (size_t)std::min<int64_t>((int64_t)P, c->opt.widen_pages) * sizeof(WideItem) + S * sizeof(int32_t) + 16 * 16;
     int rc = ensure_work(c, bytes);
     if (rc != TS_OK) return rc;
+    if (desc_uses_mfma(c->desc) && c->opt.pf_split_min_keys > 0) {
+        rc = ensure_pf_parts(c, (int64_t)c->opt.n_cu);
+        if (rc != TS_OK) return rc;
+    }
     if (c->desc.kv_dtype == TS_FP8_E4M3 && desc_uses_mfma(c->desc) && c->opt.widen_pages > 0) {
         rc = ensure_wide(c, std::min<int64_t>((int64_t)P, c->opt.widen_pages));
         if (rc != TS_OK) return rc;
@@ -606,6 +633,11 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         c->opt.mixed_mode = (int32_t)value;
         return TS_OK;
     }
+    if (!strcmp(name, "prefill_split_min_keys")) {
+        if (value < 0 || value > (1 << 24) || value % 64) return fail(c, TS_ERR_INVALID_ARG, "prefill_split_min_keys must be a multiple of 64");
+        c->opt.pf_split_min_keys = (int32_t)value;
+        return TS_OK;
+    }
     if (!strcmp(name, "prefill_widen_pages")) {
         if (value < 0 || value > ((int64_t)1 << 24)) return fail(c, TS_ERR_INVALID_ARG, "prefill_widen_pages out of range");
         c->opt.widen_pages = value;
@@ -638,6 +670,7 @@ extern "C" int ts_get_option(const ts_ctx* c, const char* name, int64_t* value)
     else if (!strcmp(name, "mixed_mode")) *value = c->opt.mixed_mode;
     else if (!strcmp(name, "xcd_count")) *value = c->opt.xcds;
     else if (!strcmp(name, "prefill_widen_pages")) *value = c->opt.widen_pages;
+    else if (!strcmp(name, "prefill_split_min_keys")) *value = c->opt.pf_split_min_keys;
     else if (!strcmp(name, "validate_block_table")) *value = c->validate_pages ? 1 : 0;
     else if (!strcmp(name, "kernel_timing")) *value = c->timing;
     else if (!strcmp(name, "scratch_allocations")) *value = c->n_alloc;
@@ -713,7 +746,10 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
     if (c->dec_slots > 0) c->opt.wg_slots = c->dec_slots;
     {
         PlanOptions opt = c->opt;
-        if (c->static_call) opt.widen_pages = 0;           // (no scratch for widened pages: the tiles widen themselves)
+        if (c->static_call) {                              // (no scratch for widened pages or for partial results of cut tiles)
+            opt.widen_pages = 0;
+            opt.pf_split_min_keys = 0;
+        }
         build_plan(c->desc, q_lens, ctx_lens, num_seqs, opt, &c->plan);
     }
     const Plan& p = c->plan;
@@ -723,6 +759,10 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
     if (rc != TS_OK) return rc;
     if (!p.wide.empty()) {
         rc = ensure_wide(c, (int64_t)p.wide.size());
+        if (rc != TS_OK) return rc;
+    }
+    if (p.info.prefill_parts > 0) {
+        rc = ensure_pf_parts(c, p.info.prefill_parts);
         if (rc != TS_OK) return rc;
     }
     const WorkLayout w = layout_of(p);
@@ -765,6 +805,8 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
     a.dec = (const DecItem*)(wb + w.dec);   a.n_dec = (int32_t)p.dec.size();
     a.cmb = (const CmbItem*)(wb + w.cmb);   a.n_cmb = (int32_t)p.cmb.size();
     a.pf = (const PfItem*)(wb + w.pf);      a.n_pf = (int32_t)p.pf.size();
+    a.pfcmb = (const PfCmb*)(wb + w.pfcmb); a.n_pfcmb = (int32_t)p.pfcmb.size();
+    a.pf_part_o = c->d_pf_part_o; a.pf_part_ml = c->d_pf_part_ml;
     a.pfmap = (const PfSlot*)(wb + w.pfmap); a.n_pfmap = (int32_t)p.pfmap.size();
     a.rows = (const RowItem*)(wb + w.rows); a.n_rows = (int32_t)p.rows.size();
     a.queue = (const QItem*)(wb + w.queue); a.q_off = (const int32_t*)(wb + w.q_off);
@@ -815,6 +857,8 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
         e = (hipError_t)timed_launch(c, TS_K_PREFILL, a.n_pf > 0, st, [&] { return launch_prefill(a, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "prefill launch");
     }
+    e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_pfcmb > 0, st, [&] { return launch_prefill_combine(a, stream); });
+    if (e != hipSuccess) return hip_fail(c, e, "prefill combine launch");
     e = (hipError_t)timed_launch(c, TS_K_ROWS, a.n_rows > 0, st, [&] { return launch_rows(a, stream); });
     if (e != hipSuccess) return hip_fail(c, e, "rows launch");
 

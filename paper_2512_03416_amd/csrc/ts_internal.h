@@ -44,8 +44,20 @@ struct PfItem {           // a causal tile of a prefill chunk; launched once per
     int32_t tok_begin;    // tile covers chunk tokens [tok_begin, tok_begin + tok_count)
     int32_t tok_count;
     int32_t ctx_len;
+    int32_t part;         // -1: the item covers all keys of the tile and writes the output rows; else it covers the
+                          // keys [kv_begin, kv_end) only and writes partial result number `part`
+    int32_t kv_begin;     // multiple of 64, at most the tile's first query position: every row sees key kv_begin
+    int32_t kv_end;       // multiple of 64, or INT32_MAX for "up to the tile's last key"
+    int32_t pad0, pad1;
+};
+
+struct PfCmb {            // a tile whose key range was cut: its partial results part_begin .. part_begin + n_part - 1
+    int32_t item;         // index of the tile's first part in the prefill list (for the rows it covers)
+    int32_t part_begin;
+    int32_t n_part;
     int32_t pad;
 };
+constexpr int kPfPartRows = 256;   // rows of one prefill partial result (a whole tile)
 
 struct PfSlot {           // workgroup -> (prefill tile, KV head); item < 0 = nothing to do
     int32_t item;
@@ -92,6 +104,7 @@ struct Plan {
     std::vector<DecItem> dec;
     std::vector<CmbItem> cmb;
     std::vector<PfItem> pf;
+    std::vector<PfCmb> pfcmb;        // tiles cut along the keys: what to merge
     std::vector<PfSlot> pfmap;       // launch order of the prefill workgroups (XCD-aware)
     std::vector<AppTile> apt;        // page-wise append work of the chunks
     std::vector<AppRow> apr;         // token-wise append work: short sequences, and everything the page-wise kernel does not cover
@@ -112,6 +125,7 @@ struct PlanOptions {
     bool generic_only = false;  // every row through the generic kernel
     bool prefill_generic = false;
     int32_t tile_tokens = 0;    // query tokens per prefill tile
+    int32_t pf_split_min_keys = 1024;   // shortest key range of a cut prefill tile (multiple of 64; 0 = never cut)
     int64_t widen_pages = 16384; // fp8 caches: most pages of prefill sequences that are widened to bf16 per pass (0 = never)
 };
 
@@ -176,6 +190,10 @@ struct AttnArgs {
     int32_t dec_nbuf;          // KV tiles in flight per decode wave (2..4)
     int32_t mixed_wgs;         // workgroups of the persistent kernel that are resident on the GPU at once
     int32_t n_cu;              // compute units of the GPU
+    // prefill tiles cut along the keys: partial results o [part][kv head][256 rows][D] fp32 (unnormalised),
+    // ml [part][kv head][256 rows][2] = (reference maximum in log2 units, weight sum)
+    const PfCmb* pfcmb; int32_t n_pfcmb;
+    float* pf_part_o; float* pf_part_ml;
     // split-K partials: o [slot][Hq][D] fp32 (unnormalised), ml [slot][Hq][2] = (max, sum) in log2 units
     float* part_o; float* part_ml;
 };
@@ -193,5 +211,6 @@ int launch_widen(const AttnArgs& a, void* wide_k, void* wide_v, void* stream);
 int launch_prefill(const AttnArgs& a, void* stream);
 int launch_mixed(const AttnArgs& a, void* stream);
 int launch_prefill_resident(const AttnArgs& a, void* stream);
+int launch_prefill_combine(const AttnArgs& a, void* stream);
 
 }  // namespace ts

@@ -42,6 +42,69 @@ __global__ __launch_bounds__(256) void widen_kernel(AttnArgs a, uint16_t* __rest
     *(uint4*)(vd + t * 8) = make_uint4(v0.x, v0.y, v1.x, v1.y);
 }
 
+// Merge of the parts of a tile that was cut along the keys, in part order:
+//   M = max m_i,  out = sum o_i 2^(m_i - M) / sum l_i 2^(m_i - M)  (times the V scale of an fp8 cache).
+// One workgroup per (cut tile, KV head, 32 rows); 32 lanes hold the 128 dims of a row, 8 rows per step.  The
+// partial rows of up to eight parts are requested together, then added one after the other (the sums keep
+// their order).
+constexpr int kPfCmbRows = 32;
+__global__ __launch_bounds__(256) void prefill_combine_kernel(AttnArgs a)
+{
+    constexpr int D = 128, kBatch = 8, kGroups = kPfPartRows / kPfCmbRows;
+    const int Hkv = a.geo.Hkv, G = a.geo.G, Hq = a.geo.Hq;
+    const int grp = blockIdx.x % kGroups, g = (blockIdx.x / kGroups) % Hkv, ci = blockIdx.x / (kGroups * Hkv);
+    const int32_t TS_CONSTANT* c = as_constant((const int32_t*)(a.pfcmb + ci));
+    const int item = c[0], part0 = c[1], n_part = c[2];
+    const int32_t TS_CONSTANT* it = as_constant((const int32_t*)(a.pf + item));
+    const int row0 = it[1], tok_begin = it[4], tok_count = it[5];
+    const float vscale = a.geo.kv_dtype == TS_FP8_E4M3 ? a.v_scale[g] : 1.0f;
+    const int lane = threadIdx.x & 31, sub = threadIdx.x >> 5;
+    const int64_t part_step = (int64_t)Hkv * kPfPartRows;          // rows between two parts of one (tile, head)
+#pragma unroll
+    for (int step = 0; step < kPfCmbRows / 8; ++step) {
+        const int rho = grp * kPfCmbRows + step * 8 + sub;
+        const int t = rho / G, hd = rho - t * G;
+        if (t >= tok_count) continue;
+        const int64_t slot0 = ((int64_t)part0 * Hkv + g) * kPfPartRows + rho;
+        float M = -INFINITY;
+        for (int k = 0; k < n_part; ++k) M = fmaxf(M, a.pf_part_ml[(slot0 + k * part_step) * 2]);
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        float L = 0.f;
+        for (int k0 = 0; k0 < n_part; k0 += kBatch) {
+            float2 ml[kBatch];
+            f32x4 v[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int64_t slot = slot0 + min(k0 + j, n_part - 1) * part_step;
+                ml[j] = *(const float2*)(a.pf_part_ml + slot * 2);
+                v[j] = *(const f32x4*)(a.pf_part_o + slot * D + 4 * lane);
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                if (k0 + j < n_part) {
+                    const float w = __builtin_amdgcn_exp2f(ml[j].x - M);
+                    L += ml[j].y * w;
+                    o += v[j] * w;
+                }
+            }
+        }
+        const float inv = vscale / L;
+        uint2 w;
+        w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{o[0] * inv, o[1] * inv}, bf16x2));
+        w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{o[2] * inv, o[3] * inv}, bf16x2));
+        *(uint2*)((uint16_t*)a.out + ((int64_t)(row0 + tok_begin + t) * Hq + g * G + hd) * D + 4 * lane) = w;
+    }
+}
+
+int launch_prefill_combine(const AttnArgs& a, void* stream)
+{
+    if (a.n_pfcmb <= 0) return (int)hipSuccess;
+    if (a.geo.D != 128 || !a.pf_part_o || !a.pf_part_ml) return (int)hipErrorInvalidValue;
+    const unsigned grid = (unsigned)a.n_pfcmb * (unsigned)a.geo.Hkv * (unsigned)(kPfPartRows / kPfCmbRows);
+    hipLaunchKernelGGL(prefill_combine_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
 int launch_widen(const AttnArgs& a, void* wide_k, void* wide_v, void* stream)
 {
     if (a.n_wide <= 0) return (int)hipSuccess;

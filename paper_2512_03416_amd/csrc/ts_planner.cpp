@@ -7,6 +7,7 @@
 // over all CUs; prefill chunks are cut into causal query tiles.  Items are ordered longest first
 // so that the hardware dispatcher, which hands out workgroups in order, balances the tail.
 #include <algorithm>
+#include <climits>
 #include <cstdio>
 #include <cstring>
 
@@ -116,6 +117,11 @@ static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int6
 // are launched next to each other: they walk the stream's pages almost in step, and the pages are
 // fetched from HBM about once instead of once per tile.  Streams are spread over the dies by
 // decreasing work (greedy), longest tiles of a stream first.
+static int64_t pf_keys(const PfItem& t)
+{
+    return std::min(t.prefix + t.tok_begin + t.tok_count, t.kv_end) - t.kv_begin;
+}
+
 static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds, int mixed_mode)
 {
     p.pfmap.clear();
@@ -135,7 +141,7 @@ static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds, int mixed_mode)
             std::vector<int32_t> items;
             while (j < order.size() && p.pf[order[j]].seq == p.pf[order[i]].seq) {
                 const PfItem& it = p.pf[order[j]];
-                work += it.prefix + it.tok_begin + it.tok_count;
+                work += std::min(it.prefix + it.tok_begin + it.tok_count, it.kv_end) - it.kv_begin;
                 items.push_back(order[j]);       // p.pf is sorted longest first, the stable sort keeps that
                 ++j;
             }
@@ -182,7 +188,7 @@ static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds, int mixed_mode)
     for (int x = 0; x < xcds; ++x) {
         double dtot = 0, ptot = 0;
         for (const PfSlot& d : dper[x]) dtot += p.dec[d.item].page_end - p.dec[d.item].page_begin;
-        for (const PfSlot& t : per[x]) ptot += p.pf[t.item].prefix + p.pf[t.item].tok_begin + p.pf[t.item].tok_count;
+        for (const PfSlot& t : per[x]) ptot += pf_keys(p.pf[t.item]);
         size_t di = 0, ti = 0;
         double dacc = 0, pacc = 0;
         while (di < dper[x].size() || ti < per[x].size()) {
@@ -194,7 +200,7 @@ static void map_prefill_to_xcds(Plan& p, int Hkv, int xcds, int mixed_mode)
                 p.queue.push_back(QItem{0, d.item, d.head_kv, 0});
             } else {
                 const PfSlot& t = per[x][ti++];
-                pacc += p.pf[t.item].prefix + p.pf[t.item].tok_begin + p.pf[t.item].tok_count;
+                pacc += pf_keys(p.pf[t.item]);
                 p.queue.push_back(QItem{1, t.item, t.head_kv, 0});
             }
         }
@@ -263,7 +269,9 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     p.info.split_pages = L;
     p.info.tile_tokens = TT;
 
-    int32_t part = 0;
+    int32_t part = 0, pf_part = 0;
+    // parts per prefill tile that would give every CU a workgroup (1 = the tiles fill the GPU as they are)
+    const int64_t pf_parts_wanted = tile_heads > 0 ? std::min<int64_t>(16, opt.n_cu / tile_heads) : 1;
     for (int s = 0; s < num_seqs; ++s) {
         const SeqMeta& m = p.seqs[s];
         if (m.q_len == 0) continue;
@@ -281,9 +289,36 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
             }
             if (n_split > 1) part += n_split;
         } else if (as_tiles) {
-            for (int32_t t0 = 0; t0 < m.q_len; t0 += TT)
-                p.pf.push_back(PfItem{s, m.q_off, m.q_len, m.prefix, t0, std::min(TT, m.q_len - t0),
-                                      m.ctx_len, 0});
+            for (int32_t t0 = 0; t0 < m.q_len; t0 += TT) {
+                const int32_t cnt = std::min(TT, m.q_len - t0);
+                // Cut along the keys when the batch's tiles cannot occupy the GPU (a short chunk over a long
+                // prefix -- the one-task-at-a-time shape of Sec. 4.4 -- walks thousands of keys in a handful of
+                // workgroups otherwise).  Cuts lie at multiples of 64 keys at or below the tile's first query
+                // position, so that every row sees the first key of every part; parts are of equal length.
+                const int32_t below = (m.prefix + t0) / 64;                       // whole stages every row sees fully
+                int32_t n_part = 1;
+                if (pf_parts_wanted > 1 && opt.pf_split_min_keys > 0)
+                    n_part = (int32_t)std::max<int64_t>(1, std::min<int64_t>(pf_parts_wanted, (int64_t)below * 64 / opt.pf_split_min_keys));
+                if (n_part == 1) {
+                    p.pf.push_back(PfItem{s, m.q_off, m.q_len, m.prefix, t0, cnt, m.ctx_len, -1, 0, INT32_MAX, 0, 0});
+                    continue;
+                }
+                const int32_t total = (m.prefix + t0 + cnt + 63) / 64;            // stages of the whole tile
+                const int32_t per = (total + n_part - 1) / n_part;
+                int32_t begin = 0, made = 0;
+                const int32_t first = pf_part;
+                for (int32_t cut = per; cut <= below && cut < total; cut += per, ++made) {
+                    p.pf.push_back(PfItem{s, m.q_off, m.q_len, m.prefix, t0, cnt, m.ctx_len, pf_part++, begin * 64, cut * 64, 0, 0});
+                    begin = cut;
+                }
+                if (made == 0) {                                                   // no admissible cut after all
+                    p.pf.push_back(PfItem{s, m.q_off, m.q_len, m.prefix, t0, cnt, m.ctx_len, -1, 0, INT32_MAX, 0, 0});
+                    continue;
+                }
+                p.pf.push_back(PfItem{s, m.q_off, m.q_len, m.prefix, t0, cnt, m.ctx_len, pf_part++, begin * 64, INT32_MAX, 0, 0});
+                ++made;
+                p.pfcmb.push_back(PfCmb{(int32_t)p.pf.size() - made, first, made, 0});
+            }
         } else {
             for (int32_t i = 0; i < m.q_len; ++i)
                 p.rows.push_back(RowItem{m.q_off + i, s, m.prefix + i + 1, 0});
@@ -311,9 +346,19 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     std::stable_sort(p.dec.begin(), p.dec.end(), [](const DecItem& a, const DecItem& b) {
         return (a.page_end - a.page_begin) > (b.page_end - b.page_begin);
     });
-    std::stable_sort(p.pf.begin(), p.pf.end(), [](const PfItem& a, const PfItem& b) {
-        return (a.prefix + a.tok_begin + a.tok_count) > (b.prefix + b.tok_begin + b.tok_count);
-    });
+    {
+        // (the merge list refers to the tiles by position: sort a permutation and carry the references along)
+        auto keys_of = [](const PfItem& t) {
+            return std::min(t.prefix + t.tok_begin + t.tok_count, t.kv_end) - t.kv_begin;
+        };
+        std::vector<int32_t> order(p.pf.size()), where(p.pf.size());
+        for (size_t i = 0; i < order.size(); ++i) order[i] = (int32_t)i;
+        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return keys_of(p.pf[a]) > keys_of(p.pf[b]); });
+        std::vector<PfItem> sorted(p.pf.size());
+        for (size_t i = 0; i < order.size(); ++i) { sorted[i] = p.pf[order[i]]; where[order[i]] = (int32_t)i; }
+        p.pf.swap(sorted);
+        for (PfCmb& cm : p.pfcmb) cm.item = where[cm.item];
+    }
     map_prefill_to_xcds(p, Hkv, std::max(1, opt.xcds), mixed_mode);
     std::stable_sort(p.rows.begin(), p.rows.end(),
                      [](const RowItem& a, const RowItem& b) { return a.n_keys > b.n_keys; });
@@ -322,6 +367,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     p.info.n_prefill_tiles = (int32_t)p.pf.size();
     p.info.n_generic_rows = (int32_t)p.rows.size();
     p.info.partial_slots = part;
+    p.info.prefill_parts = pf_part;
 }
 
 }  // namespace ts
@@ -388,6 +434,7 @@ extern "C" int64_t ts_plan_export(const ts_attn_desc* desc, const int32_t* q_len
     case TS_LIST_QOFF:    src = plan.q_off.data(); n = (int64_t)plan.q_off.size(); words = 1; break;
     case TS_LIST_APPEND:  src = plan.apt.data();   n = (int64_t)plan.apt.size();   words = sizeof(ts::AppTile) / 4; break;
     case TS_LIST_APPEND_ROWS: src = plan.apr.data(); n = (int64_t)plan.apr.size(); words = sizeof(ts::AppRow) / 4; break;
+    case TS_LIST_PFCOMBINE: src = plan.pfcmb.data(); n = (int64_t)plan.pfcmb.size(); words = sizeof(ts::PfCmb) / 4; break;
     case TS_LIST_WIDEN:   src = plan.wide.data();  n = (int64_t)plan.wide.size();  words = sizeof(ts::WideItem) / 4; break;
     default: return TS_ERR_INVALID_ARG;
     }

@@ -199,7 +199,12 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     constexpr int D = 128, KS = 8, DB = 4, kHalf = 32;     // KS: 16-dim steps of K Q^T, DB: 32-dim blocks of O^T
     // (through the constant address space: the tile's description is wave-uniform and belongs in scalar registers)
     const int32_t TS_CONSTANT* itp = as_constant((const int32_t*)(a.pf + item_idx));
-    const PfItem it{itp[0], itp[1], itp[2], itp[3], itp[4], itp[5], itp[6], 0};
+    const PfItem it{itp[0], itp[1], itp[2], itp[3], itp[4], itp[5], itp[6], itp[7], itp[8], itp[9], 0, 0};
+    // A tile cut along the keys works on the keys [kv_begin, kv_end) only.  Everything below is written in
+    // positions relative to kv_begin (a multiple of 64: stage 0 of this item is stage kv_begin / 64 of the
+    // sequence); every row of the tile sees key kv_begin, and only the last part reaches the diagonal.
+    const int kv0 = it.kv_begin;
+    const int ctx_rel = it.ctx_len - kv0;                  // keys of the sequence from kv_begin on
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, h = lane >> 5,
               n = lane & 31;
     const int Hq = a.geo.Hq, G = a.geo.G;
@@ -225,9 +230,9 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // (the scale of the exponent is wave-uniform: kept in a scalar register, it costs no vector register)
     const float kscale = fp8_cache ? as_constant(a.k_scale)[g] : 1.0f;
     const float c = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.sm_scale * kscale * kLog2e)));
-    const int qpos = it.prefix + it.tok_begin + tok;
-    const int wave_min_q = it.prefix + it.tok_begin + min((32 * wave) / G, it.tok_count - 1);
-    const int kv_hi = it.prefix + it.tok_begin + it.tok_count;     // keys [0, kv_hi) matter to this tile
+    const int qpos = it.prefix + it.tok_begin + tok - kv0;
+    const int wave_min_q = it.prefix + it.tok_begin + min((32 * wave) / G, it.tok_count - 1) - kv0;
+    const int kv_hi = min(it.prefix + it.tok_begin + it.tok_count, it.kv_end) - kv0;   // keys [0, kv_hi) matter to this item
     const int last_page = (it.ctx_len - 1) / kPage;
     const int32_t TS_CONSTANT* bt = as_constant(a.block_table) + (int64_t)it.seq * a.geo.max_pages;
     const int wbase = widened ? as_constant(a.wide_base)[it.seq] : 0;
@@ -461,8 +466,8 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // i+3 is fetched into the registers.
     constexpr bool kCopy = sizeof(KT) == 2;
     // bf16: the stage that holds tokens >= ctx_len (if this tile reads it) needs its V tail cleared
-    const int clear_stage = (kCopy && it.ctx_len % kStageTok != 0 && it.ctx_len / kStageTok < n_stage)
-                                ? it.ctx_len / kStageTok : -1;
+    const int clear_stage = (kCopy && ctx_rel % kStageTok != 0 && ctx_rel / kStageTok < n_stage)
+                                ? ctx_rel / kStageTok : -1;
     StageFp8 st;
     // Page of a stage this wave stages (a tile that ends inside the last page of the sequence repeats that
     // page).  The id comes through the scalar cache.  Read where it is used, the latency of that
@@ -470,7 +475,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // has anything else to issue; so the id that top(i+1) needs is requested between the two iterations
     // of body i, where the wait for it falls into a phase in which the other wave of the SIMD has work.
     auto page_id = [&](int stage) {
-        const int j = min(stage * 4 + (wave >> 1), last_page);
+        const int j = min((kv0 >> 4) + stage * 4 + (wave >> 1), last_page);
         return widened ? wbase + j : bt[j];
     };
     int32_t pid_next;                                      // page id top(i) needs: that of stage i + 3
@@ -490,7 +495,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
                 // then worked out here, once per body, instead of occupying six registers for the whole tile)
                 int t = tid;
                 asm volatile("" : "+v"(t));
-                stage_store(st, lds.k[(i + 2) % kPfRing], lds.v[(i + 2) % kPfRing], (i + 2) * kStageTok, it.ctx_len, t);
+                stage_store(st, lds.k[(i + 2) % kPfRing], lds.v[(i + 2) % kPfRing], (i + 2) * kStageTok, ctx_rel, t);
                 if (i + 3 < n_stage) stage_fetch(st, a, pid_next, g, t);
             }
         }
@@ -508,7 +513,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         __syncthreads();
         if constexpr (kCopy) {
             if (i + 2 == clear_stage) {                    // tile-uniform, at most once per tile
-                clear_v_tail(lds.v[clear_stage % kPfRing], clear_stage, it.ctx_len, opaque(tid));
+                clear_v_tail(lds.v[clear_stage % kPfRing], clear_stage, ctx_rel, opaque(tid));
                 __syncthreads();
             }
         }
@@ -526,14 +531,14 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         StageFp8 st1;
         stage_fetch(st, a, p0, g, tid);
         if (n_stage > 1) stage_fetch(st1, a, p1, g, tid);
-        stage_store(st, lds.k[0], lds.v[0], 0, it.ctx_len, tid);
+        stage_store(st, lds.k[0], lds.v[0], 0, ctx_rel, tid);
         if (n_stage > 2) stage_fetch(st, a, p2, g, tid);
-        if (n_stage > 1) stage_store(st1, lds.k[1], lds.v[1], kStageTok, it.ctx_len, tid);
+        if (n_stage > 1) stage_store(st1, lds.k[1], lds.v[1], kStageTok, ctx_rel, tid);
     }
     __syncthreads();
     if constexpr (kCopy) {
         if (clear_stage == 0 || clear_stage == 1) {
-            clear_v_tail(lds.v[clear_stage], clear_stage, it.ctx_len, opaque(tid));
+            clear_v_tail(lds.v[clear_stage], clear_stage, ctx_rel, opaque(tid));
             __syncthreads();
         }
     }
@@ -554,9 +559,10 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // Bodies whose iterations all have a half-stage hs+2 to multiply run the steady state: first those
     // that lie below the first query position of the tile (no wave needs a mask), then those that
     // reach into the diagonal; the last one or two bodies drain the pipeline.
-    const int hfull_tile = (it.prefix + it.tok_begin + 1) / kHalf;
-    const int n_plain = max(0, (hfull_tile - 2) / 2);      // 2i+3 < hfull_tile
+    const int hfull_tile = (it.prefix + it.tok_begin + 1 - kv0) / kHalf;
     const int n_steady = max(0, (hend - 2) / 2);           // 2i+3 < hend
+    // (a part of a cut tile that ends below the diagonal has no masked body at all)
+    const int n_plain = min(n_steady, max(0, (hfull_tile - 2) / 2));      // 2i+3 < hfull_tile
     int i = 0;
     constexpr std::true_type yes{};
     constexpr std::false_type no{};
@@ -593,6 +599,23 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // store one whole 256-byte row as 16-byte pieces and an instruction covers 4 rows.
     // (Lane indices are derived afresh from an opaque copy of the thread index: nothing of this stage then
     // occupies a register during the loops above.)
+    if (it.part >= 0) {
+        // One part of a tile cut along the keys: the unnormalised rows and their (reference maximum, weight sum)
+        // go to the partial-result buffers as they are; prefill_combine_kernel merges the parts.
+        const int tid_o = opaque(tid), wave_o = __builtin_amdgcn_readfirstlane(tid_o >> 6), lane_o = tid_o & 63,
+                  h_o = lane_o >> 5, n_o = lane_o & 31;
+        const int64_t slot = ((int64_t)it.part * a.geo.Hkv + g) * kPfPartRows + 32 * wave_o + n_o;
+        float* po = a.pf_part_o + slot * D + 4 * h_o;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *(f32x4*)(po + 32 * b + 8 * j) = f32x4{acc[b][4 * j], acc[b][4 * j + 1], acc[b][4 * j + 2], acc[b][4 * j + 3]};
+        const float l_row = pair32_sum(l_part);
+        if (h_o == 0) *(float2*)(a.pf_part_ml + slot * 2) = make_float2(m_ref, l_row);
+        __syncthreads();                                   // LDS may be reused by the caller
+        return;
+    }
     constexpr int kOutStride = 272;
     const int tid_o = opaque(tid), wave_o = __builtin_amdgcn_readfirstlane(tid_o >> 6), lane_o = tid_o & 63,
               h_o = lane_o >> 5, n_o = lane_o & 31;

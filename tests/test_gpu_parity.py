@@ -201,6 +201,37 @@ def test_fp8_prefill_widened_pages_and_in_tile_widening_agree(mode):
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[1], outs[2])
 
 
+@pytest.mark.parametrize("kv,heads", [("bf16", (32, 8)), ("fp8", (64, 8)), ("bf16", (8, 8)), ("fp8", (16, 1))])
+def test_prefill_tiles_cut_along_the_keys(kv, heads):
+    """A short chunk over a long prefix cannot give every CU a tile: the tiles are cut along the keys and the
+    parts merged.  Chunks whose prefix ends inside a page, a stage and a part; parts of 64 keys (the finest cut)
+    and the default; next to decode rows (one persistent kernel) and alone; same results with cutting off."""
+    import paper_2512_03416_amd as ts
+    shape = AttnShape(heads[0], heads[1], 128, "bf16", kv)
+    g = gpu()
+    for q, c in [([200], [200 + 4099]), ([64, 37], [64 + 2048, 37 + 1000]), ([1, 130, 1, 1], [700, 130 + 3001, 64, 2500])]:
+        mk = lambda: make_batch(shape, q, c, seed=61, pool_rule=1.2, value_mult=0.5 if kv == "bf16" else 1.0)
+        b = mk()
+        assert ts.plan_describe(g.make_desc(b), b.q_lens, b.ctx_lens).prefill_parts > 1
+        ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
+        outs = []
+        for opts in ({}, {"prefill_split_min_keys": 64}, {"prefill_split_min_keys": 0},
+                     {"prefill_split_min_keys": 64, "prefill_widen_pages": 0, "mixed_mode": 0}):
+            print(f"[case] cut tiles kv={kv} heads={heads} q={q} ctx={c} opts={opts}", flush=True)
+            out, gk, gv = g.run_batch(mk(), options=opts)
+            assert same_bytes(gk, rk) and same_bytes(gv, rv)
+            assert np.all(np.isfinite(out))
+            err = float(np.max(np.abs(out - ref)))
+            print(f"       max abs err {err:.3e}", flush=True)
+            assert err <= TOL[kv]
+            outs.append(out)
+        # same cuts, other launch mode / widening: the chunk rows come out bit-identical (decode rows may be
+        # cut into other page ranges in another launch mode)
+        q_off = np.concatenate([[0], np.cumsum(q)])
+        rows = np.concatenate([np.arange(q_off[i], q_off[i + 1]) for i in range(len(q)) if q[i] > 1])
+        assert np.array_equal(outs[1][rows], outs[3][rows])
+
+
 def binding_export(desc, b, which):
     from paper_2512_03416_amd import binding
     return binding.plan_export(desc, b.q_lens, b.ctx_lens, which)

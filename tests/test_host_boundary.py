@@ -222,18 +222,37 @@ def test_plan_invariants_on_seeded_random_batches(seed):
     assert sorted(used) == list(range(len(used)))
 
     pf = exp("prefill")
-    toks = {}
-    for seq, row0, q_len, prefix, t0, cnt, ctx_len, _ in pf:
+    toks, part_keys = {}, {}
+    for seq, row0, q_len, prefix, t0, cnt, ctx_len, part, kv_b, kv_e, *_ in pf:
         assert ql[seq] > 1 and row0 == q_off[seq] and q_len == ql[seq] and prefix == ctx[seq] - ql[seq] and ctx_len == ctx[seq]
         assert t0 % tile_tokens == 0 and 0 < cnt <= tile_tokens
+        hi = prefix + t0 + cnt                                    # keys the tile's last row sees
+        if part < 0:
+            assert kv_b == 0 and kv_e >= hi
+            toks.setdefault(seq, []).extend(range(t0, t0 + cnt))
+        else:                                                     # a part of a tile cut along the keys
+            assert kv_b % 64 == 0 and kv_b <= prefix + t0 and kv_b < min(kv_e, hi)
+            assert kv_e % 64 == 0 or kv_e >= hi
+            part_keys.setdefault((seq, t0, cnt), []).append((kv_b, min(kv_e, hi), part))
+    for (seq, t0, cnt), parts in part_keys.items():               # the parts of a tile cover its keys exactly once
+        parts.sort()
+        assert len(parts) > 1 and parts[0][0] == 0 and parts[-1][1] == ctx[seq] - ql[seq] + t0 + cnt
+        assert all(a[1] == b[0] for a, b in zip(parts, parts[1:]))
+        assert all(e <= ctx[seq] - ql[seq] + t0 for _, e, _ in parts[:-1])        # only the last part meets the diagonal
+        assert [p for _, _, p in parts] == list(range(parts[0][2], parts[0][2] + len(parts)))
         toks.setdefault(seq, []).extend(range(t0, t0 + cnt))
+    pfc = exp("pfcombine")
+    assert len(pfc) == len(part_keys)
+    for item, p0, n_part, _ in pfc:
+        seq, _, _, _, t0, cnt, *_ = pf[item]
+        assert len(part_keys[(seq, t0, cnt)]) == n_part and min(p for _, _, p in part_keys[(seq, t0, cnt)]) == p0
     assert set(toks) == {s for s in range(n) if ql[s] > 1}
     for s, t in toks.items():
         assert sorted(t) == list(range(ql[s]))
 
     pfmap = exp("pfmap")
     live = [(int(t), int(g)) for t, g in pfmap if t >= 0]
-    assert sorted(live) == sorted((t, g) for t in range(len(pf)) for g in range(hkv))
+    assert sorted(live) == sorted((t, g) for t in range(len(pf)) for g in range(hkv))      # (every part is a work item)
 
     queue, qoff = exp("queue"), exp("qoff")[:, 0]
     if len(dec) and len(pf) and mode != 0:                    # a mixed batch has per-die queues
