@@ -514,9 +514,9 @@ extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
             rc = TS_ERR_NOMEM;
         }
     }
+    if (rc == TS_OK && desc_uses_mfma_decode(c->desc))     // launch shapes of this GPU, asked here so that no later call has to
+        c->dec_slots = decode_resident_workgroups(c->desc.kv_dtype, c->dec_nbuf, c->desc.head_dim);
     if (rc == TS_OK && desc_uses_mfma(c->desc)) {
-        // launch shapes of this GPU, asked here so that no later call has to
-        c->dec_slots = decode_resident_workgroups(c->desc.kv_dtype, c->dec_nbuf);
         c->mixed_wgs = mixed_resident_workgroups(c->desc.kv_dtype);
         if (c->mixed_wgs <= 0) rc = fail(c, TS_ERR_HIP, "occupancy query of the persistent kernel failed");
     }
@@ -624,7 +624,8 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         if (c->dec_nbuf != (int)value) {
             DeviceGuard guard(c->device);
             c->dec_nbuf = (int)value;
-            if (desc_uses_mfma(c->desc)) c->dec_slots = decode_resident_workgroups(c->desc.kv_dtype, c->dec_nbuf);
+            if (desc_uses_mfma_decode(c->desc))
+                c->dec_slots = decode_resident_workgroups(c->desc.kv_dtype, c->dec_nbuf, c->desc.head_dim);
         }
         return TS_OK;
     }

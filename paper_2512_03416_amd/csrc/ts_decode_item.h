@@ -28,32 +28,35 @@ namespace ts {
 
 constexpr float kRaise = 16.0f;   // log2 units: weights stay below 2^16 relative to the reference
 
-template <typename KT> struct KVTile;
-template <> struct KVTile<uint16_t> { uint4 k[4]; uint2 v[8]; };
-template <> struct KVTile<uint8_t>  { uint4 k[2]; uint32_t v[8]; };
+// One (page, KV head) tile in registers, D = head dim (64 or 128): K as 1 KB runs, V as 16-dim blocks.
+template <typename KT, int D> struct KVTile;
+template <int D> struct KVTile<uint16_t, D> { uint4 k[D / 32]; uint2 v[D / 16]; };
+template <int D> struct KVTile<uint8_t, D>  { uint4 k[D / 64]; uint32_t v[D / 16]; };
 
 // Tiles are read with the non-temporal hint: the scan touches every byte once, and keeping it out
 // of the L2's replacement traffic raised the rate from 5.9 to 6.45 TB/s (bf16; fp8: 5.9 to 6.3).
-__device__ __forceinline__ void load_tile(KVTile<uint16_t>& t, const char* kc, const char* vc,
+template <int D>
+__device__ __forceinline__ void load_tile(KVTile<uint16_t, D>& t, const char* kc, const char* vc,
                                           int64_t tile, int lane)
 {
-    const char* kt = kc + tile * 4096 + lane * 16;
-    const char* vt = vc + tile * 4096 + (lane & 15) * 32 + (lane >> 4) * 8;
+    const char* kt = kc + tile * (32 * D) + lane * 16;
+    const char* vt = vc + tile * (32 * D) + (lane & 15) * 32 + (lane >> 4) * 8;
 #pragma unroll
-    for (int b = 0; b < 4; ++b) t.k[b] = load_nt4(kt + b * 1024);
+    for (int b = 0; b < D / 32; ++b) t.k[b] = load_nt4(kt + b * 1024);
 #pragma unroll
-    for (int b = 0; b < 8; ++b) t.v[b] = load_nt2(vt + b * 512);
+    for (int b = 0; b < D / 16; ++b) t.v[b] = load_nt2(vt + b * 512);
 }
 
-__device__ __forceinline__ void load_tile(KVTile<uint8_t>& t, const char* kc, const char* vc,
+template <int D>
+__device__ __forceinline__ void load_tile(KVTile<uint8_t, D>& t, const char* kc, const char* vc,
                                           int64_t tile, int lane)
 {
-    const char* kt = kc + tile * 2048 + lane * 16;
-    const char* vt = vc + tile * 2048 + (lane & 15) * 16 + (lane >> 4) * 4;
+    const char* kt = kc + tile * (16 * D) + lane * 16;
+    const char* vt = vc + tile * (16 * D) + (lane & 15) * 16 + (lane >> 4) * 4;
 #pragma unroll
-    for (int b = 0; b < 2; ++b) t.k[b] = load_nt4(kt + b * 1024);
+    for (int b = 0; b < D / 64; ++b) t.k[b] = load_nt4(kt + b * 1024);
 #pragma unroll
-    for (int b = 0; b < 8; ++b) t.v[b] = __builtin_nontemporal_load((const uint32_t*)(vt + b * 256));
+    for (int b = 0; b < D / 16; ++b) t.v[b] = __builtin_nontemporal_load((const uint32_t*)(vt + b * 256));
 }
 
 // four e4m3 bytes -> four bf16 (exact: every e4m3 value is a bf16 value)
@@ -71,19 +74,21 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast
 __device__ __forceinline__ s16x4 as_s16x4(uint2 v) { return __builtin_bit_cast(s16x4, v); }
 
 // S^T (16 tokens x 16 columns) = K tile x Q^T for one page
-__device__ __forceinline__ f32x4 qk_tile(const KVTile<uint16_t>& t, const bf16x8* qb)
+template <int D>
+__device__ __forceinline__ f32x4 qk_tile(const KVTile<uint16_t, D>& t, const bf16x8* qb)
 {
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < D / 32; ++b)
         s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.k[b]), qb[b], s, 0, 0, 0);
     return s;
 }
-__device__ __forceinline__ f32x4 qk_tile(const KVTile<uint8_t>& t, const bf16x8* qb)
+template <int D>
+__device__ __forceinline__ f32x4 qk_tile(const KVTile<uint8_t, D>& t, const bf16x8* qb)
 {
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < D / 64; ++j) {
         const uint2 a0 = fp8x4_to_bf16x4(t.k[j].x), a1 = fp8x4_to_bf16x4(t.k[j].y);
         const uint2 a2 = fp8x4_to_bf16x4(t.k[j].z), a3 = fp8x4_to_bf16x4(t.k[j].w);
         s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(make_uint4(a0.x, a0.y, a1.x, a1.y)),
@@ -94,8 +99,8 @@ __device__ __forceinline__ f32x4 qk_tile(const KVTile<uint8_t>& t, const bf16x8*
     return s;
 }
 
-__device__ __forceinline__ uint2 v_operand(const KVTile<uint16_t>& t, int b) { return t.v[b]; }
-__device__ __forceinline__ uint2 v_operand(const KVTile<uint8_t>& t, int b) { return fp8x4_to_bf16x4(t.v[b]); }
+template <int D> __device__ __forceinline__ uint2 v_operand(const KVTile<uint16_t, D>& t, int b) { return t.v[b]; }
+template <int D> __device__ __forceinline__ uint2 v_operand(const KVTile<uint8_t, D>& t, int b) { return fp8x4_to_bf16x4(t.v[b]); }
 
 // dims held by k-block b of the Q operand for lane group r (must mirror the K tile order)
 template <typename KT> __device__ __forceinline__ int q_dim0(int b, int r)
@@ -112,9 +117,9 @@ template <typename KT> __device__ __forceinline__ int q_dim0(int b, int r)
 // fair share are cut into several items whose partials go through combine_kernel.
 constexpr int kDecWaves = 4;               // stand-alone decode kernel; the mixed kernel uses 8
 
-template <int WAVES>
+template <int WAVES, int D = 128>
 struct DecMerge {                          // LDS image of the non-leading waves' state
-    float o[WAVES - 1][8][64][4];          // acc[b] of every lane
+    float o[WAVES - 1][D / 16][64][4];     // acc[b] of every lane
     float m[WAVES - 1][16];
     float l[WAVES - 1][16];
 };
@@ -122,10 +127,10 @@ struct DecMerge {                          // LDS image of the non-leading waves
 // One decode item for KV head g, executed by a workgroup of WAVES waves.  All waves must call
 // it; it contains one workgroup barrier, and the caller must place another barrier before mg is
 // reused.
-template <typename KT, int NBUF, int WAVES>
-__device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int g, DecMerge<WAVES>& mg)
+template <typename KT, int NBUF, int WAVES, int D = 128>
+__device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int g, DecMerge<WAVES, D>& mg)
 {
-    constexpr int D = 128, KB = 4, DB = 8;
+    constexpr int KB = D / 32, DB = D / 16;    // 32-dim steps of K Q^T, 16-dim blocks of O^T
     const int32_t TS_CONSTANT* itp = as_constant((const int32_t*)(a.dec + item_idx));
     const int it_row = itp[0], it_seq = itp[1], it_keys = itp[2], it_pb = itp[3], it_pe = itp[4], it_part = itp[5];
     // (readfirstlane tells the compiler the wave index is uniform, which keeps everything derived
@@ -160,12 +165,12 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
         // page ids come through the scalar cache, one fetch ahead of their use
         int next_k = 0;
         int next_id = bt[0];
-        auto fetch = [&](KVTile<KT>& t) {
+        auto fetch = [&](KVTile<KT, D>& t) {
             load_tile(t, kc, vc, (int64_t)next_id * Hkv + g, lane);
             next_k = min(next_k + 1, np - 1);                     // past the end: stay on the last page
             next_id = bt[WAVES * next_k];
         };
-        KVTile<KT> buf[NBUF];
+        KVTile<KT, D> buf[NBUF];
 #pragma unroll
         for (int j = 0; j < NBUF; ++j) fetch(buf[j]);
 
@@ -174,7 +179,7 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
             for (int j = 0; j < NBUF; ++j) {
                 const int k = base + j;
                 if (k < np) {                                     // wave-uniform
-                    const KVTile<KT>& t = buf[j];
+                    const KVTile<KT, D>& t = buf[j];
                     const int page = it_pb + wave + WAVES * k;
                     f32x4 s = qk_tile(t, qb);
                     float t0 = s[0] * c, t1 = s[1] * c, t2 = s[2] * c, t3 = s[3] * c;

@@ -129,8 +129,11 @@ struct PlanOptions {
     int64_t widen_pages = 16384; // fp8 caches: most pages of prefill sequences that are widened to bf16 per pass (0 = never)
 };
 
-// Which kernels serve a descriptor.
+// Which kernels serve a descriptor: the matrix-core tile kernels for prefill chunks (head dim 128; this also
+// stands for the page-wise append, the persistent launches and their scratch), the matrix-core decode items
+// (head dim 64 or 128).  Everything else goes through the generic row kernel.
 bool desc_uses_mfma(const ts_attn_desc& d);
+bool desc_uses_mfma_decode(const ts_attn_desc& d);
 int32_t prefill_tile_tokens(const ts_attn_desc& d);
 
 // Validates lengths; returns TS_OK or an error and fills err.
@@ -205,7 +208,7 @@ int launch_decode(const AttnArgs& a, void* stream);
 int launch_combine(const AttnArgs& a, void* stream);
 // Resident workgroups of the decode / persistent kernel on the current device (0 if unknown).  The
 // caller keeps the answers per context: two contexts may sit on different GPUs.
-int decode_resident_workgroups(int kv_dtype, int nbuf);
+int decode_resident_workgroups(int kv_dtype, int nbuf, int head_dim);
 int mixed_resident_workgroups(int kv_dtype);
 int launch_widen(const AttnArgs& a, void* wide_k, void* wide_v, void* stream);
 int launch_prefill(const AttnArgs& a, void* stream);

@@ -5,22 +5,22 @@ namespace ts {
 
 // KV heads vary fastest over the grid: the Hkv workgroups of one item start together and read the
 // Hkv adjacent tiles of each page (one contiguous run of the cache) at about the same time.
-template <typename KT, int NBUF>
+template <typename KT, int NBUF, int D>
 __global__ __launch_bounds__(64 * kDecWaves) void decode_kernel(AttnArgs a)
 {
-    __shared__ DecMerge<kDecWaves> mg;
-    decode_item<KT, NBUF, kDecWaves>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
+    __shared__ DecMerge<kDecWaves, D> mg;
+    decode_item<KT, NBUF, kDecWaves, D>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
 }
 
 // The default form, two KV tiles in flight per wave, held to 128 vector registers per lane (the attribute
 // counts in units of two here): one such workgroup then fits on a CU next to a resident prefill workgroup
 // (see prefill_resident_kernel), and four fit on a CU of their own.  A single workgroup of four waves per CU
 // already keeps enough loads in flight for the bf16 scan to run at its full rate.
-template <typename KT>
+template <typename KT, int D>
 __global__ __launch_bounds__(64 * kDecWaves) __attribute__((amdgpu_num_vgpr(64))) void decode_kernel_lean(AttnArgs a)
 {
-    __shared__ DecMerge<kDecWaves> mg;
-    decode_item<KT, 2, kDecWaves>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
+    __shared__ DecMerge<kDecWaves, D> mg;
+    decode_item<KT, 2, kDecWaves, D>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
 }
 
 // Merge of a row's splits, in split order:  M = max m_i, out = sum o_i 2^(m_i-M) / sum l_i 2^(m_i-M).
@@ -66,47 +66,50 @@ __global__ __launch_bounds__(128) void combine_kernel(AttnArgs a)
     ((uint16_t*)a.out)[((int64_t)it.row * Hq + h) * D + d] = (uint16_t)float_to_bf16_bits(o * vscale / L);
 }
 
-template <typename KT>
+template <typename KT, int D>
 static int launch_decode_t(const AttnArgs& a, hipStream_t st)
 {
     dim3 grid((unsigned)a.n_dec * (unsigned)a.geo.Hkv), block(64 * kDecWaves);
     switch (a.dec_nbuf) {
-    case 3: hipLaunchKernelGGL((decode_kernel<KT, 3>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((decode_kernel<KT, 4>), grid, block, 0, st, a); break;
-    default: hipLaunchKernelGGL((decode_kernel_lean<KT>), grid, block, 0, st, a); break;
+    case 3: hipLaunchKernelGGL((decode_kernel<KT, 3, D>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((decode_kernel<KT, 4, D>), grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL((decode_kernel_lean<KT, D>), grid, block, 0, st, a); break;
     }
     return (int)hipGetLastError();
 }
 
-template <typename KT>
+template <typename KT, int D>
 static int resident_t(int nbuf)
 {
     int per_cu = 0;
     hipError_t e;
     switch (nbuf) {
-    case 3: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 3>, 64 * kDecWaves, 0); break;
-    case 4: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 4>, 64 * kDecWaves, 0); break;
-    default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel_lean<KT>, 64 * kDecWaves, 0); break;
+    case 3: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 3, D>, 64 * kDecWaves, 0); break;
+    case 4: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<KT, 4, D>, 64 * kDecWaves, 0); break;
+    default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel_lean<KT, D>, 64 * kDecWaves, 0); break;
     }
     return e == hipSuccess ? per_cu : 0;
 }
 
-int decode_resident_workgroups(int kv_dtype, int nbuf)
+int decode_resident_workgroups(int kv_dtype, int nbuf, int head_dim)
 {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return 0;
-    return cus * (kv_dtype == TS_FP8_E4M3 ? resident_t<uint8_t>(nbuf) : resident_t<uint16_t>(nbuf));
+    int per_cu;
+    if (head_dim == 64) per_cu = kv_dtype == TS_FP8_E4M3 ? resident_t<uint8_t, 64>(nbuf) : resident_t<uint16_t, 64>(nbuf);
+    else per_cu = kv_dtype == TS_FP8_E4M3 ? resident_t<uint8_t, 128>(nbuf) : resident_t<uint16_t, 128>(nbuf);
+    return cus * per_cu;
 }
 
 int launch_decode(const AttnArgs& a, void* stream)
 {
     if (a.n_dec <= 0) return (int)hipSuccess;
-    if (a.geo.D != 128 || a.geo.q_dtype != TS_BF16) return (int)hipErrorInvalidValue;
+    if ((a.geo.D != 128 && a.geo.D != 64) || a.geo.q_dtype != TS_BF16) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    if (a.geo.kv_dtype == TS_BF16) return launch_decode_t<uint16_t>(a, st);
-    if (a.geo.kv_dtype == TS_FP8_E4M3) return launch_decode_t<uint8_t>(a, st);
+    if (a.geo.kv_dtype == TS_BF16) return a.geo.D == 64 ? launch_decode_t<uint16_t, 64>(a, st) : launch_decode_t<uint16_t, 128>(a, st);
+    if (a.geo.kv_dtype == TS_FP8_E4M3) return a.geo.D == 64 ? launch_decode_t<uint8_t, 64>(a, st) : launch_decode_t<uint8_t, 128>(a, st);
     return (int)hipErrorInvalidValue;
 }
 

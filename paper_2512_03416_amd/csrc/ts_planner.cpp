@@ -21,6 +21,12 @@ bool desc_uses_mfma(const ts_attn_desc& d)
            (d.kv_dtype == TS_BF16 || d.kv_dtype == TS_FP8_E4M3);
 }
 
+bool desc_uses_mfma_decode(const ts_attn_desc& d)
+{
+    return d.q_dtype == TS_BF16 && (d.head_dim == 128 || d.head_dim == 64) &&
+           (d.kv_dtype == TS_BF16 || d.kv_dtype == TS_FP8_E4M3);
+}
+
 int32_t prefill_tile_tokens(const ts_attn_desc& d)
 {
     int G = d.num_q_heads / d.num_kv_heads;
@@ -214,6 +220,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     Plan& p = *plan;
     p = Plan();
     const bool mfma = desc_uses_mfma(d) && !opt.generic_only;
+    const bool mfma_dec = desc_uses_mfma_decode(d) && !opt.generic_only;
     const int Hkv = d.num_kv_heads;
     p.seqs.resize((size_t)num_seqs + 1);
     int32_t off = 0;
@@ -260,6 +267,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     if (mixed_mode == TS_MIXED_CORESIDENT && (tile_heads * 2 < opt.n_cu || decode_tiles < 4 * (int64_t)opt.n_cu))
         mixed_mode = TS_MIXED_ONE_KERNEL;
     if (!mfma || p.info.decode_tokens == 0 || tile_heads == 0) mixed_mode = TS_MIXED_SEPARATE;
+    if (!mfma_dec) { decode_tiles = 0; decode_pages = 0; }
     p.info.mixed_mode = mixed_mode;
     const bool filled_by_prefill = mixed_mode != TS_MIXED_SEPARATE && tile_heads >= opt.n_cu;
     const int32_t L = opt.split_pages > 0
@@ -275,7 +283,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     for (int s = 0; s < num_seqs; ++s) {
         const SeqMeta& m = p.seqs[s];
         if (m.q_len == 0) continue;
-        const bool as_decode = mfma && m.q_len == 1;
+        const bool as_decode = mfma_dec && m.q_len == 1;
         const bool as_tiles = mfma && m.q_len > 1 && !opt.prefill_generic;
         if (as_decode) {
             int32_t n_pages = (m.ctx_len + kPage - 1) / kPage;

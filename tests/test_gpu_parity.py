@@ -61,26 +61,55 @@ def test_generic_rows_shapes(shape):
 
 
 # ---------------------------------------------------------------------------------------------
-# MFMA decode path (bf16 / fp8 cache, head_dim 128)
+# MFMA decode path (bf16 / fp8 cache, head_dim 128 and 64)
 # ---------------------------------------------------------------------------------------------
 
 DEC_CTX = [1, 2, 15, 16, 17, 31, 33, 64, 100, 255, 256, 257, 600, 1000, 2049, 3000]
 
 
+@pytest.mark.parametrize("head_dim", [128, 64])
 @pytest.mark.parametrize("kv", ["bf16", "fp8"])
 @pytest.mark.parametrize("heads", [(8, 2), (4, 4), (16, 2), (32, 2), (6, 2)], ids=lambda h: f"{h[0]}q{h[1]}kv")
-def test_decode_rows(kv, heads):
-    shape = AttnShape(heads[0], heads[1], 128, "bf16", kv)
+def test_decode_rows(kv, heads, head_dim):
+    import paper_2512_03416_amd as ts
+    shape = AttnShape(heads[0], heads[1], head_dim, "bf16", kv)
     b = make_batch(shape, [1] * len(DEC_CTX), DEC_CTX, seed=31, pool_rule=1.3, value_mult=0.5)
+    info = ts.plan_describe(gpu().make_desc(b), b.q_lens, b.ctx_lens)
+    assert info.n_decode_items >= len(DEC_CTX) and info.n_generic_rows == 0       # the matrix-core decode items
     check(b)
 
 
+@pytest.mark.parametrize("head_dim", [128, 64])
 @pytest.mark.parametrize("split", [8, 9, 64, 128])
 @pytest.mark.parametrize("nbuf", [2, 3, 4])
-def test_decode_split_and_prefetch_variants(split, nbuf):
-    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+def test_decode_split_and_prefetch_variants(split, nbuf, head_dim):
+    shape = AttnShape(8, 2, head_dim, "bf16", "bf16" if (split + nbuf) % 2 else "fp8")
     b = make_batch(shape, [1] * len(DEC_CTX), DEC_CTX, seed=32, pool_rule=1.3, value_mult=0.5)
     check(b, options={"decode_split_pages": split, "decode_prefetch_tiles": nbuf})
+
+
+def test_head_dim_64_mixed_batch_and_every_fp8_code():
+    """Head dim 64 with a bf16 or e4m3 cache: decode rows through the matrix-core items, chunk rows through the
+    generic kernel, in one pass; every finite e4m3 code through K and V of single-key decode rows."""
+    for kv in ("bf16", "fp8"):
+        shape = AttnShape(16, 4, 64, "bf16", kv)
+        q = [1, 1, 90, 1, 0, 33, 1, 1]
+        c = [40, 1500, 150, 16, 9, 33, 4097, 1]
+        check(make_batch(shape, q, c, seed=46, pool_rule=1.25, value_mult=0.5))
+    shape = AttnShape(2, 2, 64, "bf16", "fp8")
+    codes = [cd for cd in range(256) if (cd & 0x7F) != 0x7F]
+    vals = torch.tensor([oracle.e4m3_to_double(cd) for cd in codes] + [0.0, 1.0], dtype=torch.float32)   # 256 values
+    b = make_batch(shape, [1, 1], [1, 1], seed=53, value_mult=0.05)
+    b.k_scale, b.v_scale = torch.tensor([1.0, 0.5]), torch.tensor([1.0, 0.25])
+    for s_ in range(2):
+        b.v_new[s_, 0] = vals[128 * s_:128 * s_ + 64].to(torch.bfloat16)
+        b.v_new[s_, 1] = (vals[128 * s_ + 64:128 * s_ + 128] * 0.25).to(torch.bfloat16)
+        b.k_new[s_, 0] = vals[128 * s_ + 64:128 * s_ + 128].to(torch.bfloat16)
+        b.k_new[s_, 1] = (vals[128 * s_:128 * s_ + 64] * 0.5).to(torch.bfloat16)
+    ref, rk, rv = oracle.run_batch(W.to_cpu(b))
+    out, gk, gv = gpu().run_batch(b)
+    assert same_bytes(gk, rk) and same_bytes(gv, rv)
+    assert np.array_equal(out, ref)                          # weight 1 on one key: exact
 
 
 def test_decode_large_scores_and_shifting_maximum():

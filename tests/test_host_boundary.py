@@ -146,12 +146,15 @@ def test_plan_append_pages_cover_every_new_token_of_the_chunks_once():
     assert len(binding.plan_export(d64, q_lens, ctx, "append_rows")) == int(q_lens.sum())
 
 
-def test_plan_routes_fp32_and_head_dim_64_to_generic_rows():
+def test_plan_routes_fp32_to_generic_rows_and_head_dim_64_chunks_too():
     d = D(q_dtype="f32", kv_dtype="f32", D=64, Hq=4, Hkv=1)
     info = ts.plan_describe(d, [1, 37, 64], [5, 37, 112])
     assert info.n_generic_rows == 102 and info.n_decode_items == 0 and info.n_prefill_tiles == 0
+    # head dim 64, bf16 / fp8 cache: decode rows are matrix-core items, chunk rows go to the generic kernel
     info = ts.plan_describe(D(D=64), [1, 4], [5, 4])
-    assert info.n_generic_rows == 5
+    assert info.n_generic_rows == 4 and info.n_decode_items == 1 and info.n_prefill_tiles == 0 and info.mixed_mode == 0
+    info = ts.plan_describe(D(D=64, kv_dtype="fp8"), [1, 1, 1], [5, 1000, 17])
+    assert info.n_generic_rows == 0 and info.n_decode_items >= 3
 
 
 def test_create_without_gpu_fails_loudly():
