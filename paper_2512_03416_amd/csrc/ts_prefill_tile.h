@@ -72,19 +72,17 @@ constexpr int kPfWaves = 8;                                // 512 threads, 256 q
 constexpr int kPfThreads = 64 * kPfWaves;
 constexpr int kPfRing = 4;                                 // stages resident in LDS
 // MFMA slots between the LDS read of an operand and its use (2..4).  Every slot of lookahead keeps four more
-// registers per lane busy; the fp8 form, which also holds a prefetched stage in registers, takes two slots so
-// that it fits the 192 registers of the co-resident launch, the form that reads widened pages three.
+// registers per lane busy.  Three slots (measured: as fast as four) let the bf16 forms fit the 192 registers of
+// the co-resident launch without spilling -- a spilled value is reloaded with a vector load, and the wait for
+// it also waits for the stage copies in flight, which cost the co-resident launch 10 % --; the fp8 form, which
+// also holds a prefetched stage in registers, takes two.
 #ifndef TS_PF_LOOKAHEAD
-#define TS_PF_LOOKAHEAD 4
+#define TS_PF_LOOKAHEAD 3
 #endif
 #ifndef TS_PF_LOOKAHEAD_FP8
 #define TS_PF_LOOKAHEAD_FP8 2
 #endif
-#ifndef TS_PF_LOOKAHEAD_WIDE
-#define TS_PF_LOOKAHEAD_WIDE 3
-#endif
-template <typename KT, bool WIDE> constexpr int kPfLookahead =
-    sizeof(KT) == 1 ? TS_PF_LOOKAHEAD_FP8 : (WIDE ? TS_PF_LOOKAHEAD_WIDE : TS_PF_LOOKAHEAD);
+template <typename KT, bool WIDE> constexpr int kPfLookahead = sizeof(KT) == 1 ? TS_PF_LOOKAHEAD_FP8 : TS_PF_LOOKAHEAD;
 
 // LDS image of a stage (bf16 in both cases): per page the 256 16-byte pieces of the cache tile,
 // reordered.

@@ -280,3 +280,35 @@ def test_plan_invariants_on_seeded_random_batches(seed):
         assert (seq, pos) not in seen and row == q_off[seq] + pos - (ctx[seq] - ql[seq])
         seen.add((seq, pos))
     assert seen == {(s, p) for s in range(n) for p in range(ctx[s] - ql[s], ctx[s])}
+
+
+def test_kernels_fit_their_register_budget_without_spilling():
+    """The co-resident launch rests on register budgets: resident prefill workgroups at <= 192 vector registers
+    per lane (two waves per SIMD) next to a lean decode workgroup at <= 128, and no kernel may spill (a spill
+    reload waits for every load in flight, the stage copies included).  Compiles the kernel sources for gfx950
+    with the library's flags and reads the compiler's resource remarks."""
+    import subprocess
+    from paper_2512_03416_amd import build as B
+    budgets = {"prefill_resident_kernel": 192, "prefill_kernel": 192, "decode_kernel_lean": 128, "mixed_kernel": 256,
+               "decode_kernel": 256}
+    seen = set()
+    for src in ("ts_kernels_mixed.hip", "ts_kernels_prefill.hip", "ts_kernels_decode.hip"):
+        r = subprocess.run([B.HIPCC] + B.FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-x", "hip", "-c",
+                                                 os.path.join(B.CSRC, src), "-o", os.devnull],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr[-2000:]
+        name = None
+        for line in r.stderr.splitlines():
+            m = re.search(r"Function Name: (\S+)", line)
+            if m:
+                name = m.group(1)
+            m = re.search(r" VGPRs: (\d+)", line)
+            if m and name:
+                key = next((k for k in sorted(budgets, key=len, reverse=True) if k in name), None)
+                if key:
+                    assert int(m.group(1)) <= budgets[key], (name, line)
+                    seen.add(key)
+            m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+            if m and name:
+                assert int(m.group(1)) == 0, f"{name} uses scratch memory (spills)"
+    assert seen == set(budgets)
