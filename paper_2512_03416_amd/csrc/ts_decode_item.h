@@ -59,14 +59,12 @@ __device__ __forceinline__ void load_tile(KVTile<uint8_t, D>& t, const char* kc,
     for (int b = 0; b < D / 16; ++b) t.v[b] = __builtin_nontemporal_load((const uint32_t*)(vt + b * 256));
 }
 
-// four e4m3 bytes -> four bf16 (exact: every e4m3 value is a bf16 value)
+// four e4m3 bytes -> four bf16 (exact: every e4m3 value is a bf16 value): one packed conversion per pair
 __device__ __forceinline__ uint2 fp8x4_to_bf16x4(uint32_t w)
 {
-    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
-    const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
     uint2 r;
-    r.x = __builtin_amdgcn_perm(__float_as_uint(lo.y), __float_as_uint(lo.x), 0x07060302u);
-    r.y = __builtin_amdgcn_perm(__float_as_uint(hi.y), __float_as_uint(hi.x), 0x07060302u);
+    r.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false));
+    r.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true));
     return r;
 }
 

@@ -41,11 +41,9 @@ __device__ __forceinline__ bf16x8 u4_bf16x8(uint4 v) { return __builtin_bit_cast
 
 __device__ __forceinline__ uint2 fp8x4_bf16x4(uint32_t w)
 {
-    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
-    const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
     uint2 r;
-    r.x = __builtin_amdgcn_perm(__float_as_uint(lo.y), __float_as_uint(lo.x), 0x07060302u);
-    r.y = __builtin_amdgcn_perm(__float_as_uint(hi.y), __float_as_uint(hi.x), 0x07060302u);
+    r.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false));
+    r.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true));
     return r;
 }
 
