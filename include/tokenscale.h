@@ -182,6 +182,11 @@ const char *ts_last_error(const ts_ctx *ctx);
 
 /* Tuning knobs (all optional).  Names:
  *   "decode_split_pages"  longest page range of one decode item (0 = choose from the batch)
+ *   "decode_merge_in_kernel"  0 (default) = a decode row cut into several items is merged by a small launch behind
+ *                         the decode items; 1 = by whichever of its items finishes last (arrival counters,
+ *                         device-scope release/acquire around the partial results; the merge reads the partials
+ *                         in item order, so the result does not depend on which item came last).  The second
+ *                         form saves a launch and is slower on this GPU (the release writes the L2 back)
  *   "prefill_path"        0 = MFMA tiles where supported, 1 = force the generic row kernel
  *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave
  *   "mixed_mode"          how a batch that holds decode rows and prefill chunks is launched:

@@ -25,13 +25,15 @@ thread_local std::string g_create_error;
 
 // Scratch of the allocation-free entry point: device memory that exists from the moment the library is
 // loaded on a GPU until the process ends, one copy per GPU.  Layout (bytes):
-//   [0, 4 KiB)       queue heads of the persistent kernel, result words of the page-id check
+//   [0, 4 KiB)       queue heads of the persistent kernel, result words of the page-id check (first 1 KiB),
+//                    arrival counters of split decode rows (768 words)
 //   [4 KiB, 1 MiB)   device copy of the work lists
 //   [1 MiB, 8 MiB)   split-K partial results
 // In host code the array's name is only a handle: the address a kernel can use is asked for once per
 // device (static_scratch_of) and kept.
 constexpr size_t kStaticBytes = 8u << 20;
 constexpr size_t kStaticCtrBytes = 4096;
+constexpr int kStaticCmbCtrs = 768;                        // words [256, 1024) of the counter area
 constexpr size_t kStaticWorkOff = kStaticCtrBytes, kStaticWorkBytes = (1u << 20) - kStaticCtrBytes;
 constexpr size_t kStaticPartOff = 1u << 20, kStaticPartBytes = kStaticBytes - kStaticPartOff;
 static __device__ __align__(256) unsigned char scratch[kStaticBytes];
@@ -77,6 +79,7 @@ struct ts_ctx {
     // device scratch
     char* d_work = nullptr;  size_t work_cap = 0;
     float* d_part_o = nullptr; float* d_part_ml = nullptr; int64_t part_cap = 0;
+    int32_t* d_cmb_ctr = nullptr;    // arrival counters of split decode rows (part_cap x Hkv, zero between launches)
     int32_t* d_q_ctr = nullptr;      // queue heads of the persistent kernel (zero between launches)
     float* d_pf_part_o = nullptr; float* d_pf_part_ml = nullptr; int64_t pf_part_cap = 0;   // partial results of cut prefill tiles
     char* d_wide_k = nullptr; char* d_wide_v = nullptr; int64_t wide_cap = 0;   // fp8 caches: widened pages (capacity in pages)
@@ -102,6 +105,11 @@ struct ts_ctx {
     // forked from the caller's stream behind the append and joined to it again with these two events.
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    // Split decode rows are merged by a launch of their own (default) or by whichever item of a row finishes
+    // last.  The second form saves a launch but needs a device-scope release in every item and an acquire in the
+    // last one; on this GPU the release writes the L2 back, and 8 rows of 1500 tokens took 30 us per pass
+    // instead of 20, a 256-token chunk next to 16 decode rows 154 us instead of 106.
+    bool merge_in_kernel = false;
     bool validate_pages = false;       // debug: check the page ids of a batch before anything is launched
     // launch shapes of this context's GPU, asked once per context (and again when the prefetch depth changes)
     int dec_nbuf = 2;                  // KV tiles in flight per decode wave
@@ -178,6 +186,12 @@ int64_t static_partial_slots(const ts_ctx* c)
 // Where the call in progress keeps its device-side scratch.
 char* work_base(const ts_ctx* c) { return c->static_call ? (char*)c->d_static + kStaticWorkOff : c->d_work; }
 int32_t* q_ctr_of(const ts_ctx* c) { return c->static_call ? (int32_t*)c->d_static : c->d_q_ctr; }
+// Arrival counters for n split rows, or NULL when the static scratch has too few (the merge then runs as a launch).
+int32_t* cmb_ctr_of(const ts_ctx* c, size_t n_rows)
+{
+    if (!c->static_call) return c->d_cmb_ctr;
+    return n_rows * (size_t)c->desc.num_kv_heads <= (size_t)kStaticCmbCtrs ? (int32_t*)c->d_static + 256 : nullptr;
+}
 float* part_o_of(const ts_ctx* c) { return c->static_call ? (float*)(c->d_static + kStaticPartOff) : c->d_part_o; }
 float* part_ml_of(const ts_ctx* c)
 {
@@ -199,13 +213,16 @@ int ensure_partials(ts_ctx* c, int64_t slots)
     TS_HIP(c, hipDeviceSynchronize());
     if (c->d_part_o) TS_HIP(c, hipFree(c->d_part_o));
     if (c->d_part_ml) TS_HIP(c, hipFree(c->d_part_ml));
-    c->d_part_o = c->d_part_ml = nullptr; c->part_cap = 0;
+    if (c->d_cmb_ctr) TS_HIP(c, hipFree(c->d_cmb_ctr));
+    c->d_part_o = c->d_part_ml = nullptr; c->d_cmb_ctr = nullptr; c->part_cap = 0;
     const size_t Hq = (size_t)c->desc.num_q_heads, D = (size_t)c->desc.head_dim;
+    const size_t ctr_bytes = (size_t)cap * c->desc.num_kv_heads * sizeof(int32_t);
     if (hipMalloc((void**)&c->d_part_o, (size_t)cap * Hq * D * sizeof(float)) != hipSuccess ||
-        hipMalloc((void**)&c->d_part_ml, (size_t)cap * Hq * 2 * sizeof(float)) != hipSuccess)
+        hipMalloc((void**)&c->d_part_ml, (size_t)cap * Hq * 2 * sizeof(float)) != hipSuccess ||
+        hipMalloc((void**)&c->d_cmb_ctr, ctr_bytes) != hipSuccess || hipMemset(c->d_cmb_ctr, 0, ctr_bytes) != hipSuccess)
         return fail(c, TS_ERR_NOMEM, "split-K partial scratch allocation failed");
     c->part_cap = cap;
-    c->n_alloc += 2;
+    c->n_alloc += 3;
     return TS_OK;
 }
 
@@ -283,7 +300,8 @@ int acquire_slot(ts_ctx* c, size_t bytes, HostSlot** out, bool exact = false)
 __global__ __launch_bounds__(256) void upload_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16,
                                                      int32_t* zero, int n_zero)
 {
-    if (blockIdx.x == 0 && (int)threadIdx.x < n_zero) zero[threadIdx.x] = 0;
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < n_zero; i += blockDim.x) zero[i] = 0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
@@ -364,7 +382,7 @@ int upload_plan(ts_ctx* c, hipStream_t st, const WorkLayout& w, UploadJob* defer
     }
     if (n16 > 0) {
         hipLaunchKernelGGL(upload_kernel, dim3(blocks), dim3(256), 0, st, (const uint4*)slot->dev_ptr, (uint4*)work_base(c),
-                           n16, c->static_call ? q_ctr_of(c) : nullptr, c->static_call ? 128 : 0);
+                           n16, c->static_call ? q_ctr_of(c) : nullptr, c->static_call ? (int)(kStaticCtrBytes / 4) : 0);
         TS_HIP(c, hipGetLastError());
     }
     return TS_OK;
@@ -549,6 +567,7 @@ extern "C" int ts_destroy(ts_ctx* c)
     if (c->d_work) (void)hipFree(c->d_work);
     if (c->d_part_o) (void)hipFree(c->d_part_o);
     if (c->d_part_ml) (void)hipFree(c->d_part_ml);
+    if (c->d_cmb_ctr) (void)hipFree(c->d_cmb_ctr);
     if (c->d_q_ctr) (void)hipFree(c->d_q_ctr);
     if (c->d_pf_part_o) (void)hipFree(c->d_pf_part_o);
     if (c->d_pf_part_ml) (void)hipFree(c->d_pf_part_ml);
@@ -634,6 +653,10 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         c->opt.mixed_mode = (int32_t)value;
         return TS_OK;
     }
+    if (!strcmp(name, "decode_merge_in_kernel")) {
+        c->merge_in_kernel = value != 0;
+        return TS_OK;
+    }
     if (!strcmp(name, "prefill_split_min_keys")) {
         if (value < 0 || value > (1 << 24) || value % 64) return fail(c, TS_ERR_INVALID_ARG, "prefill_split_min_keys must be a multiple of 64");
         c->opt.pf_split_min_keys = (int32_t)value;
@@ -672,6 +695,7 @@ extern "C" int ts_get_option(const ts_ctx* c, const char* name, int64_t* value)
     else if (!strcmp(name, "xcd_count")) *value = c->opt.xcds;
     else if (!strcmp(name, "prefill_widen_pages")) *value = c->opt.widen_pages;
     else if (!strcmp(name, "prefill_split_min_keys")) *value = c->opt.pf_split_min_keys;
+    else if (!strcmp(name, "decode_merge_in_kernel")) *value = c->merge_in_kernel ? 1 : 0;
     else if (!strcmp(name, "validate_block_table")) *value = c->validate_pages ? 1 : 0;
     else if (!strcmp(name, "kernel_timing")) *value = c->timing;
     else if (!strcmp(name, "scratch_allocations")) *value = c->n_alloc;
@@ -813,6 +837,8 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
     a.queue = (const QItem*)(wb + w.queue); a.q_off = (const int32_t*)(wb + w.q_off);
     a.n_queue = (int32_t)p.queue.size(); a.n_xcd = p.q_off.empty() ? 0 : (int32_t)p.q_off.size() - 1;
     a.q_ctr = q_ctr_of(c);
+    // (the merging form of the decode kernel exists for a prefetch depth of two tiles and outside the one-kernel launch)
+    a.cmb_ctr = c->merge_in_kernel && c->dec_nbuf == 2 && p.info.mixed_mode != TS_MIXED_ONE_KERNEL ? cmb_ctr_of(c, p.cmb.size()) : nullptr;
     a.dec_nbuf = c->dec_nbuf; a.mixed_wgs = c->mixed_wgs; a.n_cu = c->opt.n_cu;
     a.part_o = part_o_of(c); a.part_ml = part_ml_of(c);
     if (!p.wide.empty()) {
@@ -837,7 +863,7 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
             if (r == hipSuccess) r = (hipError_t)launch_prefill_resident(a, stream);
             if (r == hipSuccess) r = hipStreamWaitEvent(c->side, c->ev_fork, 0);
             if (r == hipSuccess) r = (hipError_t)launch_decode(a, (void*)c->side);
-            if (r == hipSuccess) r = (hipError_t)launch_combine(a, (void*)c->side);
+            if (r == hipSuccess && !a.cmb_ctr) r = (hipError_t)launch_combine(a, (void*)c->side);
             // (the join is made even after a failed launch: the side stream must not run on unordered)
             const hipError_t j1 = hipEventRecord(c->ev_join, c->side);
             const hipError_t j2 = j1 == hipSuccess ? hipStreamWaitEvent(st, c->ev_join, 0) : j1;
@@ -848,12 +874,12 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
         // mixed batch: decode items and prefill tiles share the CUs in one persistent launch
         e = (hipError_t)timed_launch(c, TS_K_MIXED, true, st, [&] { return launch_mixed(a, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "mixed launch");
-        e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_cmb > 0, st, [&] { return launch_combine(a, stream); });
+        e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_cmb > 0 && !a.cmb_ctr, st, [&] { return a.cmb_ctr ? 0 : launch_combine(a, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "combine launch");
     } else {
         e = (hipError_t)timed_launch(c, TS_K_DECODE, a.n_dec > 0, st, [&] { return launch_decode(a, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "decode launch");
-        e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_cmb > 0, st, [&] { return launch_combine(a, stream); });
+        e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_cmb > 0 && !a.cmb_ctr, st, [&] { return a.cmb_ctr ? 0 : launch_combine(a, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "combine launch");
         e = (hipError_t)timed_launch(c, TS_K_PREFILL, a.n_pf > 0, st, [&] { return launch_prefill(a, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "prefill launch");

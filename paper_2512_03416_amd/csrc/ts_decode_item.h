@@ -125,12 +125,14 @@ struct DecMerge {                          // LDS image of the non-leading waves
 // One decode item for KV head g, executed by a workgroup of WAVES waves.  All waves must call
 // it; it contains one workgroup barrier, and the caller must place another barrier before mg is
 // reused.
-template <typename KT, int NBUF, int WAVES, int D = 128>
+// MERGE: the code for merging a split row by its last item is compiled in (it is used when a.cmb_ctr is set).
+template <typename KT, int NBUF, int WAVES, int D = 128, bool MERGE = false>
 __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int g, DecMerge<WAVES, D>& mg)
 {
     constexpr int KB = D / 32, DB = D / 16;    // 32-dim steps of K Q^T, 16-dim blocks of O^T
     const int32_t TS_CONSTANT* itp = as_constant((const int32_t*)(a.dec + item_idx));
     const int it_row = itp[0], it_seq = itp[1], it_keys = itp[2], it_pb = itp[3], it_pe = itp[4], it_part = itp[5];
+    const int it_cmb = MERGE ? itp[6] : -1, it_part_first = MERGE ? itp[7] : -1;
     // (readfirstlane tells the compiler the wave index is uniform, which keeps everything derived
     // from it -- the page-id loads above all -- on the scalar unit)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -272,6 +274,66 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
                 ml[0] = M;
                 ml[1] = l_tot;
             }
+        }
+    }
+    if constexpr (!MERGE) return;
+    if (it_part < 0 || a.cmb_ctr == nullptr) return;
+
+    // ---- a split row: the last of its items to get here merges the partials (no launch for the merge) ----
+    // Release: this item's partials are visible device-wide before its arrival is counted; acquire: the item
+    // that counts the last arrival sees every other item's partials.  The merge reads all partials back from
+    // memory, its own included, in split order: the result does not depend on which item came last.
+    const int32_t TS_CONSTANT* cm = as_constant((const int32_t*)(a.cmb + it_cmb));
+    const int n_split = cm[2];
+    __threadfence();
+    int last = 0;
+    if (lane == 0) {
+        int32_t* ctr = a.cmb_ctr + (int64_t)it_cmb * Hkv + g;
+        const int seen = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        last = seen == n_split - 1;
+        if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    }
+    last = __builtin_amdgcn_readfirstlane(last);
+    if (!last) return;
+    __threadfence();
+    if (n < G) {
+        constexpr int kBatch = 4;
+        const int h = g * G + n;
+        const float* pml = a.part_ml + ((int64_t)it_part_first * Hq + h) * 2;     // split k: pml[k * Hq * 2 + {0, 1}]
+        const float* po = a.part_o + ((int64_t)it_part_first * Hq + h) * D + 4 * r;   // split k: po[k * Hq * D + 16 b]
+        const int64_t ml_step = (int64_t)Hq * 2, po_step = (int64_t)Hq * D;
+        float Mx = -INFINITY;
+        for (int k = 0; k < n_split; ++k) Mx = fmaxf(Mx, pml[k * ml_step]);
+        f32x4 sum[DB];
+#pragma unroll
+        for (int b = 0; b < DB; ++b) sum[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float L = 0.0f;
+        for (int k0 = 0; k0 < n_split; k0 += kBatch) {
+            float w[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int k = min(k0 + j, n_split - 1);
+                w[j] = k0 + j < n_split ? __builtin_amdgcn_exp2f(pml[k * ml_step] - Mx) : 0.0f;
+                L += k0 + j < n_split ? pml[k * ml_step + 1] * w[j] : 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int k = min(k0 + j, n_split - 1);
+#pragma unroll
+                for (int b = 0; b < DB; ++b) sum[b] += *(const f32x4*)(po + k * po_step + 16 * b) * w[j];
+            }
+        }
+        const float vscale = (sizeof(KT) == 1) ? a.v_scale[g] : 1.0f;
+        const float inv = vscale / L;
+        uint16_t* o = (uint16_t*)a.out + ((int64_t)it_row * Hq + h) * D + 4 * r;
+#pragma unroll
+        for (int b = 0; b < DB; ++b) {
+            const bf16x2 x = __builtin_convertvector(f32x2{sum[b][0] * inv, sum[b][1] * inv}, bf16x2);
+            const bf16x2 y = __builtin_convertvector(f32x2{sum[b][2] * inv, sum[b][3] * inv}, bf16x2);
+            uint2 wv;
+            wv.x = __builtin_bit_cast(uint32_t, x);
+            wv.y = __builtin_bit_cast(uint32_t, y);
+            *(uint2*)(o + 16 * b) = wv;
         }
     }
 }

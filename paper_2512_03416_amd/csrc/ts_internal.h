@@ -26,7 +26,8 @@ struct DecItem {          // one split of one decode row; launched once per KV h
     int32_t page_begin;   // [page_begin, page_end) of the sequence's page list
     int32_t page_end;
     int32_t part;         // partial slot, or -1 when the row has a single split
-    int32_t pad0, pad1;
+    int32_t cmb;          // split rows: index of the row in the combine list (its arrival counters), else -1
+    int32_t part_first;   // split rows: partial slot of the row's first split (the splits' slots are consecutive)
 };
 
 struct CmbItem {          // a decode row whose splits must be merged
@@ -197,6 +198,10 @@ struct AttnArgs {
     // ml [part][kv head][256 rows][2] = (reference maximum in log2 units, weight sum)
     const PfCmb* pfcmb; int32_t n_pfcmb;
     float* pf_part_o; float* pf_part_ml;
+    // Arrival counters of the split decode rows, one per (combine row, KV head), zero between launches: the
+    // workgroup that finds n_split - 1 in it is the last of the row and merges the partials itself.  NULL = the
+    // items only write their partials and combine_kernel merges them.
+    int32_t* cmb_ctr;
     // split-K partials: o [slot][Hq][D] fp32 (unnormalised), ml [slot][Hq][2] = (max, sum) in log2 units
     float* part_o; float* part_ml;
 };

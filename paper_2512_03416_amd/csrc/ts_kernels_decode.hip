@@ -23,6 +23,14 @@ __global__ __launch_bounds__(64 * kDecWaves) __attribute__((amdgpu_num_vgpr(64))
     decode_item<KT, 2, kDecWaves, D>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
 }
 
+// The same with the merge of split rows by their last item compiled in (option "decode_merge_in_kernel").
+template <typename KT, int D>
+__global__ __launch_bounds__(64 * kDecWaves) void decode_kernel_merging(AttnArgs a)
+{
+    __shared__ DecMerge<kDecWaves, D> mg;
+    decode_item<KT, 2, kDecWaves, D, true>(a, blockIdx.x / a.geo.Hkv, blockIdx.x % a.geo.Hkv, mg);
+}
+
 // Merge of a row's splits, in split order:  M = max m_i, out = sum o_i 2^(m_i-M) / sum l_i 2^(m_i-M).
 // The partials of up to eight splits are requested together and then added one after the other: the
 // sums keep their order, and a row of ten splits waits for four loads instead of thirty.
@@ -70,6 +78,10 @@ template <typename KT, int D>
 static int launch_decode_t(const AttnArgs& a, hipStream_t st)
 {
     dim3 grid((unsigned)a.n_dec * (unsigned)a.geo.Hkv), block(64 * kDecWaves);
+    if (a.cmb_ctr) {
+        hipLaunchKernelGGL((decode_kernel_merging<KT, D>), grid, block, 0, st, a);
+        return (int)hipGetLastError();
+    }
     switch (a.dec_nbuf) {
     case 3: hipLaunchKernelGGL((decode_kernel<KT, 3, D>), grid, block, 0, st, a); break;
     case 4: hipLaunchKernelGGL((decode_kernel<KT, 4, D>), grid, block, 0, st, a); break;

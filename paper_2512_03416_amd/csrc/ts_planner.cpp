@@ -290,10 +290,11 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
             int32_t n_split = (n_pages + L - 1) / L;
             int32_t per = (n_pages + n_split - 1) / n_split;
             n_split = (n_pages + per - 1) / per;
+            const int32_t cmb_idx = n_split > 1 ? (int32_t)p.cmb.size() : -1;
             if (n_split > 1) p.cmb.push_back(CmbItem{m.q_off, part, n_split, 0});
             for (int32_t k = 0; k < n_split; ++k) {
                 int32_t b = k * per, e = std::min(n_pages, b + per);
-                p.dec.push_back(DecItem{m.q_off, s, m.ctx_len, b, e, n_split > 1 ? part + k : -1, 0, 0});
+                p.dec.push_back(DecItem{m.q_off, s, m.ctx_len, b, e, n_split > 1 ? part + k : -1, cmb_idx, n_split > 1 ? part : -1});
             }
             if (n_split > 1) part += n_split;
         } else if (as_tiles) {

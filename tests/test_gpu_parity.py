@@ -112,6 +112,37 @@ def test_head_dim_64_mixed_batch_and_every_fp8_code():
     assert np.array_equal(out, ref)                          # weight 1 on one key: exact
 
 
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+def test_split_rows_merged_by_their_last_item_or_by_a_launch(kv):
+    """Rows cut into 2 ... 60 items: merged by the merge launch (default) and inside the decode kernel by the last
+    item to arrive; both within the bar, each bit-identical over 20 repetitions on one context (the order of the
+    sums is fixed, whichever item comes last), next to a prefill chunk in all three launch modes."""
+    import paper_2512_03416_amd as ts
+    g = gpu()
+    shape = AttnShape(32, 8, 128, "bf16", kv)
+    ctxs = [9000, 130, 1, 4000, 257, 33, 2100, 16, 7777, 640]
+    for q, c, modes in (([1] * len(ctxs), ctxs, [0]), ([1] * len(ctxs) + [300], ctxs + [300 + 1000], [2, 1, 0])):
+        mk = lambda: make_batch(shape, q, c, seed=34, pool_rule=1.2, value_mult=0.5 if kv == "bf16" else 1.0)
+        ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
+        for mode in modes:
+            for in_kernel in (1, 0):
+                b = g.to_dev(mk())
+                ctx = ts.Context(g.make_desc(b))
+                for k_, v_ in (("decode_split_pages", 9), ("mixed_mode", mode), ("decode_merge_in_kernel", in_kernel)):
+                    ctx.set_option(k_, v_)
+                print(f"[case] split rows kv={kv} rows={len(q)} mode={mode} in_kernel={in_kernel}", flush=True)
+                first = None
+                for rep in range(20):
+                    out, gk, gv = g.run_batch(b, ctx=ctx)
+                    if first is None:
+                        first = out
+                        assert same_bytes(gk, rk) and same_bytes(gv, rv)
+                        assert float(np.max(np.abs(out - ref))) <= TOL[kv]
+                    else:
+                        assert np.array_equal(out, first), f"repetition {rep} differs"
+                ctx.close()
+
+
 def test_decode_large_scores_and_shifting_maximum():
     # keys grow along the sequence so the running maximum keeps rising across pages and splits
     shape = AttnShape(8, 2, 128, "bf16", "bf16")
