@@ -609,11 +609,11 @@ extern "C" int ts_reserve(ts_ctx* c, int64_t max_tokens, int64_t max_seqs, int64
                          (size_t)std::min<int64_t>((int64_t)P, c->opt.widen_pages) * sizeof(WideItem) + S * sizeof(int32_t) + 16 * 16;
     int rc = ensure_work(c, bytes);
     if (rc != TS_OK) return rc;
-    if (desc_uses_mfma(c->desc) && c->opt.pf_split_min_keys > 0) {
+    if (desc_uses_mfma_tiles(c->desc) && c->opt.pf_split_min_keys > 0) {
         rc = ensure_pf_parts(c, (int64_t)c->opt.n_cu);
         if (rc != TS_OK) return rc;
     }
-    if (c->desc.kv_dtype == TS_FP8_E4M3 && desc_uses_mfma(c->desc) && c->opt.widen_pages > 0) {
+    if (c->desc.kv_dtype == TS_FP8_E4M3 && desc_uses_mfma_tiles(c->desc) && c->opt.widen_pages > 0) {
         rc = ensure_wide(c, std::min<int64_t>((int64_t)P, c->opt.widen_pages));
         if (rc != TS_OK) return rc;
     }

@@ -135,6 +135,7 @@ struct PlanOptions {
 // (head dim 64 or 128).  Everything else goes through the generic row kernel.
 bool desc_uses_mfma(const ts_attn_desc& d);
 bool desc_uses_mfma_decode(const ts_attn_desc& d);
+bool desc_uses_mfma_tiles(const ts_attn_desc& d);      // (head dim 64: bf16 pages only, one launch per class)
 int32_t prefill_tile_tokens(const ts_attn_desc& d);
 
 // Validates lengths; returns TS_OK or an error and fills err.

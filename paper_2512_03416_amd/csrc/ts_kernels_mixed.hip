@@ -53,9 +53,9 @@ __device__ __forceinline__ void drain_queues(const AttnArgs& a, LDS& sh)
         asm volatile("" : "+v"(t));                            // (see prefill_tile)
         if constexpr (WITH_DECODE) {
             if (kind == 0) decode_item<KT, NBUF, kPfWaves>(a, item, g, sh.mg);
-            else prefill_tile<PKT, WIDE>(a, item, g, sh.lds, t);
+            else prefill_tile<PKT, WIDE, 128>(a, item, g, sh.lds, t);
         } else {
-            prefill_tile<PKT, WIDE>(a, item, g, sh, t);
+            prefill_tile<PKT, WIDE, 128>(a, item, g, sh, t);
         }
         __syncthreads();                                       // LDS is reused by the next item
     }

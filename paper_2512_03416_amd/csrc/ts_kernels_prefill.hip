@@ -4,14 +4,14 @@
 namespace ts {
 
 // (held to 192 vector registers per lane like the resident form: the attribute counts in units of two)
-template <typename KT, bool WIDE>
+template <typename KT, bool WIDE, int D>
 __global__ __launch_bounds__(kPfThreads) __attribute__((amdgpu_num_vgpr(96))) void prefill_kernel(AttnArgs a)
 {
-    __shared__ PfLds lds;
+    __shared__ PfLdsT<D> lds;
     const int32_t TS_CONSTANT* slot = as_constant((const int32_t*)(a.pfmap + blockIdx.x));
     const int item_idx = slot[0], g = slot[1];
     if (item_idx < 0) return;                               // padding of the die-aware launch order
-    prefill_tile<KT, WIDE>(a, item_idx, g, lds, threadIdx.x);
+    prefill_tile<KT, WIDE, D>(a, item_idx, g, lds, threadIdx.x);
 }
 
 // fp8 caches: bf16 copies of the pages the prefill tiles will read, one workgroup per (page, KV head).  The
@@ -19,18 +19,21 @@ __global__ __launch_bounds__(kPfThreads) __attribute__((amdgpu_num_vgpr(96))) vo
 // token-fastest [D][16 slots] -- so the tile kernel copies them into LDS exactly like bf16 cache pages.  Every
 // e4m3 value is a bf16 value: the conversion is exact, and pages are copied whole (slots past the end of the
 // sequence hold whatever the cache holds; the tile kernel masks them as it does for a bf16 cache).
+template <int D>
 __global__ __launch_bounds__(256) void widen_kernel(AttnArgs a, uint16_t* __restrict__ wk, uint16_t* __restrict__ wv)
 {
     const int Hkv = a.geo.Hkv;
+    constexpr int TB = 16 * D;                                 // bytes of an e4m3 tile = elements of a tile
     const int item = blockIdx.x / Hkv, g = blockIdx.x % Hkv;
     const int32_t TS_CONSTANT* w = as_constant((const int32_t*)(a.wide + item));
     const int seq = w[0], pidx = w[1];
     const int64_t page = as_constant(a.block_table)[(int64_t)seq * a.geo.max_pages + pidx];
-    const uint8_t* ks = (const uint8_t*)a.k_cache + (page * Hkv + g) * 2048;
-    const uint8_t* vs = (const uint8_t*)a.v_cache + (page * Hkv + g) * 2048;
-    uint16_t* kd = wk + ((int64_t)item * Hkv + g) * 2048;
-    uint16_t* vd = wv + ((int64_t)item * Hkv + g) * 2048;
+    const uint8_t* ks = (const uint8_t*)a.k_cache + (page * Hkv + g) * TB;
+    const uint8_t* vs = (const uint8_t*)a.v_cache + (page * Hkv + g) * TB;
+    uint16_t* kd = wk + ((int64_t)item * Hkv + g) * TB;
+    uint16_t* vd = wv + ((int64_t)item * Hkv + g) * TB;
     const int t = threadIdx.x;
+    if (t >= TB / 8) return;
     // thread t takes 8 consecutive bytes of each tile.  K: bytes of chunk (c16 = t / 32, slot = (t / 2) % 16),
     // dims 16 c16 + 8 (t % 2) .. + 7 -> bf16 chunk (2 c16 + t % 2, slot).  V: elements 8 t .. 8 t + 7 keep their place.
     const uint2 kb = *(const uint2*)(ks + t * 8);
@@ -44,13 +47,15 @@ __global__ __launch_bounds__(256) void widen_kernel(AttnArgs a, uint16_t* __rest
 
 // Merge of the parts of a tile that was cut along the keys, in part order:
 //   M = max m_i,  out = sum o_i 2^(m_i - M) / sum l_i 2^(m_i - M)  (times the V scale of an fp8 cache).
-// One workgroup per (cut tile, KV head, 32 rows); 32 lanes hold the 128 dims of a row, 8 rows per step.  The
+// One workgroup per (cut tile, KV head, 32 rows); D / 4 lanes hold the dims of a row.  The
 // partial rows of up to eight parts are requested together, then added one after the other (the sums keep
 // their order).
 constexpr int kPfCmbRows = 32;
+template <int D>
 __global__ __launch_bounds__(256) void prefill_combine_kernel(AttnArgs a)
 {
-    constexpr int D = 128, kBatch = 8, kGroups = kPfPartRows / kPfCmbRows;
+    constexpr int kBatch = 8, kGroups = kPfPartRows / kPfCmbRows;
+    constexpr int kLanes = D / 4, kSub = 256 / kLanes;           // lanes per row (4 dims each), rows per step
     const int Hkv = a.geo.Hkv, G = a.geo.G, Hq = a.geo.Hq;
     const int grp = blockIdx.x % kGroups, g = (blockIdx.x / kGroups) % Hkv, ci = blockIdx.x / (kGroups * Hkv);
     const int32_t TS_CONSTANT* c = as_constant((const int32_t*)(a.pfcmb + ci));
@@ -58,11 +63,11 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(AttnArgs a)
     const int32_t TS_CONSTANT* it = as_constant((const int32_t*)(a.pf + item));
     const int row0 = it[1], tok_begin = it[4], tok_count = it[5];
     const float vscale = a.geo.kv_dtype == TS_FP8_E4M3 ? a.v_scale[g] : 1.0f;
-    const int lane = threadIdx.x & 31, sub = threadIdx.x >> 5;
+    const int lane = threadIdx.x % kLanes, sub = threadIdx.x / kLanes;
     const int64_t part_step = (int64_t)Hkv * kPfPartRows;          // rows between two parts of one (tile, head)
 #pragma unroll
-    for (int step = 0; step < kPfCmbRows / 8; ++step) {
-        const int rho = grp * kPfCmbRows + step * 8 + sub;
+    for (int step = 0; step < kPfCmbRows / kSub; ++step) {
+        const int rho = grp * kPfCmbRows + step * kSub + sub;
         const int t = rho / G, hd = rho - t * G;
         if (t >= tok_count) continue;
         const int64_t slot0 = ((int64_t)part0 * Hkv + g) * kPfPartRows + rho;
@@ -99,31 +104,38 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(AttnArgs a)
 int launch_prefill_combine(const AttnArgs& a, void* stream)
 {
     if (a.n_pfcmb <= 0) return (int)hipSuccess;
-    if (a.geo.D != 128 || !a.pf_part_o || !a.pf_part_ml) return (int)hipErrorInvalidValue;
+    if ((a.geo.D != 128 && a.geo.D != 64) || !a.pf_part_o || !a.pf_part_ml) return (int)hipErrorInvalidValue;
     const unsigned grid = (unsigned)a.n_pfcmb * (unsigned)a.geo.Hkv * (unsigned)(kPfPartRows / kPfCmbRows);
-    hipLaunchKernelGGL(prefill_combine_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+    if (a.geo.D == 64) hipLaunchKernelGGL(prefill_combine_kernel<64>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(prefill_combine_kernel<128>, dim3(grid), dim3(256), 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 
 int launch_widen(const AttnArgs& a, void* wide_k, void* wide_v, void* stream)
 {
     if (a.n_wide <= 0) return (int)hipSuccess;
-    if (a.geo.D != 128 || a.geo.kv_dtype != TS_FP8_E4M3 || !wide_k || !wide_v) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL(widen_kernel, dim3((unsigned)a.n_wide * (unsigned)a.geo.Hkv), dim3(256), 0, (hipStream_t)stream, a,
-                       (uint16_t*)wide_k, (uint16_t*)wide_v);
+    if ((a.geo.D != 128 && a.geo.D != 64) || a.geo.kv_dtype != TS_FP8_E4M3 || !wide_k || !wide_v) return (int)hipErrorInvalidValue;
+    const dim3 grid((unsigned)a.n_wide * (unsigned)a.geo.Hkv);
+    if (a.geo.D == 64) hipLaunchKernelGGL(widen_kernel<64>, grid, dim3(256), 0, (hipStream_t)stream, a, (uint16_t*)wide_k, (uint16_t*)wide_v);
+    else hipLaunchKernelGGL(widen_kernel<128>, grid, dim3(256), 0, (hipStream_t)stream, a, (uint16_t*)wide_k, (uint16_t*)wide_v);
     return (int)hipGetLastError();
 }
 
 int launch_prefill(const AttnArgs& a, void* stream)
 {
     if (a.n_pf <= 0) return (int)hipSuccess;
-    if (a.geo.D != 128 || a.geo.q_dtype != TS_BF16) return (int)hipErrorInvalidValue;
+    if ((a.geo.D != 128 && a.geo.D != 64) || a.geo.q_dtype != TS_BF16) return (int)hipErrorInvalidValue;
     dim3 grid((unsigned)a.n_pfmap), block(kPfThreads);
     hipStream_t st = (hipStream_t)stream;
-    // (an fp8 cache whose pages were widened beforehand is read through the bf16 form)
-    if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_kernel<uint16_t, false>), grid, block, 0, st, a);
-    else if (a.geo.kv_dtype == TS_FP8_E4M3 && a.wide_base) hipLaunchKernelGGL((prefill_kernel<uint16_t, true>), grid, block, 0, st, a);
-    else if (a.geo.kv_dtype == TS_FP8_E4M3) hipLaunchKernelGGL((prefill_kernel<uint8_t, false>), grid, block, 0, st, a);
+    // (an fp8 cache whose pages were widened beforehand is read through the bf16 form; head dim 64 has no other)
+    if (a.geo.D == 64) {
+        if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_kernel<uint16_t, false, 64>), grid, block, 0, st, a);
+        else if (a.geo.kv_dtype == TS_FP8_E4M3 && a.wide_base) hipLaunchKernelGGL((prefill_kernel<uint16_t, true, 64>), grid, block, 0, st, a);
+        else return (int)hipErrorInvalidValue;
+    }
+    else if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_kernel<uint16_t, false, 128>), grid, block, 0, st, a);
+    else if (a.geo.kv_dtype == TS_FP8_E4M3 && a.wide_base) hipLaunchKernelGGL((prefill_kernel<uint16_t, true, 128>), grid, block, 0, st, a);
+    else if (a.geo.kv_dtype == TS_FP8_E4M3) hipLaunchKernelGGL((prefill_kernel<uint8_t, false, 128>), grid, block, 0, st, a);
     else return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
 }

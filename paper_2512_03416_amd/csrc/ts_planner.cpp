@@ -27,6 +27,11 @@ bool desc_uses_mfma_decode(const ts_attn_desc& d)
            (d.kv_dtype == TS_BF16 || d.kv_dtype == TS_FP8_E4M3);
 }
 
+bool desc_uses_mfma_tiles(const ts_attn_desc& d)
+{
+    return desc_uses_mfma_decode(d);
+}
+
 int32_t prefill_tile_tokens(const ts_attn_desc& d)
 {
     int G = d.num_q_heads / d.num_kv_heads;
@@ -221,6 +226,15 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     p = Plan();
     const bool mfma = desc_uses_mfma(d) && !opt.generic_only;
     const bool mfma_dec = desc_uses_mfma_decode(d) && !opt.generic_only;
+    // fp8 caches: can the pages of the chunks' sequences be widened to bf16 for this pass (see below)?
+    int64_t chunk_pages = 0;
+    for (int s = 0; s < num_seqs; ++s)
+        if (q_lens[s] > 1) chunk_pages += (ctx_lens[s] + kPage - 1) / kPage;
+    const bool widen = d.kv_dtype == TS_FP8_E4M3 && chunk_pages > 0 && opt.widen_pages > 0 && chunk_pages <= opt.widen_pages;
+    // Chunk rows run as matrix-core tiles; with head dim 64 the tiles read bf16 pages only (a bf16 cache, or the
+    // widened copies of an e4m3 cache), otherwise the rows go to the generic kernel.
+    const bool mfma_tiles = desc_uses_mfma_tiles(d) && !opt.generic_only && !opt.prefill_generic &&
+                            (d.head_dim == 128 || d.kv_dtype == TS_BF16 || widen);
     const int Hkv = d.num_kv_heads;
     p.seqs.resize((size_t)num_seqs + 1);
     int32_t off = 0;
@@ -257,7 +271,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
 
     const int32_t TT = opt.tile_tokens > 0 ? opt.tile_tokens : prefill_tile_tokens(d);
     int64_t tile_heads = 0;                                // prefill workgroups of the batch
-    if (mfma && !opt.prefill_generic)
+    if (mfma_tiles)
         for (int s = 0; s < num_seqs; ++s)
             if (p.seqs[s].q_len > 1) tile_heads += (int64_t)((p.seqs[s].q_len + TT - 1) / TT) * Hkv;
     // How a batch with both kinds of rows is launched.  Co-resident by default; the fork and join of the
@@ -284,7 +298,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
         const SeqMeta& m = p.seqs[s];
         if (m.q_len == 0) continue;
         const bool as_decode = mfma_dec && m.q_len == 1;
-        const bool as_tiles = mfma && m.q_len > 1 && !opt.prefill_generic;
+        const bool as_tiles = mfma_tiles && m.q_len > 1;
         if (as_decode) {
             int32_t n_pages = (m.ctx_len + kPage - 1) / kPage;
             int32_t n_split = (n_pages + L - 1) / L;
@@ -336,18 +350,13 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     // fp8 caches: the pages of the chunks' sequences are widened to bf16 once per pass (every tile of a chunk
     // reads the whole prefix: widening inside the tiles repeats the conversion once per tile and costs the tile
     // kernel 8 % of its time), provided they fit the scratch the option allows
-    if (d.kv_dtype == TS_FP8_E4M3 && !p.pf.empty() && opt.widen_pages > 0) {
-        int64_t need = 0;
-        for (int s = 0; s < num_seqs; ++s)
-            if (p.seqs[s].q_len > 1) need += (p.seqs[s].ctx_len + kPage - 1) / kPage;
-        if (need <= opt.widen_pages) {
-            p.wide_base.assign((size_t)num_seqs, -1);
-            for (int s = 0; s < num_seqs; ++s) {
-                if (p.seqs[s].q_len <= 1) continue;
-                p.wide_base[s] = (int32_t)p.wide.size();
-                const int32_t n_pages = (p.seqs[s].ctx_len + kPage - 1) / kPage;
-                for (int32_t j = 0; j < n_pages; ++j) p.wide.push_back(WideItem{s, j});
-            }
+    if (widen && !p.pf.empty()) {
+        p.wide_base.assign((size_t)num_seqs, -1);
+        for (int s = 0; s < num_seqs; ++s) {
+            if (p.seqs[s].q_len <= 1) continue;
+            p.wide_base[s] = (int32_t)p.wide.size();
+            const int32_t n_pages = (p.seqs[s].ctx_len + kPage - 1) / kPage;
+            for (int32_t j = 0; j < n_pages; ++j) p.wide.push_back(WideItem{s, j});
         }
     }
     p.info.widened_pages = (int64_t)p.wide.size();

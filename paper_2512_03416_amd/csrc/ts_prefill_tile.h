@@ -92,10 +92,13 @@ template <typename KT, bool WIDE> constexpr int kPfLookahead = sizeof(KT) == 1 ?
 //   V page: piece (dim d, token half t) at [d / 32][t][d % 32]: the A operand (32 dims x 16
 //           tokens) of dim block b is 1 KB at lane * 16.
 // Stage i lives in slot i % kPfRing of both rings.
-struct __align__(16) PfLds {
-    unsigned char k[kPfRing][4 * 4096];
-    unsigned char v[kPfRing][4 * 4096];
+// D = head dim (128 or 64): a page takes 32 D bytes in either ring.
+template <int D>
+struct __align__(16) PfLdsT {
+    unsigned char k[kPfRing][4 * 32 * D];
+    unsigned char v[kPfRing][4 * 32 * D];
 };
+using PfLds = PfLdsT<128>;
 __device__ __forceinline__ int swap23(int s) { return (s & 3) | ((s & 4) << 1) | ((s & 8) >> 1); }
 __device__ __forceinline__ int k_piece_offset(int chunk, int slot) { return (chunk * 16 + swap23(slot)) * 16; }
 __device__ __forceinline__ int v_piece_offset(int dim, int half) { return (((dim >> 5) * 2 + half) * 32 + (dim & 31)) * 16; }
@@ -126,17 +129,24 @@ __device__ __forceinline__ void copy_1k_to_lds(uint32_t lds_addr, const void* ba
 }
 __device__ __forceinline__ int copy_k_lane_offset(int lane) { return (lane >> 4) * 256 + swap23(lane & 15) * 16; }
 __device__ __forceinline__ int copy_v_lane_offset(int lane) { return (lane & 31) * 32 + (lane >> 5) * 16; }
+template <int D>
 __device__ __forceinline__ void stage_copy_bf16(const char* kbase, const char* vbase, int Hkv, int stage, int page_id, int g,
-                                                int wave, int lane, PfLds& lds)
+                                                int wave, int lane, PfLdsT<D>& lds)
 {
-    const int64_t off = ((int64_t)page_id * Hkv + g) * 4096 + (wave & 1) * 2048;   // (page_id: of page 4 stage + wave / 2)
+    constexpr int PB = 32 * D;                             // bytes of a page: a wave copies half a page of K and of V
+    const int64_t off = ((int64_t)page_id * Hkv + g) * PB + (wave & 1) * (PB / 2);   // (page_id: of page 4 stage + wave / 2)
     const int slot = stage % kPfRing;
     // K: LDS piece [c0 + lane / 16][lane % 16] takes cache piece (c0 + lane / 16, swap23(lane % 16))
     // V: LDS piece [b0][lane / 32][lane % 32] takes cache piece (dim 32 b0 + lane % 32, half lane / 32)
-    copy_2k_to_lds(lds_address(lds.k[slot]) + wave * 2048, kbase + off, copy_k_lane_offset(lane));
-    copy_2k_to_lds(lds_address(lds.v[slot]) + wave * 2048, vbase + off, copy_v_lane_offset(lane));
+    if constexpr (D == 128) {
+        copy_2k_to_lds(lds_address(lds.k[slot]) + wave * (PB / 2), kbase + off, copy_k_lane_offset(lane));
+        copy_2k_to_lds(lds_address(lds.v[slot]) + wave * (PB / 2), vbase + off, copy_v_lane_offset(lane));
+    } else {
+        copy_1k_to_lds<0>(lds_address(lds.k[slot]) + wave * (PB / 2), kbase + off, copy_k_lane_offset(lane));
+        copy_1k_to_lds<0>(lds_address(lds.v[slot]) + wave * (PB / 2), vbase + off, copy_v_lane_offset(lane));
+    }
 }
-constexpr int kCopiesPerStage = 4;                         // vmcnt units one stage_copy_bf16 adds per wave
+template <int D> constexpr int kCopiesPerStage = D / 32;   // vmcnt units one stage_copy_bf16 adds per wave (1 KB each)
 template <int N> __device__ __forceinline__ void pf_wait_copies()
 {
     static_assert(N >= 0 && N < 16, "vmcnt immediate");
@@ -144,13 +154,15 @@ template <int N> __device__ __forceinline__ void pf_wait_copies()
 }
 // V rows of tokens at or beyond ctx_len hold whatever the cache page held (possibly NaN patterns):
 // their weights are zero, but 0 x NaN is not, so they are cleared in LDS once the stage has landed.
+template <int D>
 __device__ __forceinline__ void clear_v_tail(unsigned char* lv, int stage, int ctx_len, int tid)
 {
-    const int pg = tid >> 7, dim = tid & 127;
+    if (tid >= 4 * D) return;                              // one thread per (page of the stage, dim)
+    const int pg = tid / D, dim = tid % D;
     const int nvalid = ctx_len - (stage * kStageTok + pg * kPage);     // valid tokens of this page
     if (nvalid >= kPage) return;
-    uint4* lo = (uint4*)(lv + pg * 4096 + v_piece_offset(dim, 0));
-    uint4* hi = (uint4*)(lv + pg * 4096 + v_piece_offset(dim, 1));
+    uint4* lo = (uint4*)(lv + pg * (32 * D) + v_piece_offset(dim, 0));
+    uint4* hi = (uint4*)(lv + pg * (32 * D) + v_piece_offset(dim, 1));
     *lo = keep_first16(*lo, max(nvalid, 0));
     *hi = keep_first16(*hi, max(nvalid - 8, 0));
 }
@@ -183,16 +195,39 @@ __device__ __forceinline__ void stage_store(const StageFp8& st, unsigned char* l
     *(uint4*)(lv + pg * 4096 + v_piece_offset(c, 1)) = make_uint4(b2.x, b2.y, b3.x, b3.y);
 }
 
+// Order of the MFMAs of a steady-state iteration.  Values 0 .. NV-1 = V^T P^T step u (page u / DB, dim block
+// u % DB; NV = 2 DB), NV .. NV+KS-1 = K Q^T step u - NV.  warm: the K operands of the first slots were read
+// during the previous iteration; cold: the K stage has only just been published, so V^T P^T steps come first.
+template <int D>
+__device__ __forceinline__ constexpr int pf_slot_op(bool warm, int j)
+{
+    if constexpr (D == 128) {
+        constexpr int kWarm[16] = {0, 8, 1, 9, 2, 10, 3, 11, 4, 12, 5, 13, 6, 14, 7, 15};
+        constexpr int kCold[16] = {0, 1, 2, 8, 3, 9, 4, 10, 5, 11, 6, 12, 7, 13, 14, 15};
+        return warm ? kWarm[j] : kCold[j];
+    } else {
+        constexpr int kWarm[8] = {0, 4, 1, 5, 2, 6, 3, 7};
+        constexpr int kCold[8] = {0, 1, 2, 4, 3, 5, 6, 7};
+        return warm ? kWarm[j] : kCold[j];
+    }
+}
+
 // One causal tile for KV head g, executed by a workgroup of kPfThreads threads.  All threads must call
 // it; it ends with a workgroup barrier, so lds may be reused right after it returns.
 // tid: the thread's index in the workgroup (a caller that runs tiles in a loop passes an opaque copy, so
 // that the many lane offsets derived from it are worked out per tile instead of being kept in registers
 // across the loop).
 // WIDE: KT is bf16 and the pages are the widened copies of an e4m3 cache.
-template <typename KT, bool WIDE>
-__device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, int g, PfLds& lds, int tid)
+// D: head dim, 128 or 64 (64: bf16 pages only -- a bf16 cache or widened copies).
+template <typename KT, bool WIDE, int D = 128>
+__device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, int g, PfLdsT<D>& lds, int tid)
 {
-    constexpr int D = 128, KS = 8, DB = 4, kHalf = 32;     // KS: 16-dim steps of K Q^T, DB: 32-dim blocks of O^T
+    constexpr int KS = D / 16, DB = D / 32, kHalf = 32;    // KS: 16-dim steps of K Q^T, DB: 32-dim blocks of O^T
+    constexpr int PB = 32 * D;                             // bytes of a (bf16) page in LDS and in a bf16 cache
+    constexpr int NV = 2 * DB, NSLOT = NV + KS;            // MFMAs of an iteration: V^T P^T steps, then both products
+    constexpr int WPS = 16 / NSLOT;                        // weights formed per MFMA slot (1 or 2)
+    static_assert(D == 128 || (D == 64 && sizeof(KT) == 2), "head dim 64 reads bf16 pages");
+    static_assert(NSLOT * WPS == 16, "16 weights per lane and half-stage");
     // (through the constant address space: the tile's description is wave-uniform and belongs in scalar registers)
     const int32_t TS_CONSTANT* itp = as_constant((const int32_t*)(a.pf + item_idx));
     const PfItem it{itp[0], itp[1], itp[2], itp[3], itp[4], itp[5], itp[6], itp[7], itp[8], itp[9], 0, 0};
@@ -250,11 +285,11 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     float m_ref = -INFINITY;                               // reference maximum of the row (scaled log2 units)
 
     // lane's operand addresses of half-stage hs inside the LDS rings.  K operand of dim step s:
-    // 16 bytes at kptr + 512 s.  V operand of page t, dim block b: 16 bytes at vptr + 4096 t + 1024 b.
+    // 16 bytes at kptr + 512 s.  V operand of page t, dim block b: 16 bytes at vptr + PB t + 1024 b.
     auto kptr = [&](int hs) {
-        return lds.k[(hs >> 1) % kPfRing] + (hs & 1) * 8192 + (n >> 4) * 4096 + h * 256 + (n & 15) * 16;
+        return lds.k[(hs >> 1) % kPfRing] + (hs & 1) * (2 * PB) + (n >> 4) * PB + h * 256 + (n & 15) * 16;
     };
-    auto vptr = [&](int hs) { return lds.v[(hs >> 1) % kPfRing] + (hs & 1) * 8192 + lane * 16; };
+    auto vptr = [&](int hs) { return lds.v[(hs >> 1) % kPfRing] + (hs & 1) * (2 * PB) + lane * 16; };
     auto lds16 = [](const unsigned char* p) { return u4_bf16x8(*(const uint4*)p); };
     auto mfma = [](bf16x8 x, bf16x8 y, f32x16 z) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, z, 0, 0, 0); };
     auto pack2 = [](float x, float y) {
@@ -320,7 +355,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int b = 0; b < DB; ++b) acc[b] = mfma(lds16(lv + t * 4096 + b * 1024), pop[t], acc[b]);
+            for (int b = 0; b < DB; ++b) acc[b] = mfma(lds16(lv + t * PB + b * 1024), pop[t], acc[b]);
     };
 
     // ---- steady state: one iteration = V^T P^T of half-stage hs and K Q^T of hs+2 on the matrix
@@ -341,24 +376,26 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     const char* cp_k = nullptr;                            // ... and what it reads (wave-uniform)
     const char* cp_v = nullptr;
     const int cp_k_src = copy_k_lane_offset(lane), cp_v_src = copy_v_lane_offset(lane);
-    auto copy_quarter = [&](int q) {
-        if (q == 0) copy_1k_to_lds<0>(cp_lds_k, cp_k, cp_k_src);
-        if (q == 1) copy_1k_to_lds<1024>(cp_lds_k, cp_k, cp_k_src);
-        if (q == 2) copy_1k_to_lds<0>(cp_lds_v, cp_v, cp_v_src);
-        if (q == 3) copy_1k_to_lds<1024>(cp_lds_v, cp_v, cp_v_src);
+    auto copy_quarter = [&](int q) {                       // q < kCopiesPerStage<D>: one 1 KB copy each
+        if constexpr (D == 128) {
+            if (q == 0) copy_1k_to_lds<0>(cp_lds_k, cp_k, cp_k_src);
+            if (q == 1) copy_1k_to_lds<1024>(cp_lds_k, cp_k, cp_k_src);
+            if (q == 2) copy_1k_to_lds<0>(cp_lds_v, cp_v, cp_v_src);
+            if (q == 3) copy_1k_to_lds<1024>(cp_lds_v, cp_v, cp_v_src);
+        } else {
+            if (q == 0) copy_1k_to_lds<0>(cp_lds_k, cp_k, cp_k_src);
+            if (q == 1) copy_1k_to_lds<0>(cp_lds_v, cp_v, cp_v_src);
+        }
     };
     bf16x8 vpre[3], kpre[2];
     auto fast_iter = [&](auto kin_tag, auto kout_tag, auto dma_tag, int hs, bool masked, const f32x16& s1, f32x16& s2,
                          const bf16x8 (&pop0)[2], bf16x8 (&pop1)[2]) {
         constexpr bool KIN = decltype(kin_tag)::value, KOUT = decltype(kout_tag)::value, DMA = decltype(dma_tag)::value;
-        // slot -> MFMA: values 0..7 = V^T P^T step u (page u / 4, dim block u % 4), 8..15 = K Q^T step u - 8
-        constexpr int kWarm[16] = {0, 8, 1, 9, 2, 10, 3, 11, 4, 12, 5, 13, 6, 14, 7, 15};
-        constexpr int kCold[16] = {0, 1, 2, 8, 3, 9, 4, 10, 5, 11, 6, 12, 7, 13, 14, 15};
         const unsigned char* lk = kptr(hs + 2);
         const unsigned char* lv = vptr(hs);
         const unsigned char* lvn = vptr(hs + 1);
         const unsigned char* lkn = kptr(hs + 3);
-        auto v_at = [&](const unsigned char* base, int u) { return lds16(base + (u >> 2) * 4096 + (u & 3) * 1024); };
+        auto v_at = [&](const unsigned char* base, int u) { return lds16(base + (u / DB) * PB + (u % DB) * 1024); };
         // The weights of hs+1 are formed against the current reference maximum without looking at the
         // scores first; their sum shows afterwards whether one of them was above 2^kRaisePf, i.e. that
         // the maximum has to be raised (a sum above 16 x 2^kRaisePf needs such a weight; larger weights
@@ -366,7 +403,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         // then are the weights of this half-stage formed again (the scores are still there).
         const float nm = -m_ref;
         const float l_before = l_part;
-        bf16x8 kop[KS], vop[2 * DB];
+        bf16x8 kop[KS], vop[NV];
         uint32_t w[8];
         constexpr int LA = kPfLookahead<KT, WIDE>;
         __builtin_amdgcn_sched_barrier(0);
@@ -374,57 +411,61 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         // stage was already published: KIN), else here
 #pragma unroll
         for (int p = 0; p < LA; ++p) {
-            const int op = KIN ? kWarm[p] : kCold[p];
-            if (op < 8) vop[op] = vpre[op];
-            else if constexpr (KIN) kop[op - 8] = kpre[op - 8];
-            else kop[op - 8] = lds16(lk + (op - 8) * 512);
+            const int op = pf_slot_op<D>(KIN, p);
+            if (op < NV) vop[op] = vpre[op];
+            else if constexpr (KIN) kop[op - NV] = kpre[op - NV];
+            else kop[op - NV] = lds16(lk + (op - NV) * 512);
         }
         // The weight arithmetic is spread over the slots such that no instruction uses a result of its
-        // own slot: slot j scales score j+1, takes the exponential of score j, adds weight j-1 to the
-        // row sum and (even j) packs the weights j-2 and j-1.  Only instructions that measurably run in
-        // the shadow of an MFMA for free are used here (fma, exp, add, pack; the bf16 dot-product
-        // instruction, which would sum two packed weights at once, is not one of them: it delays the
-        // MFMAs of the SIMD).
+        // own step: step i scales score i+1, takes the exponential of score i, adds weight i-1 to the
+        // row sum and (even i) packs the weights i-2 and i-1; a slot carries WPS steps (one with 16 MFMAs per
+        // iteration, two with 8).  Only instructions that measurably run in the shadow of an MFMA for free are
+        // used here (fma, exp, add, pack; the bf16 dot-product instruction, which would sum two packed weights
+        // at once, is not one of them: it delays the MFMAs of the SIMD).
         float t_next = __builtin_fmaf(s1[0], c, nm);
         float p_a = 0.f, p_b = 0.f;                        // the two most recent weights
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int op = KIN ? kWarm[j] : kCold[j];
-            if (op < 8) {
-                acc[op & 3] = mfma(vop[op], pop0[op >> 2], acc[op & 3]);
-            } else {
-                if (op == 8) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) s2[v] = 0.f;
-                }
-                s2 = mfma(kop[op - 8], qb[op - 8], s2);
-            }
-            // read the operand of the MFMA LA slots on; the last LA slots read the first operands of the next
-            // iteration (its K operands only if their stage is already published: KOUT)
-            if (j + LA < 16) {
-                const int nx = KIN ? kWarm[j + LA] : kCold[j + LA];
-                if (nx < 8) vop[nx] = v_at(lv, nx);
-                else kop[nx - 8] = lds16(lk + (nx - 8) * 512);
-            } else {
-                const int nx = KOUT ? kWarm[j + LA - 16] : kCold[j + LA - 16];
-                if (nx < 8) vpre[nx] = v_at(lvn, nx);
-                else if constexpr (KOUT) kpre[nx - 8] = lds16(lkn + (nx - 8) * 512);
-            }
-            if (j >= 1) {
-                l_part += (j & 1) ? p_a : p_b;             // weight j-1
+        auto weight_step = [&](int i) {
+            if (i >= 1) {
+                l_part += (i & 1) ? p_a : p_b;             // weight i-1
                 asm volatile("" : "+v"(l_part));           // (keeps the instruction in this slot)
-                if (!(j & 1)) {
-                    w[(j - 2) >> 1] = pack2(p_a, p_b);
-                    asm volatile("" : "+v"(w[(j - 2) >> 1]));
+                if (!(i & 1)) {
+                    w[(i - 2) >> 1] = pack2(p_a, p_b);
+                    asm volatile("" : "+v"(w[(i - 2) >> 1]));
                 }
             }
             const float t_cur = t_next;
-            if (j + 1 < 16) t_next = __builtin_fmaf(s1[j + 1], c, nm);
+            if (i + 1 < 16) t_next = __builtin_fmaf(s1[i + 1], c, nm);
             const float p = __builtin_amdgcn_exp2f(t_cur);
-            if (j & 1) p_b = p; else p_a = p;
+            if (i & 1) p_b = p; else p_a = p;
+        };
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < NSLOT; ++j) {
+            const int op = pf_slot_op<D>(KIN, j);
+            if (op < NV) {
+                acc[op % DB] = mfma(vop[op], pop0[op / DB], acc[op % DB]);
+            } else {
+                if (op == NV) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s2[v] = 0.f;
+                }
+                s2 = mfma(kop[op - NV], qb[op - NV], s2);
+            }
+            // read the operand of the MFMA LA slots on; the last LA slots read the first operands of the next
+            // iteration (its K operands only if their stage is already published: KOUT)
+            if (j + LA < NSLOT) {
+                const int nx = pf_slot_op<D>(KIN, j + LA);
+                if (nx < NV) vop[nx] = v_at(lv, nx);
+                else kop[nx - NV] = lds16(lk + (nx - NV) * 512);
+            } else {
+                const int nx = pf_slot_op<D>(KOUT, j + LA - NSLOT);
+                if (nx < NV) vpre[nx] = v_at(lvn, nx);
+                else if constexpr (KOUT) kpre[nx - NV] = lds16(lkn + (nx - NV) * 512);
+            }
+#pragma unroll
+            for (int k = 0; k < WPS; ++k) weight_step(j * WPS + k);
             if constexpr (DMA) {
-                if ((j & 3) == 3) copy_quarter(j >> 2);
+                if ((j & 3) == 3 && (j >> 2) < kCopiesPerStage<D>) copy_quarter(j >> 2);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -480,9 +521,9 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     // page again (nobody reads it).  The bodies of the draining loop copy nothing.
     auto top = [&](int i) {
         if constexpr (kCopy) {
-            const int64_t off = ((int64_t)pid_next * a.geo.Hkv + g) * 4096 + (wave & 1) * 2048;
-            cp_lds_k = lds_address(lds.k[(i + 3) % kPfRing]) + wave * 2048;
-            cp_lds_v = lds_address(lds.v[(i + 3) % kPfRing]) + wave * 2048;
+            const int64_t off = ((int64_t)pid_next * a.geo.Hkv + g) * PB + (wave & 1) * (PB / 2);
+            cp_lds_k = lds_address(lds.k[(i + 3) % kPfRing]) + wave * (PB / 2);
+            cp_lds_v = lds_address(lds.v[(i + 3) % kPfRing]) + wave * (PB / 2);
             cp_k = kbase + off;
             cp_v = vbase + off;
         } else {
@@ -504,12 +545,12 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     auto bottom = [&](int i, auto steady_tag) {
         if constexpr (kCopy) {
             // the copies of stage i+2 must have landed; those this body issued (steady bodies) may still fly
-            if constexpr (decltype(steady_tag)::value) pf_wait_copies<kCopiesPerStage>(); else pf_wait_copies<0>();
+            if constexpr (decltype(steady_tag)::value) pf_wait_copies<kCopiesPerStage<D>>(); else pf_wait_copies<0>();
         }
         __syncthreads();
         if constexpr (kCopy) {
             if (i + 2 == clear_stage) {                    // tile-uniform, at most once per tile
-                clear_v_tail(lds.v[clear_stage % kPfRing], clear_stage, ctx_rel, opaque(tid));
+                clear_v_tail<D>(lds.v[clear_stage % kPfRing], clear_stage, ctx_rel, opaque(tid));
                 __syncthreads();
             }
         }
@@ -519,7 +560,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         pid_next = page_id(3);
         stage_copy_bf16(kbase, vbase, a.geo.Hkv, 0, p0, g, wave, lane, lds);
         if (n_stage > 1) stage_copy_bf16(kbase, vbase, a.geo.Hkv, 1, p1, g, wave, lane, lds);
-        if (n_stage > 2) { stage_copy_bf16(kbase, vbase, a.geo.Hkv, 2, p2, g, wave, lane, lds); pf_wait_copies<kCopiesPerStage>(); }
+        if (n_stage > 2) { stage_copy_bf16(kbase, vbase, a.geo.Hkv, 2, p2, g, wave, lane, lds); pf_wait_copies<kCopiesPerStage<D>>(); }
         else pf_wait_copies<0>();
     } else {
         const int32_t p0 = page_id(0), p1 = page_id(1), p2 = page_id(2);
@@ -534,7 +575,7 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     __syncthreads();
     if constexpr (kCopy) {
         if (clear_stage == 0 || clear_stage == 1) {
-            clear_v_tail(lds.v[clear_stage], clear_stage, ctx_rel, opaque(tid));
+            clear_v_tail<D>(lds.v[clear_stage], clear_stage, ctx_rel, opaque(tid));
             __syncthreads();
         }
     }
@@ -564,10 +605,11 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     constexpr std::false_type no{};
     constexpr std::bool_constant<kCopy> dma{};
     {                                                      // V operands of the first slots of the first iteration
-        constexpr int kColdHead[4] = {0, 1, 2, 8};
 #pragma unroll
-        for (int p = 0; p < kPfLookahead<KT, WIDE>; ++p)
-            if (kColdHead[p] < 8) vpre[kColdHead[p]] = lds16(vptr(0) + kColdHead[p] * 1024);
+        for (int p = 0; p < kPfLookahead<KT, WIDE>; ++p) {
+            const int op = pf_slot_op<D>(false, p);
+            if (op < NV) vpre[op] = lds16(vptr(0) + (op / DB) * PB + (op % DB) * 1024);
+        }
     }
     for (; i < n_plain; ++i) {
         top(i);
@@ -612,7 +654,8 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
         __syncthreads();                                   // LDS may be reused by the caller
         return;
     }
-    constexpr int kOutStride = 272;
+    constexpr int kOutStride = 2 * D + 16;                 // bytes of a staged row (16 bytes of padding against bank conflicts)
+    constexpr int kLanesPerRow = D / 8, kRowsPerStep = 64 / kLanesPerRow;
     const int tid_o = opaque(tid), wave_o = __builtin_amdgcn_readfirstlane(tid_o >> 6), lane_o = tid_o & 63,
               h_o = lane_o >> 5, n_o = lane_o & 31;
     unsigned char* ob = (unsigned char*)&lds + wave_o * (32 * kOutStride);
@@ -631,15 +674,16 @@ __device__ __forceinline__ void prefill_tile(const AttnArgs& a, int item_idx, in
     __builtin_amdgcn_wave_barrier();                       // (the rows are read back by other lanes of this wave)
     const float inv_g = 1.0f / (float)opaque_uniform(G);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int r = 4 * i + (lane_o >> 4);               // row of the wave, 16 lanes per row
+    for (int i = 0; i < 32 / kRowsPerStep; ++i) {
+        const int r = kRowsPerStep * i + lane_o / kLanesPerRow;    // row of the wave, D / 8 lanes per row
+        const int piece = lane_o % kLanesPerRow;
         const int rho_r = 32 * wave_o + r;
         const int t_r = (int)(((float)rho_r + 0.5f) * inv_g);      // rho_r / G (exact for rho_r < 256, G <= 16)
         const int hd_r = rho_r - t_r * G;
-        const uint4 v = *(const uint4*)(ob + r * kOutStride + (lane_o & 15) * 16);
+        const uint4 v = *(const uint4*)(ob + r * kOutStride + piece * 16);
         if (t_r < it.tok_count) {
             uint16_t* o = (uint16_t*)a.out + ((int64_t)(it.row0 + it.tok_begin + t_r) * Hq + g * G + hd_r) * D;
-            *(uint4*)(o + (lane_o & 15) * 8) = v;
+            *(uint4*)(o + piece * 8) = v;
         }
     }
     __syncthreads();                                       // LDS may be reused by the caller

@@ -89,13 +89,15 @@ def test_decode_split_and_prefetch_variants(split, nbuf, head_dim):
 
 
 def test_head_dim_64_mixed_batch_and_every_fp8_code():
-    """Head dim 64 with a bf16 or e4m3 cache: decode rows through the matrix-core items, chunk rows through the
-    generic kernel, in one pass; every finite e4m3 code through K and V of single-key decode rows."""
+    """Head dim 64 with a bf16 or e4m3 cache: decode rows through the matrix-core items, chunks through the
+    matrix-core tiles (e4m3: widened pages; the generic kernel when widening is off), in one pass; every
+    finite e4m3 code through K and V of single-key decode rows."""
     for kv in ("bf16", "fp8"):
         shape = AttnShape(16, 4, 64, "bf16", kv)
         q = [1, 1, 90, 1, 0, 33, 1, 1]
         c = [40, 1500, 150, 16, 9, 33, 4097, 1]
         check(make_batch(shape, q, c, seed=46, pool_rule=1.25, value_mult=0.5))
+        check(make_batch(shape, q, c, seed=46, pool_rule=1.25, value_mult=0.5), options={"prefill_widen_pages": 0})
     shape = AttnShape(2, 2, 64, "bf16", "fp8")
     codes = [cd for cd in range(256) if (cd & 0x7F) != 0x7F]
     vals = torch.tensor([oracle.e4m3_to_double(cd) for cd in codes] + [0.0, 1.0], dtype=torch.float32)   # 256 values
@@ -156,35 +158,41 @@ def test_decode_large_scores_and_shifting_maximum():
 # MFMA prefill path
 # ---------------------------------------------------------------------------------------------
 
+@pytest.mark.parametrize("head_dim", [128, 64])
 @pytest.mark.parametrize("kv", ["bf16", "fp8"])
 @pytest.mark.parametrize("heads", [(8, 2), (4, 4), (16, 2), (32, 2), (6, 2)], ids=lambda h: f"{h[0]}q{h[1]}kv")
-def test_prefill_chunks(kv, heads):
-    shape = AttnShape(heads[0], heads[1], 128, "bf16", kv)
+def test_prefill_chunks(kv, heads, head_dim):
+    import paper_2512_03416_amd as ts
+    shape = AttnShape(heads[0], heads[1], head_dim, "bf16", kv)
     q = [37, 64, 2, 130, 300, 17]
     pre = [0, 48, 0, 5, 200, 63]
     b = make_batch(shape, q, [a + c for a, c in zip(q, pre)], seed=41, pool_rule=1.3, value_mult=0.5)
+    info = ts.plan_describe(gpu().make_desc(b), b.q_lens, b.ctx_lens)
+    assert info.n_prefill_tiles >= len(q) and info.n_generic_rows == 0          # the matrix-core tiles
     check(b)
 
 
+@pytest.mark.parametrize("head_dim", [128, 64])
 @pytest.mark.parametrize("kv", ["bf16", "fp8"])
 @pytest.mark.parametrize("heads", [(8, 2), (16, 2)], ids=lambda h: f"{h[0]}q{h[1]}kv")
-def test_prefill_pipeline_boundaries(kv, heads):
+def test_prefill_pipeline_boundaries(kv, heads, head_dim):
     """Chunks whose first and last tiles start at every kind of position relative to the 32-token
     half-stages, the 64-token stages and the tile size: tiles with one, two, three ... half-stages,
     with and without an unmasked steady state, prefixes that end inside a stage (cache tail beyond
     ctx_len holds the poison pattern)."""
-    shape = AttnShape(heads[0], heads[1], 128, "bf16", kv)
+    shape = AttnShape(heads[0], heads[1], head_dim, "bf16", kv)
     pre = [0, 1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 159, 160, 191, 192, 193, 255, 257]
     q = [2 + (7 * i) % 70 for i in range(len(pre))]
     b = make_batch(shape, q, [a + c for a, c in zip(q, pre)], seed=43, pool_rule=1.2, value_mult=0.5)
     check(b, options={"mixed_mode": 0})
 
 
-def test_prefill_maximum_rises_late():
+@pytest.mark.parametrize("head_dim", [128, 64])
+def test_prefill_maximum_rises_late(head_dim):
     """Scores that keep growing along the context: the running maximum has to be raised again and
     again after the weights were formed (large jumps included), in the steady state and in the
     drain."""
-    shape = AttnShape(8, 2, 128, "bf16", "bf16")
+    shape = AttnShape(8, 2, head_dim, "bf16", "bf16")
     b = make_batch(shape, [300, 70], [1500, 400], seed=44, pool_rule=1.2, value_mult=0.5)
     # scale the keys with their position: later keys score higher by construction for positive q . k
     pos_pre = torch.cat([torch.arange(1200), torch.arange(330)]).float()
@@ -261,13 +269,14 @@ def test_fp8_prefill_widened_pages_and_in_tile_widening_agree(mode):
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[1], outs[2])
 
 
-@pytest.mark.parametrize("kv,heads", [("bf16", (32, 8)), ("fp8", (64, 8)), ("bf16", (8, 8)), ("fp8", (16, 1))])
-def test_prefill_tiles_cut_along_the_keys(kv, heads):
+@pytest.mark.parametrize("kv,heads,head_dim", [("bf16", (32, 8), 128), ("fp8", (64, 8), 128), ("bf16", (8, 8), 128),
+                                               ("fp8", (16, 1), 128), ("bf16", (32, 8), 64), ("fp8", (16, 2), 64)])
+def test_prefill_tiles_cut_along_the_keys(kv, heads, head_dim):
     """A short chunk over a long prefix cannot give every CU a tile: the tiles are cut along the keys and the
     parts merged.  Chunks whose prefix ends inside a page, a stage and a part; parts of 64 keys (the finest cut)
     and the default; next to decode rows (one persistent kernel) and alone; same results with cutting off."""
     import paper_2512_03416_amd as ts
-    shape = AttnShape(heads[0], heads[1], 128, "bf16", kv)
+    shape = AttnShape(heads[0], heads[1], head_dim, "bf16", kv)
     g = gpu()
     for q, c in [([200], [200 + 4099]), ([64, 37], [64 + 2048, 37 + 1000]), ([1, 130, 1, 1], [700, 130 + 3001, 64, 2500])]:
         mk = lambda: make_batch(shape, q, c, seed=61, pool_rule=1.2, value_mult=0.5 if kv == "bf16" else 1.0)
@@ -275,8 +284,10 @@ def test_prefill_tiles_cut_along_the_keys(kv, heads):
         assert ts.plan_describe(g.make_desc(b), b.q_lens, b.ctx_lens).prefill_parts > 1
         ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
         outs = []
-        for opts in ({}, {"prefill_split_min_keys": 64}, {"prefill_split_min_keys": 0},
-                     {"prefill_split_min_keys": 64, "prefill_widen_pages": 0, "mixed_mode": 0}):
+        last = {"prefill_split_min_keys": 64, "mixed_mode": 0}
+        if head_dim == 128:
+            last["prefill_widen_pages"] = 0                  # (head dim 64 reads an e4m3 cache through widened pages only)
+        for opts in ({}, {"prefill_split_min_keys": 64}, {"prefill_split_min_keys": 0}, last):
             print(f"[case] cut tiles kv={kv} heads={heads} q={q} ctx={c} opts={opts}", flush=True)
             out, gk, gv = g.run_batch(mk(), options=opts)
             assert same_bytes(gk, rk) and same_bytes(gv, rv)

@@ -146,15 +146,18 @@ def test_plan_append_pages_cover_every_new_token_of_the_chunks_once():
     assert len(binding.plan_export(d64, q_lens, ctx, "append_rows")) == int(q_lens.sum())
 
 
-def test_plan_routes_fp32_to_generic_rows_and_head_dim_64_chunks_too():
+def test_plan_routes_fp32_to_generic_rows_and_head_dim_64_to_the_matrix_cores():
     d = D(q_dtype="f32", kv_dtype="f32", D=64, Hq=4, Hkv=1)
     info = ts.plan_describe(d, [1, 37, 64], [5, 37, 112])
     assert info.n_generic_rows == 102 and info.n_decode_items == 0 and info.n_prefill_tiles == 0
-    # head dim 64, bf16 / fp8 cache: decode rows are matrix-core items, chunk rows go to the generic kernel
+    # head dim 64, bf16 cache: decode rows are matrix-core items, chunks matrix-core tiles, one launch per class
     info = ts.plan_describe(D(D=64), [1, 4], [5, 4])
-    assert info.n_generic_rows == 4 and info.n_decode_items == 1 and info.n_prefill_tiles == 0 and info.mixed_mode == 0
-    info = ts.plan_describe(D(D=64, kv_dtype="fp8"), [1, 1, 1], [5, 1000, 17])
-    assert info.n_generic_rows == 0 and info.n_decode_items >= 3
+    assert info.n_generic_rows == 0 and info.n_decode_items == 1 and info.n_prefill_tiles == 1 and info.mixed_mode == 0
+    # head dim 64, e4m3 cache: the tiles read widened pages; without them the chunk rows take the generic kernel
+    info = ts.plan_describe(D(D=64, kv_dtype="fp8"), [1, 1, 40], [5, 1000, 17 + 40])
+    assert info.n_generic_rows == 0 and info.n_decode_items >= 2 and info.n_prefill_tiles >= 1 and info.widened_pages == 4
+    rows = binding.plan_export(D(D=64, kv_dtype="fp8", max_pages_per_seq=20000), [40], [40 + 16 * 16384], "rows")
+    assert len(rows) == 40                                    # more pages than the widening scratch takes
 
 
 def test_create_without_gpu_fails_loudly():
