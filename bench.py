@@ -191,7 +191,7 @@ CPU_SAMPLE = {   # workload -> (decode sequences, prefill chunks, chunk row stri
 }
 
 
-def roofline_of(work, ktimes, batch_name):
+def roofline_of(work, ktimes, batch_name, mixed_mode=1):
     """Roofline block of the kernel that takes the most time, from the algorithmic work of the batch and
     the kernel's mean duration (HIP events on the launch stream)."""
     tot = {k: v[0] * v[1] for k, v in ktimes.items()}
@@ -199,7 +199,12 @@ def roofline_of(work, ktimes, batch_name):
     n, ms = ktimes[dominant]
     sec = ms * 1e-3
     all_bytes = work["decode_bytes"] + work["prefill_bytes"]
-    common = dict(kernel=dominant + "_kernel", kernel_ms=ms, kernel_launches_timed=n)
+    name = dominant + "_kernel"
+    if dominant == "mixed" and mixed_mode == 2:
+        # co-resident launch: two kernels run side by side; the duration is the span from the start of the first to
+        # the end of the last (events on the caller's stream around the fork and the join)
+        name = "prefill_resident_kernel || decode_kernel_lean"
+    common = dict(kernel=name, kernel_ms=ms, kernel_launches_timed=n)
     if dominant == "decode":
         ach = work["decode_bytes"] / sec / 1e9
         return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
@@ -313,7 +318,7 @@ def run_workload(name, args, with_cpu: bool):
     log(f"[bench] token velocity counters: prefill {vel.prefill_tok_per_s:.0f} tok/s, decode "
         f"{vel.decode_tok_per_s:.0f} tok/s over {vel.window_s:.3f} s ({vel.passes} passes)")
     work = algorithmic_work(batch)
-    roof = roofline_of(work, ktimes, batch.name)
+    roof = roofline_of(work, ktimes, batch.name, int(info.mixed_mode))
     res = {
         "value": T * args.steps / elapsed, "ms_per_step": ms_step,
         "dtype": ("bf16" if sh.q_dtype == "bf16" else "f32") + (" (e4m3 KV cache)" if sh.kv_dtype == "fp8" else ""),
@@ -326,7 +331,7 @@ def run_workload(name, args, with_cpu: bool):
         "ms_per_step_without_kernel_events": ms_plain,
         "kernels_us": {k: round(v[1] * 1e3, 2) for k, v in ktimes.items() if v[0]},
     }
-    if roof["kernel"] == "mixed_kernel" and not args.no_persistent:
+    if "mixed" in ktimes and ktimes["mixed"][0] and not args.no_persistent:
         # the same batch with one launch per class: what each class reaches on its own
         ctx.set_option("mixed_mode", 0)
         for _ in range(max(2, args.warmup // 3)):
@@ -334,6 +339,7 @@ def run_workload(name, args, with_cpu: bool):
         n_sep = max(4, args.steps // 2)
         dt_sep, kt_sep = region(n_sep, max(1, args.time_every // 2))
         ctx.set_option("mixed_mode", 2)
+        roof["mixed_mode"] = int(info.mixed_mode)
         roof["per_class"] = per_class_of(work, kt_sep)
         roof["ms_per_step_separate_launches"] = dt_sep * 1e3 / n_sep
         log(f"[bench] {batch.name}, one launch per class: {dt_sep * 1e3 / n_sep:.4f} ms/step; kernels: " +
@@ -353,8 +359,47 @@ def run_workload(name, args, with_cpu: bool):
     return res
 
 
+def summarise_trace(path):
+    """Markdown summary of a rocprofv3 --kernel-trace output folder: per kernel the calls and the mean / min / max
+    duration, and for the co-resident launch the span of each pair (start of the resident prefill kernel to the
+    end of whichever of the two kernels ends last)."""
+    import csv
+    import glob
+    rows = []
+    for f in glob.glob(os.path.join(path, "**", "*kernel_trace.csv"), recursive=True):
+        for r in csv.DictReader(open(f)):
+            rows.append((int(r["Start_Timestamp"]), int(r["End_Timestamp"]), r["Kernel_Name"].split("(")[0]))
+    rows.sort()
+    per = {}
+    for s, e, n in rows:
+        if "ts::" in n or "calib" in n:
+            per.setdefault(n, []).append(e - s)
+    print("| kernel | calls | mean us | min us | max us |\n|---|---|---|---|---|")
+    for n, d in sorted(per.items(), key=lambda kv: -sum(kv[1])):
+        print(f"| `{n}` | {len(d)} | {sum(d) / len(d) / 1e3:.1f} | {min(d) / 1e3:.1f} | {max(d) / 1e3:.1f} |")
+    spans = {}
+    for i, (s, e, n) in enumerate(rows):
+        if "prefill_resident_kernel" not in n:
+            continue
+        end, partner = e, None
+        for s2, e2, n2 in rows[i + 1:i + 8]:
+            if "decode_kernel" in n2 and s2 < e:
+                end, partner = max(end, e2), (s2 - s, e2 - s2)
+                break
+        if partner:
+            spans.setdefault(n, []).append((end - s, e - s, partner[1], partner[0]))
+    for n, v in spans.items():
+        k = len(v)
+        print(f"\nco-resident pairs of `{n}` ({k}): span mean {sum(x[0] for x in v) / k / 1e3:.1f} us "
+              f"(min {min(x[0] for x in v) / 1e3:.1f}, max {max(x[0] for x in v) / 1e3:.1f}); the prefill kernel itself "
+              f"{sum(x[1] for x in v) / k / 1e3:.1f} us, the decode kernel next to it {sum(x[2] for x in v) / k / 1e3:.1f} us, "
+              f"started {sum(x[3] for x in v) / k / 1e3:.1f} us after it")
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--summarise-trace", default="", metavar="DIR",
+                    help="print a summary of a rocprofv3 --kernel-trace output folder and exit (no GPU needed)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
@@ -372,6 +417,9 @@ def main():
     ap.add_argument("--time-every", type=int, default=4,
                     help="record HIP events around the kernels of every N-th step of the timed region")
     args = ap.parse_args()
+    if args.summarise_trace:
+        summarise_trace(args.summarise_trace)
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
