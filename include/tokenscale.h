@@ -191,12 +191,20 @@ const char *ts_last_error(const ts_ctx *ctx);
  *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave
  *   "mixed_mode"          how a batch that holds decode rows and prefill chunks is launched:
  *                         2 (default, TS_MIXED_CORESIDENT) = the prefill tiles run in resident workgroups,
- *                         one per CU, that leave room on every CU for one decode workgroup, and the decode
- *                         items run next to them as a grid of their own on an internal side stream (forked
- *                         from and joined to the caller's stream with events); batches too small to gain
- *                         from it take mode 1 by themselves;
+ *                         at most one per CU, that leave room on their CU for one decode workgroup, and the
+ *                         decode items run next to them as a grid of their own on an internal side stream
+ *                         (forked from and joined to the caller's stream with events).  A batch with hardly
+ *                         any decode pages takes mode 1 by itself, one with hardly any prefill work mode 0.
+ *                         The side stream is an ordinary stream of the process: where the runtime maps it
+ *                         to the hardware queue that also serves the caller's stream (a process has 4 by
+ *                         default), the two launches run in turn -- same results, no overlap;
  *                         1 (TS_MIXED_ONE_KERNEL) = decode items and prefill tiles share the workgroups of one
  *                         persistent launch;  0 (TS_MIXED_SEPARATE) = decode kernel, then prefill kernel
+ *   "prefill_resident_workgroups"  co-resident launch: number of resident prefill workgroups.  0 (default) =
+ *                         chosen per batch from the estimated times of its tiles and of its decode scan: all
+ *                         CUs when the tiles dominate, fewer (in multiples of the die count) when the scan
+ *                         outlasts them, so that the remaining CUs hold decode workgroups only.  A value > 0
+ *                         fixes the number (capped at the CU count) and keeps mode 2 for every mixed batch
  *   "prefill_split_min_keys"  a batch whose prefill tiles cannot give every CU a workgroup (a short chunk over a
  *                         long prefix) has its tiles cut along the keys, below their first query position, into
  *                         parts of at least this many keys (multiple of 64, default 1024; 0 = never); the
@@ -249,7 +257,7 @@ typedef struct {
     int64_t partial_slots;      /* split-K partial results held in scratch                     */
     int64_t ctx_pages;          /* sum over sequences of ceil(ctx_len/16)                      */
     int32_t mixed_mode;         /* TS_MIXED_* the batch is launched with (SEPARATE if one kind only) */
-    int32_t reserved;
+    int32_t prefill_workgroups; /* co-resident launch: resident workgroups that work through the prefill tiles (else 0) */
     int64_t widened_pages;      /* fp8 caches: pages widened to bf16 before the prefill tiles run   */
     int64_t prefill_parts;      /* partial results of prefill tiles cut along the keys (0 = none cut) */
 } ts_plan_info;

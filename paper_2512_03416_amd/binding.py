@@ -57,7 +57,7 @@ class PlanInfo(ctypes.Structure):
                 ("n_combine_rows", ctypes.c_int32), ("n_prefill_tiles", ctypes.c_int32),
                 ("n_generic_rows", ctypes.c_int32), ("split_pages", ctypes.c_int32),
                 ("tile_tokens", ctypes.c_int32), ("partial_slots", ctypes.c_int64),
-                ("ctx_pages", ctypes.c_int64), ("mixed_mode", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("ctx_pages", ctypes.c_int64), ("mixed_mode", ctypes.c_int32), ("prefill_workgroups", ctypes.c_int32),
                 ("widened_pages", ctypes.c_int64), ("prefill_parts", ctypes.c_int64)]
 
 

@@ -662,6 +662,11 @@ extern "C" int ts_set_option(ts_ctx* c, const char* name, int64_t value)
         c->opt.pf_split_min_keys = (int32_t)value;
         return TS_OK;
     }
+    if (!strcmp(name, "prefill_resident_workgroups")) {
+        if (value < 0 || value > 65536) return fail(c, TS_ERR_INVALID_ARG, "prefill_resident_workgroups out of range");
+        c->opt.pf_resident_wgs = (int32_t)value;
+        return TS_OK;
+    }
     if (!strcmp(name, "prefill_widen_pages")) {
         if (value < 0 || value > ((int64_t)1 << 24)) return fail(c, TS_ERR_INVALID_ARG, "prefill_widen_pages out of range");
         c->opt.widen_pages = value;
@@ -694,6 +699,7 @@ extern "C" int ts_get_option(const ts_ctx* c, const char* name, int64_t* value)
     else if (!strcmp(name, "mixed_mode")) *value = c->opt.mixed_mode;
     else if (!strcmp(name, "xcd_count")) *value = c->opt.xcds;
     else if (!strcmp(name, "prefill_widen_pages")) *value = c->opt.widen_pages;
+    else if (!strcmp(name, "prefill_resident_workgroups")) *value = c->opt.pf_resident_wgs;
     else if (!strcmp(name, "prefill_split_min_keys")) *value = c->opt.pf_split_min_keys;
     else if (!strcmp(name, "decode_merge_in_kernel")) *value = c->merge_in_kernel ? 1 : 0;
     else if (!strcmp(name, "validate_block_table")) *value = c->validate_pages ? 1 : 0;
@@ -839,7 +845,7 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
     a.q_ctr = q_ctr_of(c);
     // (the merging form of the decode kernel exists for a prefetch depth of two tiles and outside the one-kernel launch)
     a.cmb_ctr = c->merge_in_kernel && c->dec_nbuf == 2 && p.info.mixed_mode != TS_MIXED_ONE_KERNEL ? cmb_ctr_of(c, p.cmb.size()) : nullptr;
-    a.dec_nbuf = c->dec_nbuf; a.mixed_wgs = c->mixed_wgs; a.n_cu = c->opt.n_cu;
+    a.dec_nbuf = c->dec_nbuf; a.mixed_wgs = c->mixed_wgs; a.n_cu = c->opt.n_cu; a.pf_wgs = p.info.prefill_workgroups;
     a.part_o = part_o_of(c); a.part_ml = part_ml_of(c);
     if (!p.wide.empty()) {
         a.wide = (const WideItem*)(wb + w.wide); a.n_wide = (int32_t)p.wide.size();

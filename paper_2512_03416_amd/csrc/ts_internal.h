@@ -127,6 +127,7 @@ struct PlanOptions {
     bool prefill_generic = false;
     int32_t tile_tokens = 0;    // query tokens per prefill tile
     int32_t pf_split_min_keys = 1024;   // shortest key range of a cut prefill tile (multiple of 64; 0 = never cut)
+    int32_t pf_resident_wgs = 0; // co-resident launch: resident prefill workgroups (0 = from the batch's two costs)
     int64_t widen_pages = 16384; // fp8 caches: most pages of prefill sequences that are widened to bf16 per pass (0 = never)
 };
 
@@ -195,6 +196,7 @@ struct AttnArgs {
     int32_t dec_nbuf;          // KV tiles in flight per decode wave (2..4)
     int32_t mixed_wgs;         // workgroups of the persistent kernel that are resident on the GPU at once
     int32_t n_cu;              // compute units of the GPU
+    int32_t pf_wgs;            // co-resident launch: resident workgroups for the prefill tiles (at most one per CU)
     // prefill tiles cut along the keys: partial results o [part][kv head][256 rows][D] fp32 (unnormalised),
     // ml [part][kv head][256 rows][2] = (reference maximum in log2 units, weight sum)
     const PfCmb* pfcmb; int32_t n_pfcmb;

@@ -120,7 +120,8 @@ int launch_prefill_resident(const AttnArgs& a, void* stream)
 {
     if (a.n_queue <= 0) return (int)hipSuccess;
     if (a.geo.D != 128 || a.geo.q_dtype != TS_BF16 || a.n_xcd <= 0 || a.n_xcd > 64 || a.n_cu <= 0) return (int)hipErrorInvalidValue;
-    const int grid = a.n_cu < a.n_queue ? a.n_cu : a.n_queue;   // (128 KB of LDS: one per CU)
+    const int want = a.pf_wgs > 0 && a.pf_wgs < a.n_cu ? a.pf_wgs : a.n_cu;   // (128 KB of LDS: at most one per CU)
+    const int grid = want < a.n_queue ? want : a.n_queue;
     hipStream_t st = (hipStream_t)stream;
     const dim3 g3((unsigned)grid), b3(kPfThreads);
     if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((prefill_resident_kernel<uint16_t, false>), g3, b3, 0, st, a);

@@ -8,6 +8,7 @@
 // so that the hardware dispatcher, which hands out workgroups in order, balances the tail.
 #include <algorithm>
 #include <climits>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 
@@ -109,11 +110,31 @@ int validate_batch(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* 
 // workgroup per CU, a third of the stand-alone decode slots), (b) does not apply and the fair share
 // in (a) is that of a resident workgroup: measured on the burst configuration, 706 -> 692 us and no
 // combine launch.
+// Rates the two kinds of work reach on their own (decode scan: bytes per microsecond; prefill tiles: flop per
+// microsecond, all CUs).
+constexpr double kDecBytePerUs = 6.2e6;
+constexpr double kPfFlopPerUs = 1.25e9;
+// Co-resident launch: share of the CUs that get a resident prefill workgroup, from the ratio r of the two times:
+// kPfShare0 + kPfShare1 * r, at most all of them.  Measured on one chunk of 128 ... 16 256 tokens over a prefix of 0
+// or 4096 next to 128 decode rows of 1024-8192 tokens, and on the two burst configurations: too few workgroups
+// make the tiles the critical path (the time rises steeply), a few too many cost 3-8 %; r = 0.3: best at 80-128 of
+// 256, r = 0.8: 160-192, r = 1.0: 224, r >= 1.3: all.
+constexpr double kPfShare0 = 0.25;
+constexpr double kPfShare1 = 0.6;
+// Estimated time of the tiles below which a mixed batch is launched class by class: the fork and join of the
+// co-resident launch cost more than so short a prefill launch behind the decode kernel (128 decode rows next to a
+// chunk of 128 / 896 tokens without prefix: 0.410 / 0.425 ms against 0.423 / 0.432 ms; a chunk of 384 tokens over
+// a prefix of 4096, estimated at 22 us: 0.450 against 0.429 ms).
+constexpr double kPfSeparateBelowUs = 8.0;
+
 static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int64_t n_rows, int Hkv,
-                                int32_t wg_slots, int32_t n_cu, bool filled_by_prefill)
+                                int32_t wg_slots, int32_t n_cu, bool filled_by_prefill, int32_t pf_wgs)
 {
-    // (next to resident prefill tiles a CU has room for one decode workgroup)
-    const int64_t slots = std::max<int32_t>(1, filled_by_prefill ? n_cu : wg_slots);
+    // (next to a resident prefill workgroup a CU has room for one decode workgroup; the CUs without one hold
+    // their usual share of the stand-alone slots)
+    int64_t slots = std::max<int32_t>(1, filled_by_prefill ? n_cu : wg_slots);
+    if (filled_by_prefill && pf_wgs > 0 && pf_wgs < n_cu)
+        slots = pf_wgs + (int64_t)(n_cu - pf_wgs) * std::max(1, wg_slots / n_cu);
     int64_t L = std::max<int64_t>(32, (decode_tiles + slots - 1) / slots);
     if (!filled_by_prefill && n_rows * Hkv < n_cu && decode_pages > 0) {
         const int64_t want_items = (n_cu + Hkv - 1) / Hkv;             // per KV head
@@ -278,22 +299,52 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     // two launches cost a few microseconds, so a batch whose tiles cannot occupy half of the CUs, or that has
     // hardly any decode pages to hide behind them, goes through the single persistent kernel instead.
     int mixed_mode = opt.mixed_mode;
-    if (mixed_mode == TS_MIXED_CORESIDENT && (tile_heads * 2 < opt.n_cu || decode_tiles < 4 * (int64_t)opt.n_cu))
-        mixed_mode = TS_MIXED_ONE_KERNEL;
+    double t_pf = 0, t_dec = 0;                            // microseconds each kind would take alone
+    if (mixed_mode == TS_MIXED_CORESIDENT) {
+        double flop = 0;
+        for (int s = 0; s < num_seqs; ++s) {
+            const SeqMeta& m = p.seqs[s];
+            if (m.q_len > 1) flop += 4.0 * d.num_q_heads * d.head_dim * ((double)m.q_len * m.prefix + 0.5 * m.q_len * (m.q_len + 1.0));
+        }
+        t_pf = flop / kPfFlopPerUs;
+        t_dec = (double)decode_tiles * 2.0 * kPage * d.head_dim * (d.kv_dtype == TS_FP8_E4M3 ? 1 : 2) / kDecBytePerUs;
+        // (a stated number of resident workgroups asks for this launch form whatever the batch)
+        if (opt.pf_resident_wgs <= 0) {
+            if (decode_tiles < 4 * (int64_t)opt.n_cu) mixed_mode = TS_MIXED_ONE_KERNEL;
+            else if (t_pf < kPfSeparateBelowUs) mixed_mode = TS_MIXED_SEPARATE;
+        }
+    }
     if (!mfma || p.info.decode_tokens == 0 || tile_heads == 0) mixed_mode = TS_MIXED_SEPARATE;
     if (!mfma_dec) { decode_tiles = 0; decode_pages = 0; }
     p.info.mixed_mode = mixed_mode;
-    const bool filled_by_prefill = mixed_mode != TS_MIXED_SEPARATE && tile_heads >= opt.n_cu;
+    // Co-resident launch: how many CUs get a resident prefill workgroup.  Such a CU has room for one decode
+    // workgroup instead of three, so a batch whose decode scan outlasts its tiles (one restricted chunk next to a
+    // large decode batch, Sec. 4.4) keeps part of the CUs for decode rows alone: the tiles get a share of the CUs
+    // that grows with the ratio of the two times (estimated from the batch's flops and bytes at the rates the
+    // kernels reach alone), in multiples of the number of dies.
+    int32_t pf_wgs = 0;
+    if (mixed_mode == TS_MIXED_CORESIDENT) {
+        const int32_t x = std::max(1, opt.xcds);
+        const int32_t all = std::max(1, opt.n_cu);
+        if (opt.pf_resident_wgs > 0) {
+            pf_wgs = std::min(all, opt.pf_resident_wgs);
+        } else {
+            const double share = t_dec > 0 ? kPfShare0 + kPfShare1 * t_pf / t_dec : 1.0;
+            pf_wgs = share >= 1.0 ? all : (int32_t)std::ceil(share * all);
+        }
+        pf_wgs = std::min(all, std::max(x, (pf_wgs + x - 1) / x * x));
+    }
+    const bool filled_by_prefill = mixed_mode != TS_MIXED_SEPARATE && (tile_heads >= opt.n_cu || pf_wgs > 0);
     const int32_t L = opt.split_pages > 0
                           ? opt.split_pages
                           : auto_split_pages(decode_tiles, decode_pages, p.info.decode_tokens, Hkv, opt.wg_slots,
-                                             std::max(1, opt.n_cu), filled_by_prefill);
+                                             std::max(1, opt.n_cu), filled_by_prefill, pf_wgs);
     p.info.split_pages = L;
     p.info.tile_tokens = TT;
 
     int32_t part = 0, pf_part = 0;
     // parts per prefill tile that would give every CU a workgroup (1 = the tiles fill the GPU as they are)
-    const int64_t pf_parts_wanted = tile_heads > 0 ? std::min<int64_t>(16, opt.n_cu / tile_heads) : 1;
+    const int64_t pf_parts_wanted = tile_heads > 0 ? std::min<int64_t>(16, (pf_wgs > 0 ? pf_wgs : opt.n_cu) / tile_heads) : 1;
     for (int s = 0; s < num_seqs; ++s) {
         const SeqMeta& m = p.seqs[s];
         if (m.q_len == 0) continue;
@@ -386,6 +437,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     p.info.n_generic_rows = (int32_t)p.rows.size();
     p.info.partial_slots = part;
     p.info.prefill_parts = pf_part;
+    p.info.prefill_workgroups = (int32_t)std::min<int64_t>(pf_wgs, (int64_t)p.queue.size());
 }
 
 }  // namespace ts

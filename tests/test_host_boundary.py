@@ -160,6 +160,35 @@ def test_plan_routes_fp32_to_generic_rows_and_head_dim_64_to_the_matrix_cores():
     assert len(rows) == 40                                    # more pages than the widening scratch takes
 
 
+def test_plan_sizes_the_co_resident_launch_from_the_two_costs():
+    """A mixed batch is launched co-resident with as many resident prefill workgroups as the ratio of the two
+    classes' estimated times asks for (all CUs when the tiles dominate, fewer -- in multiples of the die count --
+    when the decode scan outlasts them); a batch with hardly any prefill work goes class by class, one with
+    hardly any decode pages through the one persistent kernel."""
+    rng = np.random.default_rng(3)
+    dec = rng.integers(1024, 8193, 128).tolist()
+    d = D(max_pages_per_seq=2048, num_pages=200000)
+
+    def plan(chunks):
+        q = [1] * len(dec) + [c for c, _ in chunks]
+        ctx = dec + [c + p for c, p in chunks]
+        return ts.plan_describe(d, q, ctx)
+    burst = plan([(2048, 0), (2048, 1500), (2048, 3000), (2048, 4096)])            # tiles ~ as long as the scan
+    assert burst.mixed_mode == 2 and 160 <= burst.prefill_workgroups < 256 and burst.prefill_workgroups % 8 == 0
+    heavy = plan([(4096, 4096)] * 4)                                                 # tiles dominate
+    assert heavy.mixed_mode == 2 and heavy.prefill_workgroups == 256
+    one = plan([(1920, 4096)])                                                       # the scan dominates
+    assert one.mixed_mode == 2 and 64 <= one.prefill_workgroups <= 160 and one.prefill_workgroups % 8 == 0
+    small = plan([(384, 4096)])
+    assert small.mixed_mode == 2 and 8 <= small.prefill_workgroups <= 96
+    assert plan([(128, 0)]).mixed_mode == 0 and plan([(128, 0)]).prefill_workgroups == 0
+    few = ts.plan_describe(d, [1, 1, 2048], [100, 200, 2048])
+    assert few.mixed_mode == 1 and few.prefill_workgroups == 0
+    # monotone in the prefill work
+    sizes = [plan([(n, 4096)]).prefill_workgroups for n in (512, 1024, 2048, 4096, 8192)]
+    assert sizes == sorted(sizes) and sizes[-1] == 256
+
+
 def test_create_without_gpu_fails_loudly():
     import torch
     if torch.cuda.is_available():
