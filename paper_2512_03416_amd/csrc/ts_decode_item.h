@@ -22,6 +22,8 @@
 // exceeds it by more than kRaise (any reference gives the same quotient, the bound only guards
 // the fp32 range), which removes the accumulator rescale from almost every page.
 #pragma once
+#include <type_traits>
+
 #include "ts_device.h"
 
 namespace ts {
@@ -174,50 +176,64 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
 #pragma unroll
         for (int j = 0; j < NBUF; ++j) fetch(buf[j]);
 
-        for (int base = 0; base < np; base += NBUF) {
+        // One page: S^T, online softmax against the reference maximum, O^T += V^T P^T.  MASKED is the row's last,
+        // partly filled page: scores and V of the slots past n_keys are masked (the slots hold whatever was there
+        // before).  It runs once per row, after the loop, so that the loop carries no mask arithmetic.
+        auto page_step = [&](const KVTile<KT, D>& t, const int page, auto masked) {
+            constexpr bool MASKED = decltype(masked)::value;
+            f32x4 s = qk_tile(t, qb);
+            float t0 = s[0] * c, t1 = s[1] * c, t2 = s[2] * c, t3 = s[3] * c;
+            const int nvalid = it_keys - (page * kPage + 4 * r);   // tokens tok0 .. tok0+3 valid if < nvalid
+            if constexpr (MASKED) {
+                t0 = nvalid > 0 ? t0 : -INFINITY; t1 = nvalid > 1 ? t1 : -INFINITY;
+                t2 = nvalid > 2 ? t2 : -INFINITY; t3 = nvalid > 3 ? t3 : -INFINITY;
+            }
+            const float lmax = fmaxf(fmaxf(t0, t1), fmaxf(t2, t3));
+            if (__any(lmax > m_ref + kRaise)) {           // raise the reference (rare)
+                float full = fmaxf(lmax, __shfl_xor(lmax, 16, 64));
+                full = fmaxf(full, __shfl_xor(full, 32, 64));
+                const float m_new = fmaxf(m_ref, full);
+                const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // 0 on the first page
+#pragma unroll
+                for (int b = 0; b < DB; ++b) acc[b] *= alpha;
+                l *= alpha;
+                m_ref = m_new;
+            }
+            const float p0 = __builtin_amdgcn_exp2f(t0 - m_ref), p1 = __builtin_amdgcn_exp2f(t1 - m_ref);
+            const float p2 = __builtin_amdgcn_exp2f(t2 - m_ref), p3 = __builtin_amdgcn_exp2f(t3 - m_ref);
+            l += (p0 + p1) + (p2 + p3);
+            uint2 pw;
+            pw.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p0, p1}, bf16x2));
+            pw.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p2, p3}, bf16x2));
+            const s16x4 pv = as_s16x4(pw);
+            uint64_t keep = ~0ull;
+            if constexpr (MASKED) keep = nvalid >= 4 ? ~0ull : (nvalid <= 0 ? 0ull : ((1ull << (16 * nvalid)) - 1ull));
+#pragma unroll
+            for (int b = 0; b < DB; ++b) {
+                uint2 vv = v_operand(t, b);
+                if constexpr (MASKED) { vv.x &= (uint32_t)keep; vv.y &= (uint32_t)(keep >> 32); }
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(as_s16x4(vv), pv, acc[b], 0, 0, 0);
+            }
+        };
+        // (the wave's last page is partly filled only if it is the row's last page)
+        const int page_last = it_pb + wave + WAVES * (np - 1);
+        const bool has_tail = (page_last + 1) * kPage > it_keys;      // wave-uniform
+        const int np_main = np - (has_tail ? 1 : 0);
+        for (int base = 0; base < np_main; base += NBUF) {
 #pragma unroll
             for (int j = 0; j < NBUF; ++j) {
                 const int k = base + j;
-                if (k < np) {                                     // wave-uniform
-                    const KVTile<KT, D>& t = buf[j];
-                    const int page = it_pb + wave + WAVES * k;
-                    f32x4 s = qk_tile(t, qb);
-                    float t0 = s[0] * c, t1 = s[1] * c, t2 = s[2] * c, t3 = s[3] * c;
-                    const int nvalid = it_keys - (page * kPage + 4 * r);   // tokens tok0 .. tok0+3 valid if < nvalid
-                    const bool tail = (page + 1) * kPage > it_keys;        // wave-uniform
-                    if (tail) {
-                        t0 = nvalid > 0 ? t0 : -INFINITY; t1 = nvalid > 1 ? t1 : -INFINITY;
-                        t2 = nvalid > 2 ? t2 : -INFINITY; t3 = nvalid > 3 ? t3 : -INFINITY;
-                    }
-                    const float lmax = fmaxf(fmaxf(t0, t1), fmaxf(t2, t3));
-                    if (__any(lmax > m_ref + kRaise)) {           // raise the reference (rare)
-                        float full = fmaxf(lmax, __shfl_xor(lmax, 16, 64));
-                        full = fmaxf(full, __shfl_xor(full, 32, 64));
-                        const float m_new = fmaxf(m_ref, full);
-                        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // 0 on the first page
-#pragma unroll
-                        for (int b = 0; b < DB; ++b) acc[b] *= alpha;
-                        l *= alpha;
-                        m_ref = m_new;
-                    }
-                    const float p0 = __builtin_amdgcn_exp2f(t0 - m_ref), p1 = __builtin_amdgcn_exp2f(t1 - m_ref);
-                    const float p2 = __builtin_amdgcn_exp2f(t2 - m_ref), p3 = __builtin_amdgcn_exp2f(t3 - m_ref);
-                    l += (p0 + p1) + (p2 + p3);
-                    uint2 pw;
-                    pw.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p0, p1}, bf16x2));
-                    pw.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{p2, p3}, bf16x2));
-                    const s16x4 pv = as_s16x4(pw);
-                    uint64_t keep = ~0ull;                        // zero V of slots past n_keys (poison)
-                    if (tail) keep = nvalid >= 4 ? ~0ull : (nvalid <= 0 ? 0ull : ((1ull << (16 * nvalid)) - 1ull));
-#pragma unroll
-                    for (int b = 0; b < DB; ++b) {
-                        uint2 vv = v_operand(t, b);
-                        if (tail) { vv.x &= (uint32_t)keep; vv.y &= (uint32_t)(keep >> 32); }
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(as_s16x4(vv), pv, acc[b], 0, 0, 0);
-                    }
-                }
+                if (k < np_main) page_step(buf[j], it_pb + wave + WAVES * k, std::false_type{});   // wave-uniform
                 fetch(buf[j]);                                    // refill (clamped to the wave's last page)
             }
+        }
+        if (has_tail) {
+            // fetch number f reads page min(f, np - 1) into slot f % NBUF and at least np + NBUF - 1 fetches were
+            // made: slot (np - 1) % NBUF holds the last page
+            const int jt = (np - 1) % NBUF;
+#pragma unroll
+            for (int j = 0; j < NBUF; ++j)
+                if (j == jt) page_step(buf[j], page_last, std::true_type{});
         }
     }
 
