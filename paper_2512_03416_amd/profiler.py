@@ -33,8 +33,9 @@ class SweepPoint:
     decode_only_ratio: float   # pass time relative to the decode-only pass
 
 
-def time_pass(shape, q_lens, ctx_lens, seed: int, steps: int, warmup: int) -> float:
-    """Milliseconds per ts_mixed_paged_attention call (KV append included) on a seeded batch."""
+def time_pass(shape, q_lens, ctx_lens, seed: int, steps: int, warmup: int, options=None) -> float:
+    """Milliseconds per ts_mixed_paged_attention call (KV append included) on a seeded batch; options: names and
+    values for ts_set_option."""
     import torch
     import paper_2512_03416_amd as ts
     from workloads import make_batch
@@ -42,6 +43,8 @@ def time_pass(shape, q_lens, ctx_lens, seed: int, steps: int, warmup: int) -> fl
     desc = ts.Desc.make(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, shape.q_dtype, shape.kv_dtype,
                         batch.num_pages, batch.max_pages_per_seq)
     ctx = ts.Context(desc)
+    for name, value in (options or {}).items():
+        ctx.set_option(name, value)
     nbytes = ts.cache_bytes(desc)
     kc = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda")
     vc = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda")
@@ -67,10 +70,10 @@ def time_pass(shape, q_lens, ctx_lens, seed: int, steps: int, warmup: int) -> fl
 
 
 def sweep(shape, decode_ctx: Sequence[int], chunk_sizes: Sequence[int], prefill_prefix: int, layers: int,
-          seed: int = 7, steps: int = 30, warmup: int = 5) -> List[SweepPoint]:
+          seed: int = 7, steps: int = 30, warmup: int = 5, options=None) -> List[SweepPoint]:
     """Times the pass for the decode batch alone and with one prefill task per chunk size (ascending)."""
     batch_size = len(decode_ctx)
-    base = time_pass(shape, [1] * batch_size, list(decode_ctx), seed, steps, warmup)
+    base = time_pass(shape, [1] * batch_size, list(decode_ctx), seed, steps, warmup, options)
     points = []
     for c in sorted(chunk_sizes):
         n_pf = c - batch_size
@@ -78,7 +81,7 @@ def sweep(shape, decode_ctx: Sequence[int], chunk_sizes: Sequence[int], prefill_
             raise ValueError(f"chunk size {c} leaves no room for prefill next to {batch_size} decode rows")
         q_lens = [1] * batch_size + [n_pf]
         ctx_lens = list(decode_ctx) + [prefill_prefix + n_pf]
-        ms = time_pass(shape, q_lens, ctx_lens, seed, steps, warmup)
+        ms = time_pass(shape, q_lens, ctx_lens, seed, steps, warmup, options)
         points.append(SweepPoint(c, n_pf, ms, ms * layers, ms / base))
         print(f"[profiler] chunk {c:6d} ({n_pf:6d} prefill tokens): {ms:8.3f} ms per pass, "
               f"{ms * layers:8.2f} ms per iteration, {ms / base:5.2f} x decode-only", file=sys.stderr, flush=True)
@@ -101,7 +104,10 @@ def main(argv=None):
                     help="fraction of the TPOT SLO the attention passes of an iteration may use")
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--seed", type=int, default=7)
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="library option for every pass (ts_set_option), e.g. mixed_mode=1; may be repeated")
     args = ap.parse_args(argv)
+    options = {k: int(v) for k, v in (o.split("=", 1) for o in args.option)}
 
     import torch
     if not torch.cuda.is_available():
@@ -114,7 +120,7 @@ def main(argv=None):
     rng = np.random.default_rng(args.seed)
     decode_ctx = rng.integers(args.ctx_min, args.ctx_max + 1, args.decode_batch).tolist()
     chunks = [int(x) for x in args.chunks.split(",")]
-    pts = sweep(shape, decode_ctx, chunks, args.prefill_prefix, args.layers, args.seed, args.steps)
+    pts = sweep(shape, decode_ctx, chunks, args.prefill_prefix, args.layers, args.seed, args.steps, options=options)
 
     budget_s = args.tpot_slo_ms * 1e-3 * args.attention_share
     idx = policy.tv_largest_chunk([p.iteration_attention_ms * 1e-3 for p in pts], budget_s)
@@ -122,7 +128,7 @@ def main(argv=None):
     mem_t = policy.tv_token_bytes(desc, args.layers)
     result = dict(shape=f"{hq}q/{hkv}kv/d128 kv={args.kv}", decode_batch=args.decode_batch,
                   decode_ctx=[args.ctx_min, args.ctx_max], layers=args.layers, tpot_slo_ms=args.tpot_slo_ms,
-                  attention_budget_ms=budget_s * 1e3, sweep=[asdict(p) for p in pts], chosen_index=idx)
+                  attention_budget_ms=budget_s * 1e3, options=options, sweep=[asdict(p) for p in pts], chosen_index=idx)
     if idx >= 0:
         c = pts[idx].chunk_size
         v = policy.tv_convertible_prefill_velocity(c, args.decode_batch, args.tpot_slo_ms * 1e-3)
