@@ -79,13 +79,14 @@ __global__ __launch_bounds__(256) void append_token_kernel(AppendArgs a)
     }
 }
 
-// bf16 source rows, head_dim 128; DST = uint16_t (bf16 cache) or uint8_t (e4m3 cache).
-// Thread (t = tid / 16, c = tid % 16) loads the 16 bytes (dims 8c .. 8c+7) of slot t's K and V row.
-constexpr int kRowPad = 136;                       // LDS row stride in elements: 272 bytes, avoids bank conflicts
-template <typename DST>
+// bf16 source rows, head dim D = 64 or 128; DST = uint16_t (bf16 cache) or uint8_t (e4m3 cache).
+// Thread (t = tid / (D/8), c = tid % (D/8)) loads the 16 bytes (dims 8c .. 8c+7) of slot t's K and V row
+// (head dim 64: the first 128 threads).
+template <typename DST, int D>
 __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
 {
-    constexpr int D = 128;
+    constexpr int CPR = D / 8;                         // 16-byte pieces per source row
+    constexpr int kRowPad = D + 8;                     // LDS row stride in elements: avoids bank conflicts
     __shared__ __align__(16) uint16_t ks[16 * kRowPad];
     __shared__ __align__(16) uint16_t vs[16 * kRowPad];
     const int Hkv = a.geo.Hkv;
@@ -97,45 +98,50 @@ __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
     }
     const int g = blockIdx.x % Hkv;
     const AppTile it = a.apt[blockIdx.x / Hkv];
-    const int tid = threadIdx.x, t = tid >> 4, c = tid & 15;
+    const int tid = threadIdx.x, t = tid / CPR, c = tid % CPR;
+    const bool loader = tid < kPage * CPR;
     const int64_t page = a.block_table[(int64_t)it.seq * a.geo.max_pages + it.page_idx];
-    const bool mine = t >= it.slot_lo && t < it.slot_hi;
+    const bool mine = loader && t >= it.slot_lo && t < it.slot_hi;
     uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
     if (mine) {
         const int64_t src = ((int64_t)(it.row_slot0 + t) * Hkv + g) * D + 8 * c;
         kv = *(const uint4*)((const uint16_t*)a.k_new + src);
         vv = *(const uint4*)((const uint16_t*)a.v_new + src);
     }
-    *(uint4*)(vs + t * kRowPad + 8 * c) = vv;
-    if constexpr (sizeof(DST) == 1) *(uint4*)(ks + t * kRowPad + 8 * c) = kv;
+    if (loader) {
+        *(uint4*)(vs + t * kRowPad + 8 * c) = vv;
+        if constexpr (sizeof(DST) == 1) *(uint4*)(ks + t * kRowPad + 8 * c) = kv;
+    }
     __syncthreads();
     const bool full = it.slot_lo == 0 && it.slot_hi == kPage;
 
     if constexpr (sizeof(DST) == 2) {
         uint16_t* kt = (uint16_t*)a.k_cache + tile_elem_base(page, Hkv, g, D);
         uint16_t* vt = (uint16_t*)a.v_cache + tile_elem_base(page, Hkv, g, D);
-        // K tile [16 chunks][16 slots][8]: this thread's own 16 bytes
+        // K tile [D/8 chunks][16 slots][8]: this thread's own 16 bytes
         if (mine) store_nt(kt + (c * 16 + t) * 8, kv);
-        // V tile [128 dims][16 slots]: thread (dim = tid / 2, half = tid % 2) gathers 8 slots of one dim
+        // V tile [D dims][16 slots]: thread (dim = tid / 2, half = tid % 2) gathers 8 slots of one dim
         const int dim = tid >> 1, hf = tid & 1;
-        uint16_t e[8];
+        if (dim < D) {
+            uint16_t e[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) e[i] = vs[(8 * hf + i) * kRowPad + dim];
-        uint16_t* dst = vt + dim * kPage + 8 * hf;
-        if (full) {
-            store_nt(dst, make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
-                                     e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16)));
-        } else {
+            for (int i = 0; i < 8; ++i) e[i] = vs[(8 * hf + i) * kRowPad + dim];
+            uint16_t* dst = vt + dim * kPage + 8 * hf;
+            if (full) {
+                store_nt(dst, make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
+                                         e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16)));
+            } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (8 * hf + i >= it.slot_lo && 8 * hf + i < it.slot_hi) __builtin_nontemporal_store(e[i], &dst[i]);
+                for (int i = 0; i < 8; ++i)
+                    if (8 * hf + i >= it.slot_lo && 8 * hf + i < it.slot_hi) __builtin_nontemporal_store(e[i], &dst[i]);
+            }
         }
     } else {
         uint8_t* kt = (uint8_t*)a.k_cache + tile_elem_base(page, Hkv, g, D);
         uint8_t* vt = (uint8_t*)a.v_cache + tile_elem_base(page, Hkv, g, D);
         const float kscale = a.k_scale[g], vscale = a.v_scale[g];
-        if (tid < 128) {
-            // K tile [8 chunks of 16 dims][16 slots][16]: thread (chunk = tid / 16, slot = tid % 16)
+        if (tid < D) {
+            // K tile [D/16 chunks of 16 dims][16 slots][16]: thread (chunk = tid / 16, slot = tid % 16)
             const int c16 = tid >> 4, slot = tid & 15;
             if (slot >= it.slot_lo && slot < it.slot_hi) {
                 uint32_t w[4] = {0, 0, 0, 0};
@@ -146,9 +152,9 @@ __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
                 }
                 store_nt(kt + (c16 * 16 + slot) * 16, make_uint4(w[0], w[1], w[2], w[3]));
             }
-        } else {
-            // V tile [128 dims][16 slots]: thread dim = tid - 128 gathers the 16 slots of one dim
-            const int dim = tid - 128;
+        } else if (tid < 2 * D) {
+            // V tile [D dims][16 slots]: thread dim = tid - D gathers the 16 slots of one dim
+            const int dim = tid - D;
             uint32_t w[4] = {0, 0, 0, 0};
             uint8_t b[16];
 #pragma unroll
@@ -194,10 +200,17 @@ int launch_append(const AppendArgs& args, void* stream)
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.n_apt == 0) return (int)e;
-    if (a.geo.q_dtype != TS_BF16 || a.geo.D != 128) return (int)hipErrorInvalidValue;
+    if (a.geo.q_dtype != TS_BF16 || (a.geo.D != 128 && a.geo.D != 64)) return (int)hipErrorInvalidValue;
+    if (a.geo.kv_dtype != TS_BF16 && a.geo.kv_dtype != TS_FP8_E4M3) return (int)hipErrorInvalidValue;
     dim3 tgrid((unsigned)a.n_apt * (unsigned)a.geo.Hkv + (unsigned)a.up_blocks);
-    if (a.geo.kv_dtype == TS_BF16) hipLaunchKernelGGL((append_tile_kernel<uint16_t>), tgrid, block, 0, st, a);
-    else hipLaunchKernelGGL((append_tile_kernel<uint8_t>), tgrid, block, 0, st, a);
+    const bool bf = a.geo.kv_dtype == TS_BF16;
+    if (a.geo.D == 128) {
+        if (bf) hipLaunchKernelGGL((append_tile_kernel<uint16_t, 128>), tgrid, block, 0, st, a);
+        else hipLaunchKernelGGL((append_tile_kernel<uint8_t, 128>), tgrid, block, 0, st, a);
+    } else {
+        if (bf) hipLaunchKernelGGL((append_tile_kernel<uint16_t, 64>), tgrid, block, 0, st, a);
+        else hipLaunchKernelGGL((append_tile_kernel<uint8_t, 64>), tgrid, block, 0, st, a);
+    }
     return (int)hipGetLastError();
 }
 

@@ -276,7 +276,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     p.info.total_tokens = off;
 
     // append work: chunks page by page where the page-wise kernel applies, the rest token by token
-    const bool page_wise = d.q_dtype == TS_BF16 && d.head_dim == 128;
+    const bool page_wise = d.q_dtype == TS_BF16 && d.kv_dtype != TS_F32 && (d.head_dim == 128 || d.head_dim == 64);
     for (int s = 0; s < num_seqs; ++s) {
         const SeqMeta& m = p.seqs[s];
         if (!page_wise || m.q_len < kAppendTileMin) {

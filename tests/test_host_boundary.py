@@ -144,6 +144,11 @@ def test_plan_append_pages_cover_every_new_token_of_the_chunks_once():
     d64 = binding.Desc.make(4, 1, 64, "f32", "f32", 4096, 16)
     assert len(binding.plan_export(d64, q_lens, ctx, "append")) == 0
     assert len(binding.plan_export(d64, q_lens, ctx, "append_rows")) == int(q_lens.sum())
+    # head dim 64 with bf16 inputs is appended page-wise like head dim 128 (same lists)
+    for kv in ("bf16", "fp8"):
+        d64b = binding.Desc.make(8, 2, 64, "bf16", kv, 4096, 16)
+        assert np.array_equal(binding.plan_export(d64b, q_lens, ctx, "append"), rec)
+        assert np.array_equal(binding.plan_export(d64b, q_lens, ctx, "append_rows"), rows)
 
 
 def test_plan_routes_fp32_to_generic_rows_and_head_dim_64_to_the_matrix_cores():
