@@ -79,6 +79,34 @@ __global__ __launch_bounds__(256) void append_token_kernel(AppendArgs a)
     }
 }
 
+// Sixteen fp32 values -> sixteen e4m3 bytes (four words, value i in byte i % 4 of word i / 4), the same bytes as
+// float_to_e4m3_bits gives.  The hardware conversion (two values per instruction, nearest-even, denormals and
+// -0 as the definition wants) answers a value beyond the format's range, and any NaN, with the byte 0xFF; for
+// every one of the 2^32 inputs it agrees with float_to_e4m3_bits once the value has been clamped to +-448,
+// except on NaNs (compared exhaustively on the GPU).  So: clamp, convert, and take the integer encoder when
+// any lane of the wave holds a NaN (rare; the branch is wave-uniform).
+__device__ __forceinline__ void encode_e4m3x16(const float (&x)[16], uint32_t (&w)[4])
+{
+    bool nan = false;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) nan |= x[i] != x[i];
+    if (__any(nan)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            w[j] = float_to_e4m3_bits(x[4 * j]) | (float_to_e4m3_bits(x[4 * j + 1]) << 8) |
+                   (float_to_e4m3_bits(x[4 * j + 2]) << 16) | (float_to_e4m3_bits(x[4 * j + 3]) << 24);
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float a = __builtin_amdgcn_fmed3f(x[4 * j], -448.0f, 448.0f), b = __builtin_amdgcn_fmed3f(x[4 * j + 1], -448.0f, 448.0f);
+        const float c = __builtin_amdgcn_fmed3f(x[4 * j + 2], -448.0f, 448.0f), d = __builtin_amdgcn_fmed3f(x[4 * j + 3], -448.0f, 448.0f);
+        int v = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+        v = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, v, true);
+        w[j] = (uint32_t)v;
+    }
+}
+
 // bf16 source rows, head dim D = 64 or 128; DST = uint16_t (bf16 cache) or uint8_t (e4m3 cache).
 // Thread (t = tid / (D/8), c = tid % (D/8)) loads the 16 bytes (dims 8c .. 8c+7) of slot t's K and V row
 // (head dim 64: the first 128 threads).
@@ -144,32 +172,29 @@ __global__ __launch_bounds__(256) void append_tile_kernel(AppendArgs a)
             // K tile [D/16 chunks of 16 dims][16 slots][16]: thread (chunk = tid / 16, slot = tid % 16)
             const int c16 = tid >> 4, slot = tid & 15;
             if (slot >= it.slot_lo && slot < it.slot_hi) {
-                uint32_t w[4] = {0, 0, 0, 0};
+                float x[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float x = bf16_bits_to_float(ks[slot * kRowPad + 16 * c16 + i]) / kscale;
-                    w[i >> 2] |= float_to_e4m3_bits(x) << (8 * (i & 3));
-                }
+                for (int i = 0; i < 16; ++i) x[i] = bf16_bits_to_float(ks[slot * kRowPad + 16 * c16 + i]) / kscale;
+                uint32_t w[4];
+                encode_e4m3x16(x, w);
                 store_nt(kt + (c16 * 16 + slot) * 16, make_uint4(w[0], w[1], w[2], w[3]));
             }
         } else if (tid < 2 * D) {
             // V tile [D dims][16 slots]: thread dim = tid - D gathers the 16 slots of one dim
             const int dim = tid - D;
-            uint32_t w[4] = {0, 0, 0, 0};
-            uint8_t b[16];
+            float x[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float x = bf16_bits_to_float(vs[i * kRowPad + dim]) / vscale;
-                b[i] = (uint8_t)float_to_e4m3_bits(x);
-                w[i >> 2] |= (uint32_t)b[i] << (8 * (i & 3));
-            }
+            for (int i = 0; i < 16; ++i) x[i] = bf16_bits_to_float(vs[i * kRowPad + dim]) / vscale;
+            uint32_t w[4];
+            encode_e4m3x16(x, w);
             uint8_t* dst = vt + dim * kPage;
             if (full) {
                 store_nt(dst, make_uint4(w[0], w[1], w[2], w[3]));
             } else {
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    if (i >= it.slot_lo && i < it.slot_hi) __builtin_nontemporal_store(b[i], &dst[i]);
+                    if (i >= it.slot_lo && i < it.slot_hi)
+                        __builtin_nontemporal_store((uint8_t)(w[i >> 2] >> (8 * (i & 3))), &dst[i]);
             }
         }
     }
