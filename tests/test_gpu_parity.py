@@ -241,6 +241,37 @@ def test_mixed_batch_persistent_and_separate_launches(persistent, kv):
     ctx.close()
 
 
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+def test_co_resident_launch_with_any_number_of_resident_prefill_workgroups(kv):
+    """The co-resident launch with a stated number of resident prefill workgroups (fewer than the dies, fewer than
+    the tiles, more than the CUs) and with the planner's own choice: oracle parity each time, and the chunk rows
+    bit-identical across all of them (the tiles do not depend on who runs them)."""
+    import paper_2512_03416_amd as ts
+    shape = AttnShape(32, 8, 128, "bf16", kv)
+    rng = np.random.default_rng(8)
+    q = [1] * 48 + [700, 333] + [1] * 10
+    c = list(rng.integers(1, 3500, size=48)) + [700 + 1300, 333] + list(rng.integers(1, 700, size=10))
+    mk = lambda: make_batch(shape, q, c, seed=47, pool_rule=1.25, value_mult=0.5 if kv == "bf16" else 1.0)
+    g = gpu()
+    ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
+    q_off = np.concatenate([[0], np.cumsum(q)])
+    rows = np.concatenate([np.arange(q_off[i], q_off[i + 1]) for i in range(len(q)) if q[i] > 1])
+    outs = []
+    for r in (0, 3, 8, 40, 256, 5000):
+        print(f"[case] co-resident kv={kv} resident prefill workgroups={r}", flush=True)
+        out, gk, gv = g.run_batch(mk(), options={"mixed_mode": 2, "prefill_resident_workgroups": r})
+        assert same_bytes(gk, rk) and same_bytes(gv, rv)
+        assert np.all(np.isfinite(out))
+        assert float(np.max(np.abs(out - ref))) <= TOL[kv]
+        outs.append(out)
+    for o in outs[1:]:
+        assert np.array_equal(o[rows], outs[0][rows])
+    # a stated number keeps the co-resident form even for a batch the planner would launch class by class
+    tiny = make_batch(shape, [1] * 40 + [20], list(rng.integers(1, 900, size=40)) + [20], seed=48, value_mult=0.5)
+    assert ts.plan_describe(g.make_desc(tiny), tiny.q_lens, tiny.ctx_lens).mixed_mode == 0
+    check(tiny, options={"prefill_resident_workgroups": 16})
+
+
 @pytest.mark.parametrize("mode", [2, 1, 0])
 def test_fp8_prefill_widened_pages_and_in_tile_widening_agree(mode):
     """fp8 cache: the prefill tiles read bf16 copies of the chunk sequences' pages made once per pass (default)
