@@ -197,7 +197,14 @@ const char *ts_last_error(const ts_ctx *ctx);
  *                         any decode pages takes mode 1 by itself, one with hardly any prefill work mode 0.
  *                         The side stream is an ordinary stream of the process: where the runtime maps it
  *                         to the hardware queue that also serves the caller's stream (a process has 4 by
- *                         default), the two launches run in turn -- same results, no overlap;
+ *                         default), the two launches run in turn -- same results, no overlap.  The first
+ *                         co-resident call of a context therefore sends a probe ahead (two one-thread
+ *                         kernels, at most 60 us, never under stream capture and never in the
+ *                         allocation-free entry point); a later call reads its answer without waiting and,
+ *                         if the streams ran in turn, replaces the side stream and probes again, up to 4
+ *                         times (read-only options "side_stream_overlap": 0 = no answer yet, 1 = side by
+ *                         side, 2 = in turn; "side_stream_probes": probes answered).  The probe is made
+ *                         against the stream of that call;
  *                         1 (TS_MIXED_ONE_KERNEL) = decode items and prefill tiles share the workgroups of one
  *                         persistent launch;  0 (TS_MIXED_SEPARATE) = decode kernel, then prefill kernel
  *   "prefill_resident_workgroups"  co-resident launch: number of resident prefill workgroups.  0 (default) =

@@ -105,6 +105,18 @@ struct ts_ctx {
     // forked from the caller's stream behind the append and joined to it again with these two events.
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    // Does the side stream run next to the caller's stream?  A process has few hardware queues and the runtime
+    // decides which streams share one; two streams on one queue run in turn and the co-resident launch gains
+    // nothing.  The first co-resident call therefore sends a probe ahead: a one-thread kernel on the caller's
+    // stream that waits (bounded: kProbeTicks of the 100 MHz clock) for a flag which a kernel on the side stream
+    // sets, and writes into pinned host memory whether it saw it.  A later call reads the answer (no wait) and,
+    // if the two ran in turn, takes a new side stream and probes again, kProbeTries times at most.
+    int side_state = 0;                // 0 = not probed, 1 = probe in flight, 2 = settled
+    int side_tries = 0;
+    int side_overlap = 0;              // answer of the last finished probe: 0 = none yet, 1 = side by side, 2 = in turn
+    int32_t* h_probe = nullptr;        // pinned: one answer word per try
+    int32_t* h_probe_dev = nullptr;    // the same words as the GPU addresses them
+    std::vector<hipStream_t> parked;   // side streams that ran in turn with the caller's stream
     // Split decode rows are merged by a launch of their own (default) or by whichever item of a row finishes
     // last.  The second form saves a launch but needs a device-scope release in every item and an acquire in the
     // last one; on this GPU the release writes the L2 back, and 8 rows of 1500 tokens took 30 us per pass
@@ -445,6 +457,57 @@ int drain_timed(ts_ctx* c)
     return TS_OK;
 }
 
+constexpr int kProbeTries = 4;
+constexpr long long kProbeTicks = 6000;                   // 60 us of the 100 MHz clock
+constexpr int kProbeFlagWord = 96;                         // words 96 .. 96 + kProbeTries - 1 of the counter block
+
+// Waits until *flag is set or the time is up (every path ends: the loop is bounded in iterations as well).
+__global__ void probe_wait_kernel(const int32_t* flag, int32_t* answer)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const long long t0 = wall_clock64();
+    int seen = 0;
+    for (int i = 0; i < (1 << 16); ++i) {
+        seen = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen || wall_clock64() - t0 > kProbeTicks) break;
+        __builtin_amdgcn_s_sleep(16);
+    }
+    __hip_atomic_store(answer, seen ? 1 : 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__global__ void probe_set_kernel(int32_t* flag)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) __hip_atomic_store(flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Reads a finished probe's answer and sends the next probe if one is due.  Never waits and never fails the call:
+// whatever goes wrong here leaves the side stream as it is.
+void probe_side_stream(ts_ctx* c, hipStream_t st)
+{
+    if (c->side_state == 2 || c->static_call || !c->h_probe) return;
+    if (c->side_state == 1) {
+        const int32_t ans = __atomic_load_n(&c->h_probe[c->side_tries], __ATOMIC_RELAXED);
+        if (ans == 0) return;                              // not there yet
+        c->side_overlap = ans;
+        c->side_tries += 1;
+        if (ans == 1 || c->side_tries >= kProbeTries) { c->side_state = 2; return; }
+        // in turn: another stream.  The old one is kept until the context goes (a stream made right after one was
+        // released was seen to take the released one's queue again).
+        hipStream_t fresh = nullptr;
+        if (hipStreamCreateWithFlags(&fresh, hipStreamNonBlocking) != hipSuccess) { (void)hipGetLastError(); c->side_state = 2; return; }
+        c->parked.push_back(c->side);
+        c->side = fresh;
+        c->side_state = 0;
+    }
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return; }
+    int32_t* flag = c->d_q_ctr + kProbeFlagWord + c->side_tries;
+    hipLaunchKernelGGL(probe_wait_kernel, dim3(1), dim3(64), 0, st, (const int32_t*)flag, c->h_probe_dev + c->side_tries);
+    hipLaunchKernelGGL(probe_set_kernel, dim3(1), dim3(64), 0, c->side, flag);
+    if (hipGetLastError() != hipSuccess) { c->side_state = 2; return; }
+    c->side_state = 1;
+}
+
 // Marks the end of a call's device work on its stream: the call's one event.  Runs on every path that
 // follows a successful upload_plan, error paths included (the upload kernel may still be reading the slot).
 int mark_work_done(ts_ctx* c, hipStream_t st)
@@ -543,6 +606,18 @@ extern "C" int ts_create(const ts_attn_desc* desc, int device, ts_ctx** out)
             hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming | hipEventDisableSystemFence) != hipSuccess ||
             hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming | hipEventDisableSystemFence) != hipSuccess)
             rc = fail(c, TS_ERR_HIP, "side stream / event creation failed");
+        if (rc == TS_OK) {
+            void* dev = nullptr;
+            if (hipHostMalloc((void**)&c->h_probe, 64, hipHostMallocCoherent) == hipSuccess &&
+                hipHostGetDevicePointer(&dev, c->h_probe, 0) == hipSuccess) {
+                memset(c->h_probe, 0, 64);
+                c->h_probe_dev = (int32_t*)dev;
+            } else {
+                (void)hipGetLastError();
+                if (c->h_probe) (void)hipHostFree(c->h_probe);
+                c->h_probe = nullptr;                      // (no probe then: the side stream stays as created)
+            }
+        }
     }
     if (rc == TS_OK) {
         // the allocation-free entry point: this GPU's static scratch, and a staging ring that holds the
@@ -574,6 +649,8 @@ extern "C" int ts_destroy(ts_ctx* c)
     if (c->d_wide_k) (void)hipFree(c->d_wide_k);
     if (c->d_wide_v) (void)hipFree(c->d_wide_v);
     if (c->side) (void)hipStreamDestroy(c->side);
+    for (hipStream_t s : c->parked) (void)hipStreamDestroy(s);
+    if (c->h_probe) (void)hipHostFree(c->h_probe);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     for (HostSlot& s : c->ring) {
@@ -700,6 +777,8 @@ extern "C" int ts_get_option(const ts_ctx* c, const char* name, int64_t* value)
     else if (!strcmp(name, "xcd_count")) *value = c->opt.xcds;
     else if (!strcmp(name, "prefill_widen_pages")) *value = c->opt.widen_pages;
     else if (!strcmp(name, "prefill_resident_workgroups")) *value = c->opt.pf_resident_wgs;
+    else if (!strcmp(name, "side_stream_overlap")) *value = c->side_overlap;
+    else if (!strcmp(name, "side_stream_probes")) *value = c->side_tries;
     else if (!strcmp(name, "prefill_split_min_keys")) *value = c->opt.pf_split_min_keys;
     else if (!strcmp(name, "decode_merge_in_kernel")) *value = c->merge_in_kernel ? 1 : 0;
     else if (!strcmp(name, "validate_block_table")) *value = c->validate_pages ? 1 : 0;
@@ -864,6 +943,7 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
         // this stream holds so far (the append) and which this stream waits for again before the call's end
         // is marked.  The prefill launch comes first so that its workgroups take their places on the CUs.
         // Timed as one unit (TS_K_MIXED): events between the two launches would serialise them.
+        probe_side_stream(c, st);
         e = (hipError_t)timed_launch(c, TS_K_MIXED, true, st, [&] {
             hipError_t r = hipEventRecord(c->ev_fork, st);
             if (r == hipSuccess) r = (hipError_t)launch_prefill_resident(a, stream);

@@ -776,6 +776,41 @@ def test_two_contexts_keep_their_own_options():
     c2.close()
 
 
+def test_side_stream_probe_settles_with_many_contexts_alive():
+    """The co-resident launch needs its side stream to run next to the caller's stream.  Twelve contexts alive
+    at once (so that some side streams share a hardware queue with the caller's stream), five passes each:
+    every context has an answer from its probe after the second pass, ends either side by side or after the
+    most probes it may send, and every pass of every context gives the same bytes (and matches the oracle)."""
+    import paper_2512_03416_amd as ts
+    g = gpu()
+    shape = AttnShape(32, 8, 128, "bf16", "bf16")
+    rng = np.random.default_rng(9)
+    q = [1] * 40 + [700, 150]
+    c = list(rng.integers(200, 3000, size=40)) + [700 + 1300, 150]
+    mk = lambda: make_batch(shape, q, c, seed=73, pool_rule=1.25, value_mult=0.5)
+    b = g.to_dev(mk())
+    ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
+    assert ts.plan_describe(g.make_desc(b), b.q_lens, b.ctx_lens).mixed_mode == 2
+    ctxs = [ts.Context(g.make_desc(b)) for _ in range(12)]
+    first = None
+    for rep in range(5):
+        for i, ctx in enumerate(ctxs):
+            out, gk, gv = g.run_batch(b, ctx=ctx)
+            if first is None:
+                first = out
+                assert same_bytes(gk, rk) and same_bytes(gv, rv)
+                assert float(np.max(np.abs(out - ref))) <= TOL["bf16"]
+            assert np.array_equal(out, first), f"context {i}, pass {rep}"
+            if rep >= 1:
+                assert ctx.get_option("side_stream_probes") >= 1
+    states = [(ctx.get_option("side_stream_overlap"), ctx.get_option("side_stream_probes")) for ctx in ctxs]
+    print(f"[case] side stream probes (answer, probes): {states}", flush=True)
+    for ans, n in states:
+        assert (ans == 1 and 1 <= n <= 4) or (ans == 2 and n == 4)
+    for ctx in ctxs:
+        ctx.close()
+
+
 def test_reserve_then_no_growth_and_kernel_timing_counts():
     """ts_reserve sizes the scratch for the largest batch to come (a pass within it matches the oracle);
     with kernel timing on every pass, ts_kernel_times counts one launch of each kernel the batch
