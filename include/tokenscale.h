@@ -187,6 +187,13 @@ const char *ts_last_error(const ts_ctx *ctx);
  *                         device-scope release/acquire around the partial results; the merge reads the partials
  *                         in item order, so the result does not depend on which item came last).  The second
  *                         form saves a launch and is slower on this GPU (the release writes the L2 back)
+ *   "decode_fused_append"  1 (default) / 0.  A pass that appends, holds decode rows only and is small (at most 64
+ *                         decode items and 32 split rows: its work lists travel as kernel arguments) leaves
+ *                         the append to the decode items: the workgroup that reads a row's last page takes the
+ *                         new token from k_new / v_new, converts it exactly as the append kernels do, and
+ *                         writes its cache entry; the pass has no append launch and no upload of work lists.
+ *                         Such passes are bound by their launches.  Same results and same cache bytes either
+ *                         way.  (Not with validate_block_table.)
  *   "prefill_path"        0 = MFMA tiles where supported, 1 = force the generic row kernel
  *   "decode_prefetch_tiles"  2..4 KV tiles in flight per decode wave
  *   "mixed_mode"          how a batch that holds decode rows and prefill chunks is launched:

@@ -124,17 +124,24 @@ struct DecMerge {                          // LDS image of the non-leading waves
     float l[WAVES - 1][16];
 };
 
+// An item of the device work list, through the scalar cache.
+__device__ __forceinline__ DecItem load_dec_item(const DecItem* p)
+{
+    const int32_t TS_CONSTANT* w = as_constant((const int32_t*)p);
+    return DecItem{w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]};
+}
+
 // One decode item for KV head g, executed by a workgroup of WAVES waves.  All waves must call
 // it; it contains one workgroup barrier, and the caller must place another barrier before mg is
 // reused.
 // MERGE: the code for merging a split row by its last item is compiled in (it is used when a.cmb_ctr is set).
-template <typename KT, int NBUF, int WAVES, int D = 128, bool MERGE = false>
-__device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int g, DecMerge<WAVES, D>& mg)
+// FUSED: the row's new token comes from a.k_new / a.v_new and is written into the cache here (see AttnArgs).
+template <typename KT, int NBUF, int WAVES, int D = 128, bool MERGE = false, bool FUSED = false>
+__device__ __forceinline__ void decode_item(const AttnArgs& a, const DecItem it, int g, DecMerge<WAVES, D>& mg)
 {
     constexpr int KB = D / 32, DB = D / 16;    // 32-dim steps of K Q^T, 16-dim blocks of O^T
-    const int32_t TS_CONSTANT* itp = as_constant((const int32_t*)(a.dec + item_idx));
-    const int it_row = itp[0], it_seq = itp[1], it_keys = itp[2], it_pb = itp[3], it_pe = itp[4], it_part = itp[5];
-    const int it_cmb = MERGE ? itp[6] : -1, it_part_first = MERGE ? itp[7] : -1;
+    const int it_row = it.row, it_seq = it.seq, it_keys = it.n_keys, it_pb = it.page_begin, it_pe = it.page_end, it_part = it.part;
+    const int it_cmb = MERGE ? it.cmb : -1, it_part_first = MERGE ? it.part_first : -1;
     // (readfirstlane tells the compiler the wave index is uniform, which keeps everything derived
     // from it -- the page-id loads above all -- on the scalar unit)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -149,6 +156,34 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
 #pragma unroll
     for (int b = 0; b < DB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_ref = -INFINITY, l = 0.0f;
+
+    // Fused form, e4m3 cache: the conversion of the row's new token (a division and an encoding per element) is
+    // shared out over the whole workgroup, one or two elements per thread, instead of being done by the sixteen
+    // lanes that need the bytes; every thread writes its V byte into the cache, the codes meet in LDS, and D/16
+    // threads write the K chunks.  Only the item that holds the row's last page does this (all its waves do:
+    // the condition is the same for the whole workgroup).
+    [[maybe_unused]] __shared__ __align__(16) uint8_t new_tok[FUSED && sizeof(KT) == 1 ? 2 * D : 16];
+    if constexpr (FUSED && sizeof(KT) == 1) {
+        if (it_pe * kPage >= it_keys) {
+            const int slot = (it_keys - 1) & (kPage - 1);
+            const int64_t tile = (int64_t)as_constant(a.block_table)[(int64_t)it_seq * a.geo.max_pages + ((it_keys - 1) >> 4)] * Hkv + g;
+            uint8_t* kc_w = (uint8_t*)const_cast<void*>(a.k_cache) + tile * (16 * D);
+            uint8_t* vc_w = (uint8_t*)const_cast<void*>(a.v_cache) + tile * (16 * D);
+            const uint16_t* kn = (const uint16_t*)a.k_new + ((int64_t)it_row * Hkv + g) * D;
+            const uint16_t* vn = (const uint16_t*)a.v_new + ((int64_t)it_row * Hkv + g) * D;
+            const float ks = a.k_scale[g], vs = a.v_scale[g];
+            for (int e = threadIdx.x; e < 2 * D; e += 64 * WAVES) {
+                const bool is_v = e >= D;
+                const int dim = is_v ? e - D : e;
+                const uint32_t code = float_to_e4m3_bits(bf16_bits_to_float(is_v ? vn[dim] : kn[dim]) / (is_v ? vs : ks));
+                new_tok[e] = (uint8_t)code;
+                if (is_v) __builtin_nontemporal_store((uint8_t)code, vc_w + dim * 16 + slot);
+            }
+            __syncthreads();
+            if ((int)threadIdx.x < D / 16)
+                store_nt(kc_w + (threadIdx.x * 16 + slot) * 16, *(const uint4*)(new_tok + 16 * threadIdx.x));
+        }
+    }
 
     if (np > 0) {                                                 // wave-uniform
         // Q^T operand: column n is query head g*G + n; columns >= G repeat the group's last head
@@ -176,11 +211,72 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
 #pragma unroll
         for (int j = 0; j < NBUF; ++j) fetch(buf[j]);
 
+        // (the wave's last page is partly filled only if it is the row's last page)
+        const int page_last = it_pb + wave + WAVES * (np - 1);
+        // (fused form: the row's last page always goes through the masked step, which patches in the new token)
+        const bool has_tail = FUSED ? (page_last + 1) * kPage >= it_keys : (page_last + 1) * kPage > it_keys;   // wave-uniform
+        const int np_main = np - (has_tail ? 1 : 0);
+        // Fused form: the new token's K and V in cache form (converted exactly as the append kernels convert
+        // them), asked for now so that the reads are under way during the scan.  K: the lanes of the token's slot
+        // hold its dims in tile order; V: the lanes of the slot's group of four hold one element per dim block.
+        constexpr int KR = sizeof(KT) == 2 ? D / 32 : D / 64;
+        [[maybe_unused]] const int new_slot = (it_keys - 1) & (kPage - 1);
+        [[maybe_unused]] uint4 new_k[KR];
+        [[maybe_unused]] uint32_t new_v[DB];
+        if constexpr (FUSED) {
+            if (has_tail) {
+                const uint16_t* kn = (const uint16_t*)a.k_new + ((int64_t)it_row * Hkv + g) * D;
+                const uint16_t* vn = (const uint16_t*)a.v_new + ((int64_t)it_row * Hkv + g) * D;
+                if constexpr (sizeof(KT) == 2) {
+#pragma unroll
+                    for (int b = 0; b < KR; ++b) new_k[b] = *(const uint4*)(kn + 8 * (4 * b + r));
+#pragma unroll
+                    for (int b = 0; b < DB; ++b) new_v[b] = vn[16 * b + n];
+                } else {
+                    // (converted by the whole workgroup above)
+#pragma unroll
+                    for (int j = 0; j < KR; ++j) new_k[j] = *(const uint4*)(new_tok + 16 * (4 * j + r));
+#pragma unroll
+                    for (int b = 0; b < DB; ++b) new_v[b] = new_tok[D + 16 * b + n];
+                }
+            }
+        }
+
         // One page: S^T, online softmax against the reference maximum, O^T += V^T P^T.  MASKED is the row's last,
         // partly filled page: scores and V of the slots past n_keys are masked (the slots hold whatever was there
         // before).  It runs once per row, after the loop, so that the loop carries no mask arithmetic.
-        auto page_step = [&](const KVTile<KT, D>& t, const int page, auto masked) {
+        auto page_step = [&](const KVTile<KT, D>& t_in, const int page, auto masked) {
             constexpr bool MASKED = decltype(masked)::value;
+            KVTile<KT, D> t = t_in;
+            if constexpr (MASKED && FUSED) {
+                // The row's last page: slot (n_keys - 1) % 16 belongs to the token this pass appends.  Its K and V
+                // (asked for before the scan, already in cache form) replace what the cache held in that slot and,
+                // with a bf16 cache, go from here into the cache (an e4m3 cache got them from the workgroup above).
+                const int64_t tile = (int64_t)bt[WAVES * (np - 1)] * Hkv + g;
+                char* kc_w = (char*)const_cast<void*>(a.k_cache) + tile * (16 * D * (int)sizeof(KT));
+                char* vc_w = (char*)const_cast<void*>(a.v_cache) + tile * (16 * D * (int)sizeof(KT));
+                if (n == new_slot) {
+#pragma unroll
+                    for (int b = 0; b < KR; ++b) {
+                        t.k[b] = new_k[b];
+                        if constexpr (sizeof(KT) == 2) store_nt(kc_w + lane * 16 + b * 1024, new_k[b]);
+                    }
+                }
+                if (r == (new_slot >> 2)) {
+#pragma unroll
+                    for (int b = 0; b < DB; ++b) {
+                        if constexpr (sizeof(KT) == 2) {
+                            const int sh = 16 * (new_slot & 1);
+                            uint32_t& w = (new_slot & 2) ? t.v[b].y : t.v[b].x;
+                            w = (w & ~(0xffffu << sh)) | (new_v[b] << sh);
+                            __builtin_nontemporal_store((uint16_t)new_v[b], (uint16_t*)(vc_w + (16 * b + n) * 32 + new_slot * 2));
+                        } else {
+                            const int sh = 8 * (new_slot & 3);
+                            t.v[b] = (t.v[b] & ~(0xffu << sh)) | (new_v[b] << sh);
+                        }
+                    }
+                }
+            }
             f32x4 s = qk_tile(t, qb);
             float t0 = s[0] * c, t1 = s[1] * c, t2 = s[2] * c, t3 = s[3] * c;
             const int nvalid = it_keys - (page * kPage + 4 * r);   // tokens tok0 .. tok0+3 valid if < nvalid
@@ -215,10 +311,6 @@ __device__ __forceinline__ void decode_item(const AttnArgs& a, int item_idx, int
                 acc[b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(as_s16x4(vv), pv, acc[b], 0, 0, 0);
             }
         };
-        // (the wave's last page is partly filled only if it is the row's last page)
-        const int page_last = it_pb + wave + WAVES * (np - 1);
-        const bool has_tail = (page_last + 1) * kPage > it_keys;      // wave-uniform
-        const int np_main = np - (has_tail ? 1 : 0);
         for (int base = 0; base < np_main; base += NBUF) {
 #pragma unroll
             for (int j = 0; j < NBUF; ++j) {

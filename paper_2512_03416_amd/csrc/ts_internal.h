@@ -207,6 +207,18 @@ struct AttnArgs {
     int32_t* cmb_ctr;
     // split-K partials: o [slot][Hq][D] fp32 (unnormalised), ml [slot][Hq][2] = (max, sum) in log2 units
     float* part_o; float* part_ml;
+    // Small decode-only batches, fused form (k_new != NULL): the wave that reads a row's last page takes the row's
+    // new token from k_new / v_new [T, Hkv, D] instead of the cache and writes its cache entry itself, so the pass
+    // has no append launch.
+    const void* k_new; const void* v_new;
+};
+
+// Work lists short enough to travel as kernel arguments (fused form of small decode-only batches).
+constexpr int kSmallDec = 64, kSmallCmb = 32;
+struct SmallLists {
+    int32_t n_dec, n_cmb, pad0, pad1;
+    DecItem dec[kSmallDec];
+    CmbItem cmb[kSmallCmb];
 };
 
 // Launchers (defined in the .hip files).  All return a hipError_t cast to int.
@@ -214,6 +226,7 @@ int launch_append(const AppendArgs& a, void* stream);
 int launch_rows(const AttnArgs& a, void* stream);
 int launch_decode(const AttnArgs& a, void* stream);
 int launch_combine(const AttnArgs& a, void* stream);
+int launch_decode_fused(const AttnArgs& a, const SmallLists& lists, void* stream);   // decode items + merge of split rows
 // Resident workgroups of the decode / persistent kernel on the current device (0 if unknown).  The
 // caller keeps the answers per context: two contexts may sit on different GPUs.
 int decode_resident_workgroups(int kv_dtype, int nbuf, int head_dim);

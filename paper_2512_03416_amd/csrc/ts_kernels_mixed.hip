@@ -52,7 +52,7 @@ __device__ __forceinline__ void drain_queues(const AttnArgs& a, LDS& sh)
         int t = tid;
         asm volatile("" : "+v"(t));                            // (see prefill_tile)
         if constexpr (WITH_DECODE) {
-            if (kind == 0) decode_item<KT, NBUF, kPfWaves>(a, item, g, sh.mg);
+            if (kind == 0) decode_item<KT, NBUF, kPfWaves>(a, load_dec_item(a.dec + item), g, sh.mg);
             else prefill_tile<PKT, WIDE, 128>(a, item, g, sh.lds, t);
         } else {
             prefill_tile<PKT, WIDE, 128>(a, item, g, sh, t);

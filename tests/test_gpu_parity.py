@@ -80,6 +80,55 @@ def test_decode_rows(kv, heads, head_dim):
 
 
 @pytest.mark.parametrize("head_dim", [128, 64])
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+@pytest.mark.parametrize("heads", [(8, 2), (4, 4), (32, 4)], ids=lambda h: f"{h[0]}q{h[1]}kv")
+def test_decode_items_append_their_rows_tokens_or_the_append_kernel_does(kv, heads, head_dim):
+    """A decode-only pass with the append fused into the decode items (the wave that reads a row's last page
+    patches in the new token and writes its cache entry) and with the append launch in front: same cache bytes
+    as the oracle, outputs within the bar and bit-identical between the two forms, whole and split rows; new
+    tokens in the first slot of a fresh page, in the last slot of a page, and anywhere in between."""
+    shape = AttnShape(heads[0], heads[1], head_dim, "bf16", kv)
+    ctxs = DEC_CTX + [32, 48, 49, 4096, 4097]
+    mk = lambda: make_batch(shape, [1] * len(ctxs), ctxs, seed=33, pool_rule=1.3, value_mult=0.5 if kv == "bf16" else 1.0)
+    ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
+    g = gpu()
+    for split in (0, 9):
+        outs = []
+        for fused in (1, 0):
+            print(f"[case] decode rows kv={kv} heads={heads} D={head_dim} fused append={fused} split={split}", flush=True)
+            out, gk, gv = g.run_batch(mk(), options={"decode_fused_append": fused, "decode_split_pages": split})
+            assert same_bytes(gk, rk) and same_bytes(gv, rv)
+            assert np.all(np.isfinite(out))
+            assert float(np.max(np.abs(out - ref))) <= TOL[kv]
+            outs.append(out)
+        assert np.array_equal(outs[0], outs[1])
+
+
+def test_fused_append_converts_every_bf16_pattern_like_the_append_kernel():
+    """All 65 536 bf16 bit patterns as the new K and V of 128 decode rows (4 kv heads = 4 scales) through the fused
+    form: the e4m3 cache bytes equal the oracle's (NaNs, infinities, values beyond the range, -0, denormals)."""
+    import paper_2512_03416_amd as ts
+    shape = AttnShape(4, 4, 128, "bf16", "fp8")
+    n = 65536 // (4 * 128)
+    rng = np.random.default_rng(34)
+    ctxs = [int(x) for x in rng.integers(1, 70, size=n)]
+    b = make_batch(shape, [1] * n, ctxs, seed=52)
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    allv = bits.view(torch.bfloat16).view(n, 4, 128)
+    g = gpu()
+    for rot in range(2):
+        b.k_new = torch.roll(allv, rot, dims=1).contiguous()
+        b.v_new = torch.roll(allv, rot + 1, dims=1).contiguous()
+        b.k_scale = torch.tensor([1.0, 0.0078125, 0.0123, 3.7])
+        b.v_scale = torch.tensor([1.0 / 448.0, 2.5, 0.3, 1e-3])
+        print(f"[case] fused append, every bf16 pattern, rotation {rot}", flush=True)
+        _, rk, rv = oracle.run_batch(W.to_cpu(b))
+        _, gk, gv = g.run_batch(b, options={"decode_fused_append": 1})
+        assert same_bytes(gk, rk) and same_bytes(gv, rv)
+        W.to_cpu(b)
+
+
+@pytest.mark.parametrize("head_dim", [128, 64])
 @pytest.mark.parametrize("split", [8, 9, 64, 128])
 @pytest.mark.parametrize("nbuf", [2, 3, 4])
 def test_decode_split_and_prefetch_variants(split, nbuf, head_dim):
