@@ -200,8 +200,9 @@ const char *ts_last_error(const ts_ctx *ctx);
  *                         2 (default, TS_MIXED_CORESIDENT) = the prefill tiles run in resident workgroups,
  *                         at most one per CU, that leave room on their CU for one decode workgroup, and the
  *                         decode items run next to them as a grid of their own on an internal side stream
- *                         (forked from and joined to the caller's stream with events).  A batch with hardly
- *                         any decode pages takes mode 1 by itself, one with hardly any prefill work mode 0.
+ *                         (forked from and joined to the caller's stream with events).  A batch in which
+ *                         either class is short (estimated below 20 us) takes mode 0 by itself: the fork
+ *                         and join would cost more than running side by side hides.
  *                         The side stream is an ordinary stream of the process: where the runtime maps it
  *                         to the hardware queue that also serves the caller's stream (a process has 4 by
  *                         default), the two launches run in turn -- same results, no overlap.  The first

@@ -121,11 +121,13 @@ constexpr double kPfFlopPerUs = 1.25e9;
 // 256, r = 0.8: 160-192, r = 1.0: 224, r >= 1.3: all.
 constexpr double kPfShare0 = 0.25;
 constexpr double kPfShare1 = 0.6;
-// Estimated time of the tiles below which a mixed batch is launched class by class: the fork and join of the
-// co-resident launch cost more than so short a prefill launch behind the decode kernel (128 decode rows next to a
-// chunk of 128 / 896 tokens without prefix: 0.410 / 0.425 ms against 0.423 / 0.432 ms; a chunk of 384 tokens over
-// a prefix of 4096, estimated at 22 us: 0.450 against 0.429 ms).
-constexpr double kPfSeparateBelowUs = 8.0;
+// A mixed batch is launched class by class when either class is estimated below this many microseconds: running
+// side by side hides about 40 % of the shorter class, and the fork and join of the co-resident launch cost
+// 10-15 us.  Measured: 128 decode rows (395 us) next to a chunk of 128 / 896 tokens without prefix (estimates
+// 0.1 / 5 us): 0.410 / 0.425 ms class by class against 0.423 / 0.432 ms; next to 384 tokens over a prefix of 4096
+// (22 us): 0.450 against 0.429 ms; 16 decode rows of 2500 tokens (26 us) next to 256 tokens over 4096 (14 us):
+// 85 against 89 us; 8 rows of 1500 tokens (8 us) next to 1024 tokens over 2048 (34 us): 85 against 100 us.
+constexpr double kCoresidentMinUs = 20.0;
 
 static int32_t auto_split_pages(int64_t decode_tiles, int64_t decode_pages, int64_t n_rows, int Hkv,
                                 int32_t wg_slots, int32_t n_cu, bool filled_by_prefill, int32_t pf_wgs)
@@ -295,9 +297,8 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
     if (mfma_tiles)
         for (int s = 0; s < num_seqs; ++s)
             if (p.seqs[s].q_len > 1) tile_heads += (int64_t)((p.seqs[s].q_len + TT - 1) / TT) * Hkv;
-    // How a batch with both kinds of rows is launched.  Co-resident by default; the fork and join of the
-    // two launches cost a few microseconds, so a batch whose tiles cannot occupy half of the CUs, or that has
-    // hardly any decode pages to hide behind them, goes through the single persistent kernel instead.
+    // How a batch with both kinds of rows is launched.  Co-resident by default; class by class when either class
+    // is too short for the overlap to pay for the fork and join (kCoresidentMinUs).
     int mixed_mode = opt.mixed_mode;
     double t_pf = 0, t_dec = 0;                            // microseconds each kind would take alone
     if (mixed_mode == TS_MIXED_CORESIDENT) {
@@ -309,10 +310,7 @@ void build_plan(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* ctx
         t_pf = flop / kPfFlopPerUs;
         t_dec = (double)decode_tiles * 2.0 * kPage * d.head_dim * (d.kv_dtype == TS_FP8_E4M3 ? 1 : 2) / kDecBytePerUs;
         // (a stated number of resident workgroups asks for this launch form whatever the batch)
-        if (opt.pf_resident_wgs <= 0) {
-            if (decode_tiles < 4 * (int64_t)opt.n_cu) mixed_mode = TS_MIXED_ONE_KERNEL;
-            else if (t_pf < kPfSeparateBelowUs) mixed_mode = TS_MIXED_SEPARATE;
-        }
+        if (opt.pf_resident_wgs <= 0 && std::min(t_pf, t_dec) < kCoresidentMinUs) mixed_mode = TS_MIXED_SEPARATE;
     }
     if (!mfma || p.info.decode_tokens == 0 || tile_heads == 0) mixed_mode = TS_MIXED_SEPARATE;
     if (!mfma_dec) { decode_tiles = 0; decode_pages = 0; }

@@ -271,9 +271,9 @@ def test_mixed_batch_persistent_and_separate_launches(persistent, kv):
     the side stream), one persistent kernel, one launch per class."""
     import paper_2512_03416_amd as ts
     shape = AttnShape(32, 8, 128, "bf16", kv)
-    q = [1] * 40 + [300, 129, 1000] + [1] * 17
+    q = [1] * 40 + [300, 129, 1400] + [1] * 17
     rng = np.random.default_rng(5)
-    c = list(rng.integers(1, 3000, size=40)) + [300 + 77, 129, 1000 + 640] + list(rng.integers(1, 600, size=17))
+    c = list(rng.integers(1, 4000, size=40)) + [300 + 77, 129, 1400 + 640] + list(rng.integers(1, 600, size=17))
     b = make_batch(shape, q, c, seed=44, pool_rule=1.25, value_mult=0.5)
     g = gpu()
     assert ts.plan_describe(g.make_desc(b), b.q_lens, b.ctx_lens).mixed_mode == 2      # large enough for the default
@@ -328,9 +328,9 @@ def test_fp8_prefill_widened_pages_and_in_tile_widening_agree(mode):
     and each other bit for bit (the conversion is exact), in every launch mode, with ragged page tails."""
     import paper_2512_03416_amd as ts
     shape = AttnShape(32, 8, 128, "bf16", "fp8")
-    q = [1] * 30 + [333, 1000, 64, 2] + [1] * 9
+    q = [1] * 60 + [333, 1800, 64, 2] + [1] * 9
     rng = np.random.default_rng(6)
-    c = list(rng.integers(1, 2500, size=30)) + [333 + 1111, 1000, 64 + 15, 2 + 640] + list(rng.integers(1, 900, size=9))
+    c = list(rng.integers(1, 4000, size=60)) + [333 + 1111, 1800, 64 + 15, 2 + 640] + list(rng.integers(1, 900, size=9))
     mk = lambda: make_batch(shape, q, c, seed=45, pool_rule=1.25, value_mult=1.0)
     g = gpu()
     b = mk()
@@ -338,7 +338,7 @@ def test_fp8_prefill_widened_pages_and_in_tile_widening_agree(mode):
     chunk_pages = sum(-(-cl // 16) for ql, cl in zip(q, c) if ql > 1)
     assert info.widened_pages == chunk_pages and info.mixed_mode == 2
     wide = binding_export(g.make_desc(b), b, "widen")
-    assert len(wide) == chunk_pages and sorted(set(wide[:, 0].tolist())) == [30, 31, 32, 33]
+    assert len(wide) == chunk_pages and sorted(set(wide[:, 0].tolist())) == [60, 61, 62, 63]
     ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))
     outs = []
     for pages in (16384, 0, chunk_pages - 1):
@@ -834,8 +834,8 @@ def test_side_stream_probe_settles_with_many_contexts_alive():
     g = gpu()
     shape = AttnShape(32, 8, 128, "bf16", "bf16")
     rng = np.random.default_rng(9)
-    q = [1] * 40 + [700, 150]
-    c = list(rng.integers(200, 3000, size=40)) + [700 + 1300, 150]
+    q = [1] * 40 + [1000, 150]
+    c = list(rng.integers(200, 3000, size=40)) + [1000 + 1500, 150]
     mk = lambda: make_batch(shape, q, c, seed=73, pool_rule=1.25, value_mult=0.5)
     b = g.to_dev(mk())
     ref, rk, rv = oracle.run_batch(W.to_cpu(mk()))

@@ -168,8 +168,7 @@ def test_plan_routes_fp32_to_generic_rows_and_head_dim_64_to_the_matrix_cores():
 def test_plan_sizes_the_co_resident_launch_from_the_two_costs():
     """A mixed batch is launched co-resident with as many resident prefill workgroups as the ratio of the two
     classes' estimated times asks for (all CUs when the tiles dominate, fewer -- in multiples of the die count --
-    when the decode scan outlasts them); a batch with hardly any prefill work goes class by class, one with
-    hardly any decode pages through the one persistent kernel."""
+    when the decode scan outlasts them); a batch in which either class is short goes class by class."""
     rng = np.random.default_rng(3)
     dec = rng.integers(1024, 8193, 128).tolist()
     d = D(max_pages_per_seq=2048, num_pages=200000)
@@ -187,8 +186,8 @@ def test_plan_sizes_the_co_resident_launch_from_the_two_costs():
     small = plan([(384, 4096)])
     assert small.mixed_mode == 2 and 8 <= small.prefill_workgroups <= 96
     assert plan([(128, 0)]).mixed_mode == 0 and plan([(128, 0)]).prefill_workgroups == 0
-    few = ts.plan_describe(d, [1, 1, 2048], [100, 200, 2048])
-    assert few.mixed_mode == 1 and few.prefill_workgroups == 0
+    few = ts.plan_describe(d, [1, 1, 2048], [100, 200, 2048])                        # hardly any decode pages
+    assert few.mixed_mode == 0 and few.prefill_workgroups == 0
     # monotone in the prefill work
     sizes = [plan([(n, 4096)]).prefill_workgroups for n in (512, 1024, 2048, 4096, 8192)]
     assert sizes == sorted(sizes) and sizes[-1] == 256
@@ -295,12 +294,14 @@ def test_plan_invariants_on_seeded_random_batches(seed):
     assert sorted(live) == sorted((t, g) for t in range(len(pf)) for g in range(hkv))      # (every part is a work item)
 
     queue, qoff = exp("queue"), exp("qoff")[:, 0]
-    if len(dec) and len(pf) and mode != 0:                    # a mixed batch has per-die queues
+    if len(dec) and len(pf) and mode == 1:
+        assert len(queue)                                     # (asked for by name: no other launch form is chosen)
+    if len(dec) and len(pf) and mode != 0 and len(queue):     # a mixed batch has per-die queues, unless the planner
         assert len(qoff) == 9 and qoff[0] == 0 and qoff[-1] == len(queue) and np.all(np.diff(qoff) >= 0)
         d_entries = sorted((int(i), int(g)) for k, i, g, _ in queue if k == 0)
         p_entries = sorted((int(i), int(g)) for k, i, g, _ in queue if k == 1)
-        # one persistent kernel: both kinds are queued; co-resident launch: the tiles only (a batch too small
-        # for the co-resident launch falls back to the one kernel)
+        # launches it class by class (either class too short for the co-resident launch to pay).
+        # One persistent kernel: both kinds are queued; co-resident launch: the tiles only
         assert d_entries in ([], sorted((i, g) for i in range(len(dec)) for g in range(hkv)))
         assert mode != 1 or d_entries
         assert p_entries == sorted((t, g) for t in range(len(pf)) for g in range(hkv))
