@@ -222,7 +222,7 @@ const char *ts_last_error(const ts_ctx *ctx);
  *                         fixes the number (capped at the CU count) and keeps mode 2 for every mixed batch
  *   "prefill_split_min_keys"  a batch whose prefill tiles cannot give every CU a workgroup (a short chunk over a
  *                         long prefix) has its tiles cut along the keys, below their first query position, into
- *                         parts of at least this many keys (multiple of 64, default 1024; 0 = never); the
+ *                         parts of at least this many keys (multiple of 64, default 512; 0 = never); the
  *                         parts' partial results are merged in part order by a small launch
  *   "prefill_widen_pages" fp8 caches: every tile of a prefill chunk reads the chunk's whole prefix, so the pages
  *                         of the chunks' sequences are widened from e4m3 to bf16 once per pass, into scratch of

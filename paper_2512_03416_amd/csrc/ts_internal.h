@@ -126,7 +126,7 @@ struct PlanOptions {
     bool generic_only = false;  // every row through the generic kernel
     bool prefill_generic = false;
     int32_t tile_tokens = 0;    // query tokens per prefill tile
-    int32_t pf_split_min_keys = 1024;   // shortest key range of a cut prefill tile (multiple of 64; 0 = never cut)
+    int32_t pf_split_min_keys = 512;    // shortest key range of a cut prefill tile (multiple of 64; 0 = never cut)
     int32_t pf_resident_wgs = 0; // co-resident launch: resident prefill workgroups (0 = from the batch's two costs)
     int64_t widen_pages = 16384; // fp8 caches: most pages of prefill sequences that are widened to bf16 per pass (0 = never)
 };
