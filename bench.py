@@ -312,6 +312,17 @@ def run_workload(name, args, with_cpu: bool):
     vel = ctx.token_velocity(sync=True)
     ms_step = elapsed * 1e3 / args.steps
     T = batch.total_q
+    # spread of single passes: events on the caller's stream around each pass (a pass begins and ends there, the
+    # co-resident launch included), outside the timed region
+    n_spread = min(args.steps, 50)
+    marks = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_spread)]
+    for a, b in marks:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    per_pass = sorted(a.elapsed_time(b) for a, b in marks)
+    spread = {f"p{q}": round(per_pass[min(len(per_pass) - 1, int(q / 100 * len(per_pass)))], 5) for q in (10, 50, 90)}
     log(f"[bench] {batch.name}: {ms_step:.4f} ms/step with kernel events on every {args.time_every}. step, "
         f"{ms_plain:.4f} ms/step without; kernels: " +
         ", ".join(f"{k} {v[1] * 1e3:.1f} us x{v[0]}" for k, v in ktimes.items() if v[0]))
@@ -329,6 +340,7 @@ def run_workload(name, args, with_cpu: bool):
                    "decode_split_pages": int(info.split_pages)},
         "roofline": roof,
         "ms_per_step_without_kernel_events": ms_plain,
+        "ms_per_pass_events": spread,
         "kernels_us": {k: round(v[1] * 1e3, 2) for k, v in ktimes.items() if v[0]},
     }
     if "mixed" in ktimes and ktimes["mixed"][0] and not args.no_persistent:
@@ -446,7 +458,7 @@ def main():
             r = run_workload(w, args, with_cpu=False)
             result["extra"][r["config"]["workload"]] = dict(
                 tokens_per_s=r["value"], ms_per_step=r["ms_per_step"], query_tokens=r["config"]["query_tokens"],
-                kernels_us=r["kernels_us"], roofline=r["roofline"])
+                ms_per_pass_events=r["ms_per_pass_events"], kernels_us=r["kernels_us"], roofline=r["roofline"])
     if args.calibrate:
         result["calibration"] = calibrate()
         log(f"[bench] calibration: {result['calibration']}")
