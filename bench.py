@@ -356,7 +356,7 @@ def run_workload(name, args, with_cpu: bool):
         roof["ms_per_step_separate_launches"] = dt_sep * 1e3 / n_sep
         log(f"[bench] {batch.name}, one launch per class: {dt_sep * 1e3 / n_sep:.4f} ms/step; kernels: " +
             ", ".join(f"{k} {v[1] * 1e3:.1f} us x{v[0]}" for k, v in kt_sep.items() if v[0]))
-        step()                                               # `out` as the persistent launch writes it
+        step()                                               # `out` as the default launch form writes it
         torch.cuda.synchronize()
     if with_cpu:
         out_host = out.double().cpu().numpy()
@@ -425,7 +425,7 @@ def main():
     ap.add_argument("--prefetch-tiles", type=int, default=0)
     ap.add_argument("--xcd-count", type=int, default=0)
     ap.add_argument("--no-persistent", action="store_true",
-                    help="mixed batches: decode kernel then prefill kernel instead of the persistent launch")
+                    help="mixed batches: one launch per class instead of the co-resident launch")
     ap.add_argument("--time-every", type=int, default=4,
                     help="record HIP events around the kernels of every N-th step of the timed region")
     args = ap.parse_args()

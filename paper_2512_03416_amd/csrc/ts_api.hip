@@ -975,7 +975,7 @@ int mixed_pass(ts_ctx* c, void* stream, const void* q, const void* k_new, const 
         });
         if (e != hipSuccess) return hip_fail(c, e, "co-resident launch");
     } else if (a.n_queue > 0) {
-        // mixed batch: decode items and prefill tiles share the CUs in one persistent launch
+        // mixed batch, by option: decode items and prefill tiles share the workgroups of one persistent launch
         e = (hipError_t)timed_launch(c, TS_K_MIXED, true, st, [&] { return launch_mixed(a, stream); });
         if (e != hipSuccess) return hip_fail(c, e, "mixed launch");
         e = (hipError_t)timed_launch(c, TS_K_COMBINE, a.n_cmb > 0 && !a.cmb_ctr, st, [&] { return a.cmb_ctr ? 0 : launch_combine(a, stream); });

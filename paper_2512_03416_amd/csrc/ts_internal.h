@@ -131,8 +131,8 @@ struct PlanOptions {
     int64_t widen_pages = 16384; // fp8 caches: most pages of prefill sequences that are widened to bf16 per pass (0 = never)
 };
 
-// Which kernels serve a descriptor: the matrix-core tile kernels for prefill chunks (head dim 128; this also
-// stands for the page-wise append, the persistent launches and their scratch), the matrix-core decode items
+// Which kernels serve a descriptor: the full matrix-core set (head dim 128: tile kernels, resident launches of
+// mixed batches and their scratch), the matrix-core decode items (head dim 64 or 128), the matrix-core tiles
 // (head dim 64 or 128).  Everything else goes through the generic row kernel.
 bool desc_uses_mfma(const ts_attn_desc& d);
 bool desc_uses_mfma_decode(const ts_attn_desc& d);

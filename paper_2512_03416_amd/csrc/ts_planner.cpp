@@ -106,10 +106,10 @@ int validate_batch(const ts_attn_desc& d, const int32_t* q_lens, const int32_t* 
 // items than that only add start-up, merge and combine work; 8 rows of 1500 tokens take 22 us per
 // pass in pieces of 32 pages against 26 us in pieces of 8, next to a 256-token chunk 50 against 64 us;
 // for 16-48 rows every choice between 32 and 128 pages lies within 10 % of the best.)
-// In a mixed batch whose prefill tiles fill the chip on their own (persistent launch: one resident
-// workgroup per CU, a third of the stand-alone decode slots), (b) does not apply and the fair share
-// in (a) is that of a resident workgroup: measured on the burst configuration, 706 -> 692 us and no
-// combine launch.
+// In a mixed batch launched with resident workgroups (co-resident launch or one persistent kernel: a CU that
+// holds a resident workgroup has room for one decode workgroup, a third of the stand-alone slots), (b) does not
+// apply and the fair share in (a) is that of the slots actually there: measured on the burst configuration,
+// 706 -> 692 us and no combine launch.
 // Rates the two kinds of work reach on their own (decode scan: bytes per microsecond; prefill tiles: flop per
 // microsecond, all CUs).
 constexpr double kDecBytePerUs = 6.2e6;
