@@ -69,7 +69,7 @@ DEC_CTX = [1, 2, 15, 16, 17, 31, 33, 64, 100, 255, 256, 257, 600, 1000, 2049, 30
 
 @pytest.mark.parametrize("head_dim", [128, 64])
 @pytest.mark.parametrize("kv", ["bf16", "fp8"])
-@pytest.mark.parametrize("heads", [(8, 2), (4, 4), (16, 2), (32, 2), (6, 2)], ids=lambda h: f"{h[0]}q{h[1]}kv")
+@pytest.mark.parametrize("heads", [(8, 2), (4, 4), (16, 2), (32, 2), (6, 2), (10, 2), (7, 1)], ids=lambda h: f"{h[0]}q{h[1]}kv")
 def test_decode_rows(kv, heads, head_dim):
     import paper_2512_03416_amd as ts
     shape = AttnShape(heads[0], heads[1], head_dim, "bf16", kv)
@@ -209,7 +209,7 @@ def test_decode_large_scores_and_shifting_maximum():
 
 @pytest.mark.parametrize("head_dim", [128, 64])
 @pytest.mark.parametrize("kv", ["bf16", "fp8"])
-@pytest.mark.parametrize("heads", [(8, 2), (4, 4), (16, 2), (32, 2), (6, 2)], ids=lambda h: f"{h[0]}q{h[1]}kv")
+@pytest.mark.parametrize("heads", [(8, 2), (4, 4), (16, 2), (32, 2), (6, 2), (10, 2), (7, 1)], ids=lambda h: f"{h[0]}q{h[1]}kv")
 def test_prefill_chunks(kv, heads, head_dim):
     import paper_2512_03416_amd as ts
     shape = AttnShape(heads[0], heads[1], head_dim, "bf16", kv)
